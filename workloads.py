@@ -1,0 +1,220 @@
+"""Seeded synthetic inputs for selected-block attention (shared by the oracle tests and the HIP tests).
+
+This module holds no attention arithmetic: it only draws tensors and block-index tables.  Both the CPU
+oracle and the HIP library are fed from here so that they see bit-identical bf16 inputs.
+
+Shapes follow the paper's kernel grid (d = 128, B_K = 64, T = 16, Llama/Qwen head counts; Sec. 4.1 and
+App. "Evaluations for Ultra Long Sequence Lengths").  The paper does not say how its selection indices were
+drawn, so each workload states its own recipe: forced blocks (attention sink = block 0, App. E "Attention
+Sink Optimizations"; the current block; optionally the previous block), a number of picks biased to the most
+recent blocks, and the rest uniform without replacement over the remaining earlier blocks.  Rows are left in
+generation order (forced, local, uniform) and padded with -1.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+BLOCK = 64
+HEAD_DIM = 128
+
+
+# ----------------------------------------------------------------------------- bf16 plumbing
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (round-to-nearest-even); returns the 16-bit patterns as uint16."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns exactly to float32."""
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns exactly to float64."""
+    return bf16_bits_to_f32(bits).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------- workload description
+@dataclass
+class Workload:
+    name: str
+    seqlens: List[int]
+    hq: int
+    hkv: int
+    topk: int
+    causal: bool = True
+    sink: bool = False            # block 0 forced into every row
+    recent: int = 1               # number of forced most-recent blocks (1 = current block only)
+    local_picks: int = 0          # picks drawn from the `local_window` blocks before the forced recent ones
+    local_window: int = 8
+    seed: int = 0
+    d: int = HEAD_DIM
+    block: int = BLOCK
+    # filled by realise()
+    cu_seqlens: Optional[np.ndarray] = None
+    idx: Optional[np.ndarray] = None
+    q: Optional[np.ndarray] = None
+    k: Optional[np.ndarray] = None
+    v: Optional[np.ndarray] = None
+    do: Optional[np.ndarray] = None
+    extra: dict = field(default_factory=dict)
+
+    @property
+    def total_tokens(self) -> int:
+        return int(sum(self.seqlens))
+
+    @property
+    def g(self) -> int:
+        return self.hq // self.hkv
+
+
+def _floyd_subsets(rng: np.random.Generator, n: np.ndarray, m: int) -> np.ndarray:
+    """Uniform random subsets without replacement, one per row (Floyd's algorithm, vectorised over rows).
+
+    Row r receives min(m, n[r]) distinct integers from [0, n[r]); unused columns hold -1.
+    """
+    rows = n.shape[0]
+    out = np.full((rows, max(m, 1)), -1, dtype=np.int64)
+    if m == 0:
+        return out[:, :0]
+    n = n.astype(np.int64)
+    take = np.minimum(n, m)
+    for i in range(m):
+        active = i < take
+        jmax = n - take + i                      # candidate range is [0, jmax]
+        u = rng.random(rows)
+        r = np.minimum((u * (jmax + 1)).astype(np.int64), jmax)
+        if i > 0:
+            clash = (out[:, :i] == r[:, None]).any(axis=1)
+            r = np.where(clash, jmax, r)
+        out[:, i] = np.where(active, r, -1)
+    return out
+
+
+def draw_block_indices(rng: np.random.Generator, seqlens: Sequence[int], hkv: int, topk: int, *, sink: bool,
+                       recent: int, local_picks: int, local_window: int, block: int = BLOCK) -> np.ndarray:
+    """int32 [total_tokens, hkv, topk] of sequence-local block ids, -1 padded; selections independent per
+    (token, kv head)."""
+    per_seq = []
+    for L in seqlens:
+        cur = (np.arange(L, dtype=np.int64) // block)                      # current block of each token
+        cur = np.repeat(cur[:, None], hkv, axis=1).reshape(-1)              # rows = (token, kv head)
+        rows = cur.shape[0]
+        cols = []
+        if sink:
+            cols.append(np.zeros(rows, dtype=np.int64))
+        for r in range(recent):
+            c = cur - r
+            c = np.where(c >= 0, c, -1)
+            if sink:
+                c = np.where(c == 0, -1, c)                                 # already forced as the sink
+            cols.append(c)
+        lo = 1 if sink else 0
+        hi = np.maximum(cur - (recent - 1), lo)                            # earlier pool is [lo, hi)
+        n_forced = len(cols)
+        n_free = topk - n_forced
+        assert n_free >= 0
+        n_local = min(local_picks, n_free)
+        n_unif = n_free - n_local
+        if n_local > 0:
+            llo = np.maximum(hi - local_window, lo)
+            picks = _floyd_subsets(rng, hi - llo, n_local)
+            cols.extend(list(np.where(picks >= 0, picks + llo[:, None], -1).T))
+            uhi = llo
+        else:
+            uhi = hi
+        if n_unif > 0:
+            picks = _floyd_subsets(rng, uhi - lo, n_unif)
+            cols.extend(list(np.where(picks >= 0, picks + lo, -1).T))
+        table = np.stack(cols, axis=1)                                      # [rows, topk]
+        # compact the valid ids to the front, keeping generation order; pad the tail with -1
+        order = np.argsort(table < 0, axis=1, kind="stable")
+        table = np.take_along_axis(table, order, axis=1)
+        per_seq.append(table.reshape(L, hkv, topk))
+    return np.concatenate(per_seq, axis=0).astype(np.int32)
+
+
+def realise(w: Workload, *, tensors: bool = True) -> Workload:
+    """Draw the index table and (optionally) the bf16 Q/K/V/dO tensors of a workload from its seed."""
+    rng = np.random.default_rng(w.seed)
+    T = w.total_tokens
+    w.cu_seqlens = np.concatenate([[0], np.cumsum(w.seqlens)]).astype(np.int32)
+    w.idx = draw_block_indices(rng, w.seqlens, w.hkv, w.topk, sink=w.sink, recent=w.recent,
+                               local_picks=w.local_picks, local_window=w.local_window, block=w.block)
+    if tensors:
+        def draw(heads):
+            return f32_to_bf16_bits(rng.standard_normal((T, heads, w.d), dtype=np.float32))
+        w.q = draw(w.hq)
+        w.k = draw(w.hkv)
+        w.v = draw(w.hkv)
+        w.do = draw(w.hq)
+    return w
+
+
+# ----------------------------------------------------------------------------- named workloads
+def varlen_lengths(seed: int, nseq: int = 8, lo: int = 4096, hi: int = 32768) -> List[int]:
+    rng = np.random.default_rng(seed)
+    return [int(x) for x in rng.integers(lo, hi + 1, size=nseq)]
+
+
+def named(name: str) -> Workload:
+    """The benchmark configurations: 'tiny', 'llama8b_32k', 'headline', 'qwen_g7', 'varlen_g1', 'llama70b_128k'."""
+    if name == "tiny":            # config 1
+        return Workload(name, [1024], hq=4, hkv=1, topk=8, seed=1001)
+    if name == "llama8b_32k":     # config 2
+        return Workload(name, [32768], hq=32, hkv=8, topk=16, sink=True, seed=1002)
+    if name == "headline":        # the metric's shape: config 2's heads at N = 64k, g = 4
+        return Workload(name, [65536], hq=32, hkv=8, topk=16, sink=True, seed=1000)
+    if name == "qwen_g7":         # config 3
+        return Workload(name, [65536], hq=28, hkv=4, topk=16, sink=True, local_picks=7, local_window=8,
+                        seed=1003)
+    if name == "varlen_g1":       # config 4
+        return Workload(name, varlen_lengths(1004), hq=16, hkv=16, topk=16, seed=1004)
+    if name == "llama70b_128k":   # config 5
+        return Workload(name, [131072], hq=64, hkv=8, topk=16, sink=True, recent=2, seed=1005)
+    raise KeyError(name)
+
+
+NAMES = ["tiny", "llama8b_32k", "headline", "qwen_g7", "varlen_g1", "llama70b_128k"]
+
+
+def small(name: str) -> Workload:
+    """Scaled-down cases for element-wise parity: same recipes, sizes the oracle finishes in seconds.
+    Lengths are not multiples of 64 so that tiles have ragged tails."""
+    if name == "g4":
+        return Workload(name, [2000], hq=8, hkv=2, topk=16, sink=True, seed=11)
+    if name == "g7":
+        return Workload(name, [1500], hq=7, hkv=1, topk=16, sink=True, local_picks=7, seed=12)
+    if name == "g1_varlen":
+        return Workload(name, [700, 64, 1, 333, 1029], hq=3, hkv=3, topk=16, seed=13)
+    if name == "g8":
+        return Workload(name, [1800], hq=8, hkv=1, topk=16, sink=True, recent=2, seed=14)
+    if name == "g2_noncausal":
+        return Workload(name, [900, 450], hq=4, hkv=2, topk=8, causal=False, seed=15)
+    if name == "g4_k32":
+        return Workload(name, [2500], hq=4, hkv=1, topk=32, sink=True, seed=16)
+    if name == "g3_k1":
+        return Workload(name, [777], hq=3, hkv=1, topk=1, seed=17)
+    raise KeyError(name)
+
+
+SMALL_NAMES = ["g4", "g7", "g1_varlen", "g8", "g2_noncausal", "g4_k32", "g3_k1"]
+
+
+def draw_adversarial_indices(rng: np.random.Generator, seqlens: Sequence[int], hkv: int, topk: int,
+                             block: int = BLOCK) -> np.ndarray:
+    """Index rows that exercise the drop rules: ids anywhere in [-2, b_s + 2) (future blocks, out-of-range
+    ids, padding in the middle of a row) with repeats."""
+    per_seq = []
+    for L in seqlens:
+        b = -(-L // block)
+        tab = rng.integers(-2, b + 2, size=(L, hkv, topk))
+        dup = rng.random((L, hkv, topk)) < 0.25
+        tab = np.where(dup, np.roll(tab, 1, axis=2), tab)
+        per_seq.append(tab)
+    return np.concatenate(per_seq, axis=0).astype(np.int32)
