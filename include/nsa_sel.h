@@ -1,0 +1,96 @@
+/*
+ * nsa_sel.h — C ABI of the MI355X (gfx950) selected-block attention library.
+ *
+ * The operation is the `sel` branch of Native Sparse Attention as stated in the FSA paper (arXiv 2508.18224),
+ * Sec. 2.2 Eq. (2): every query token attends only to the keys/values of its own T selected KV blocks of
+ * B_K = 64 contiguous tokens, shared by the g = hq/hkv query heads of a GQA group.  The library groups the
+ * queries per selected KV block (the paper's KV-outer loop order, Sec. 3.1-3.2) so that the QK^T and PV
+ * products are dense MFMA tiles with no padding of small query tiles.
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers; `shape` and the size_t outputs are HOST pointers.
+ *   - The library never allocates, frees or synchronises: every buffer, including workspaces, belongs to
+ *     the caller, and all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream).
+ *   - Layouts are token-major and contiguous: Q, O, dO, dQ are bf16 [total_tokens, hq, d]; K, V, dK, dV are
+ *     bf16 [total_tokens, hkv, d]; LSE is fp32 [total_tokens, hq] (natural log); query head h uses KV head
+ *     h / g (contiguous groups).
+ *   - idx is int32 [total_tokens, hkv, topk]: block ids LOCAL to the token's sequence.  Ids that are negative
+ *     (padding), >= the sequence's block count, in the future of the token when causal, or a repeat of an
+ *     earlier column of the same row are ignored (set semantics); they are data, not errors.
+ *   - cu_seqlens is int32 [nseq + 1] (device), cumulative sequence starts, cu_seqlens[nseq] == total_tokens;
+ *     it may be NULL when nseq == 1.  Sequences need not be multiples of 64; the last block is ragged.
+ *   - A row with no visible key gets O = 0, LSE = -inf and contributes no gradient.
+ *   - Return value: 0 on success, a negative NSA_SEL_E* code otherwise.  Arguments are validated on the host
+ *     before anything is launched; on error nothing has been enqueued (except NSA_SEL_EHIP, a launch failure).
+ */
+#ifndef NSA_SEL_H
+#define NSA_SEL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NSA_SEL_OK            0
+#define NSA_SEL_EINVAL       -1   /* null pointer, g outside [1,8], hq % hkv != 0, nseq < 1, negative sizes    */
+#define NSA_SEL_EUNSUPPORTED -2   /* d != 128, block != 64, topk outside [1,32], too many tokens/blocks       */
+#define NSA_SEL_EWORKSPACE   -3   /* a workspace is smaller than nsa_sel_workspace_bytes reports              */
+#define NSA_SEL_EHIP         -4   /* the HIP runtime refused a launch or attribute                            */
+
+typedef struct {
+  int32_t total_tokens;   /* sum of sequence lengths (N when nseq == 1)                                      */
+  int32_t nseq;           /* number of packed sequences, >= 1                                                */
+  int32_t hq, hkv;        /* query / KV heads; g = hq / hkv must be an integer in [1, 8]                     */
+  int32_t d;              /* head dimension; 128 only (every experiment of the paper uses d = 128)           */
+  int32_t block;          /* B_K; 64 only                                                                    */
+  int32_t topk;           /* T, selected blocks per (token, KV head); 1..32                                  */
+  int32_t causal;         /* 1: key u visible to token t only if u <= t (per sequence); 0: no mask           */
+  float   scale;          /* softmax scale; <= 0 selects 1/sqrt(d) (Eq. (1))                                 */
+  int32_t max_seqlen;     /* upper bound of the longest sequence; informational, may be 0                    */
+} nsa_sel_shape;
+
+/* Bytes of the three caller-owned workspaces for `shape` (any of the outputs may be NULL).
+ *   index_bytes: query lists and work-unit tables, written by nsa_sel_build_index / nsa_sel_fwd(rebuild_index=1)
+ *                and read by nsa_sel_fwd / nsa_sel_bwd (the paper's index tensors I_i, O_i "retrieved from
+ *                cache" in the backward pass, Sec. 3.2);
+ *   fwd_bytes:   per-(token, head, slot) partial outputs and log-sum-exps (the paper's O_buf, Sec. 3.2);
+ *   bwd_bytes:   partial dQ, delta, and per-work-unit dK/dV partial sums. */
+int nsa_sel_workspace_bytes(const nsa_sel_shape* shape, size_t* fwd_bytes, size_t* bwd_bytes, size_t* index_bytes);
+
+/* Index inversion (Sec. 3.2, "index tensors ... pre-computed from the NSA sparse selection tensor T"):
+ * histogram -> exclusive scan -> ordered scatter.  For every list L = kv_head * b_cap + global_block
+ * (b_cap = total_tokens / 64 + nseq; global blocks number the blocks of the packed sequences consecutively;
+ * lists past the real block count are empty) the result holds the ascending tokens that validly select the
+ * block and, per entry, the column of idx of the first occurrence.  Deterministic and bit-reproducible. */
+int nsa_sel_build_index(const nsa_sel_shape* shape, const int32_t* idx, const int32_t* cu_seqlens,
+                        void* index_ws, size_t index_bytes, void* stream);
+
+/* Device pointers into a built index workspace (for inspection and tests): cnt int32 [hkv * b_cap],
+ * off int32 [hkv * b_cap + 1] (exclusive prefix of cnt), qlist int32 [off[last]] token ids, qslot int32
+ * [off[last]] columns, vmask uint32 [total_tokens * hkv] (bit m set: column m of the row was kept).
+ * *b_cap receives the list stride.  Any output pointer may be NULL. */
+int nsa_sel_index_view(const nsa_sel_shape* shape, const void* index_ws, const int32_t** cnt, const int32_t** off,
+                       const int32_t** qlist, const int32_t** qslot, const uint32_t** vmask, int32_t* b_cap);
+
+/* Forward (Eq. (2), c = sel): O and LSE from Q, K, V, idx.  With rebuild_index != 0 the index workspace is
+ * (re)built from idx first; with 0 it must hold the result of an earlier build for the same idx/shape. */
+int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
+                float* LSE, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of the above: dQ, dK, dV from dO, the forward's O and LSE and the cached index workspace.
+ * dK/dV are accumulated without atomics (per-work-unit partial sums reduced in a fixed order), so results
+ * are bit-reproducible. */
+int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
+                const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws,
+                size_t index_bytes, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
+
+/* Static text for a return code. */
+const char* nsa_sel_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NSA_SEL_H */

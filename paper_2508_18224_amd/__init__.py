@@ -1,0 +1,8 @@
+"""MI355X-native selected-block attention (the `sel` branch of Native Sparse Attention, FSA paper Sec. 3).
+
+Thin ctypes binding over libnsa_sel.so (include/nsa_sel.h).  PyTorch is used for device memory and streams
+only; every step of the path runs in the library's HIP kernels.  There is no CPU fallback: without the built
+library, or without a GPU, the calls raise.
+"""
+from .binding import (NsaSelError, Shape, build_index, index_view, lib, nsa_sel_bwd, nsa_sel_fwd,  # noqa: F401
+                      workspace_bytes, SelAttention)

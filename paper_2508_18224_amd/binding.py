@@ -1,0 +1,143 @@
+"""ctypes marshalling for include/nsa_sel.h.  No arithmetic happens here."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
+_lib = None
+
+SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd",
+           "nsa_sel_strerror"]
+
+
+class NsaSelError(RuntimeError):
+    pass
+
+
+class Shape(C.Structure):
+    _fields_ = [("total_tokens", C.c_int32), ("nseq", C.c_int32), ("hq", C.c_int32), ("hkv", C.c_int32),
+                ("d", C.c_int32), ("block", C.c_int32), ("topk", C.c_int32), ("causal", C.c_int32),
+                ("scale", C.c_float), ("max_seqlen", C.c_int32)]
+
+
+def lib():
+    """Load the built library (raises if it has not been built; see paper_2508_18224_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise NsaSelError(f"{_LIB_PATH} is missing: run `python -m paper_2508_18224_amd.build` first")
+        L = C.CDLL(_LIB_PATH)
+        vp, sz, i32p = C.c_void_p, C.c_size_t, C.c_void_p
+        L.nsa_sel_workspace_bytes.argtypes = [C.POINTER(Shape), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+        L.nsa_sel_build_index.argtypes = [C.POINTER(Shape), i32p, i32p, vp, sz, vp]
+        L.nsa_sel_index_view.argtypes = [C.POINTER(Shape), vp] + [C.POINTER(vp)] * 5 + [C.POINTER(C.c_int32)]
+        L.nsa_sel_fwd.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, sz, vp]
+        L.nsa_sel_bwd.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, sz, vp]
+        L.nsa_sel_strerror.argtypes = [C.c_int]
+        L.nsa_sel_strerror.restype = C.c_char_p
+        for name in SYMBOLS[:-1]:
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise NsaSelError(f"{what}: {lib().nsa_sel_strerror(rc).decode()} ({rc})")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise NsaSelError("tensors must be contiguous device tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def workspace_bytes(shape: Shape):
+    f, b, i = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().nsa_sel_workspace_bytes(C.byref(shape), C.byref(f), C.byref(b), C.byref(i)), "nsa_sel_workspace_bytes")
+    return f.value, b.value, i.value
+
+
+def build_index(shape: Shape, idx: torch.Tensor, cu: Optional[torch.Tensor], index_ws: torch.Tensor):
+    _check(lib().nsa_sel_build_index(C.byref(shape), _ptr(idx), _ptr(cu), _ptr(index_ws), index_ws.numel(), _stream()),
+           "nsa_sel_build_index")
+
+
+def index_view(shape: Shape, index_ws: torch.Tensor):
+    """Byte offsets (from the workspace base) of cnt, off, qlist, qslot, vmask, and the list stride b_cap."""
+    outs = [C.c_void_p() for _ in range(5)]
+    bcap = C.c_int32()
+    _check(lib().nsa_sel_index_view(C.byref(shape), _ptr(index_ws), *[C.byref(o) for o in outs], C.byref(bcap)),
+           "nsa_sel_index_view")
+    base = index_ws.data_ptr()
+    return [o.value - base for o in outs], bcap.value
+
+
+def nsa_sel_fwd(shape, q, k, v, idx, cu, rebuild_index, index_ws, o, lse, ws):
+    _check(lib().nsa_sel_fwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu), int(rebuild_index),
+                             _ptr(index_ws), index_ws.numel(), _ptr(o), _ptr(lse), _ptr(ws), ws.numel(), _stream()),
+           "nsa_sel_fwd")
+
+
+def nsa_sel_bwd(shape, q, k, v, o, lse, do, cu, index_ws, dq, dk, dv, ws):
+    _check(lib().nsa_sel_bwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(cu),
+                             _ptr(index_ws), index_ws.numel(), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(),
+                             _stream()), "nsa_sel_bwd")
+
+
+class SelAttention:
+    """Owns the workspaces for one shape and calls the library (buffers are torch uint8 tensors)."""
+
+    def __init__(self, total_tokens, hq, hkv, topk, *, nseq=1, causal=True, scale=0.0, device="cuda:0", bwd=True):
+        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, 64, topk, int(causal), float(scale), 0)
+        fb, bb, ib = workspace_bytes(self.shape)
+        self.device = torch.device(device)
+        self.index_ws = torch.empty(ib, dtype=torch.uint8, device=self.device)
+        self.fwd_ws = torch.empty(fb, dtype=torch.uint8, device=self.device)
+        self.bwd_ws = torch.empty(bb, dtype=torch.uint8, device=self.device) if bwd else None
+
+    def build_index(self, idx, cu=None):
+        build_index(self.shape, idx, cu, self.index_ws)
+
+    def forward(self, q, k, v, idx, cu=None, rebuild_index=True, out=None, lse=None):
+        s = self.shape
+        o = torch.empty(s.total_tokens, s.hq, 128, dtype=torch.bfloat16, device=self.device) if out is None else out
+        l = torch.empty(s.total_tokens, s.hq, dtype=torch.float32, device=self.device) if lse is None else lse
+        nsa_sel_fwd(s, q, k, v, idx, cu, rebuild_index, self.index_ws, o, l, self.fwd_ws)
+        return o, l
+
+    def backward(self, q, k, v, o, lse, do, cu=None, out=None):
+        s = self.shape
+        if out is None:
+            dq = torch.empty_like(q)
+            dk = torch.empty_like(k)
+            dv = torch.empty_like(v)
+        else:
+            dq, dk, dv = out
+        nsa_sel_bwd(s, q, k, v, o, lse, do, cu, self.index_ws, dq, dk, dv, self.bwd_ws)
+        return dq, dk, dv
+
+    def index_arrays(self):
+        """Host copies of (cnt [hkv, b_cap], off, qlist, qslot, vmask [T, hkv]) for inspection."""
+        (o_cnt, o_off, o_ql, o_qs, o_vm), bcap = index_view(self.shape, self.index_ws)
+        s = self.shape
+        nl = s.hkv * bcap
+        raw = self.index_ws
+        def ints(off, n):
+            return raw[off:off + 4 * n].view(torch.int32).cpu().numpy()
+        cnt = ints(o_cnt, nl).reshape(s.hkv, bcap)
+        off = ints(o_off, nl + 1)
+        npairs = int(off[-1])
+        return cnt, off, ints(o_ql, npairs), ints(o_qs, npairs), ints(o_vm, s.total_tokens * s.hkv).reshape(
+            s.total_tokens, s.hkv).view("uint32"), bcap

@@ -1,0 +1,29 @@
+"""Compile the HIP sources of the library for gfx950 into libnsa_sel.so next to this file."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SOURCES = ["api.hip", "index.hip", "fwd.hip", "bwd.hip"]
+LIB = os.path.join(HERE, "libnsa_sel.so")
+# -packed-fp32-ops: keep the compiler from forming packed fp32 instructions
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature", "-Xclang",
+         "-packed-fp32-ops", "-Wall"]
+
+
+def build(verbose: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *FLAGS, "-o", LIB, *[os.path.join(HERE, "csrc", s) for s in SOURCES]]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + res.stderr)
+        raise RuntimeError("hipcc failed")
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,188 @@
+// C ABI of the library (see include/nsa_sel.h): argument validation, workspace layout, launch sequencing.
+#include "common.h"
+
+namespace nsa {
+int64_t index_scan_tmp_ints(int64_t n_counters);
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int check_shape(const nsa_sel_shape* s) {
+  if (!s) return NSA_SEL_EINVAL;
+  if (s->total_tokens < 0 || s->nseq < 1 || s->hq < 1 || s->hkv < 1) return NSA_SEL_EINVAL;
+  if (s->hq % s->hkv != 0) return NSA_SEL_EINVAL;
+  const int g = s->hq / s->hkv;
+  if (g < 1 || g > 8) return NSA_SEL_EINVAL;
+  if (s->d != kD || s->block != kBlock) return NSA_SEL_EUNSUPPORTED;
+  if (s->topk < 1 || s->topk > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
+  if (s->nseq > (1 << 20)) return NSA_SEL_EUNSUPPORTED;
+  const int64_t b_cap = (int64_t)s->total_tokens / kBlock + s->nseq;
+  // LDS tables of the inversion (12 bytes per block) must fit in one CU's 160 KB
+  if (b_cap * 12 + 64 * (int64_t)(s->topk + 1) * 4 > 160 * 1024) return NSA_SEL_EUNSUPPORTED;
+  const int64_t p_max = (int64_t)s->total_tokens * s->hkv * s->topk;
+  if (p_max >= ((int64_t)1 << 31) - 4096) return NSA_SEL_EUNSUPPORTED;
+  const int64_t n_chunks = ((int64_t)s->total_tokens + kChunkTokens - 1) / kChunkTokens;
+  if (b_cap * s->hkv * (n_chunks > 0 ? n_chunks : 1) >= ((int64_t)1 << 31) - 4096) return NSA_SEL_EUNSUPPORTED;
+  return NSA_SEL_OK;
+}
+
+static IndexLayout make_layout(const nsa_sel_shape* s) {
+  IndexLayout L;
+  L.T = s->total_tokens;
+  L.nseq = s->nseq;
+  L.hkv = s->hkv;
+  L.topk = s->topk;
+  L.causal = s->causal ? 1 : 0;
+  L.b_cap = s->total_tokens / kBlock + s->nseq;
+  L.n_lists = s->hkv * L.b_cap;
+  L.n_chunks = (s->total_tokens + kChunkTokens - 1) / kChunkTokens;
+  if (L.n_chunks < 1) L.n_chunks = 1;
+  L.n_counters = (int64_t)L.n_lists * L.n_chunks;
+  L.p_max = (int64_t)s->total_tokens * s->hkv * s->topk;
+  L.fwd_units_max = (int32_t)(L.n_lists + L.p_max / kFwdUnit);
+  L.bwd_units_max = (int32_t)(L.n_lists + L.p_max / kBwdUnit);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };
+  L.hdr = take(64);
+  L.blk_base = take(4 * (size_t)(L.nseq + 1));
+  L.blk_tok0 = take(4 * (size_t)L.b_cap);
+  L.blk_len = take(4 * (size_t)L.b_cap);
+  L.chunk_off = take(4 * (size_t)(L.n_counters + 1));
+  L.cnt = take(4 * (size_t)L.n_lists);
+  L.off = take(4 * (size_t)(L.n_lists + 1));
+  L.qlist = take(4 * (size_t)(L.p_max + 1));
+  L.qslot = take(4 * (size_t)(L.p_max + 1));
+  L.vmask = take(4 * ((size_t)L.T * L.hkv + 1));
+  L.f_nu = take(4 * (size_t)(L.n_lists + 1));
+  L.f_list = take(4 * (size_t)(L.fwd_units_max + 1));
+  L.f_start = take(4 * (size_t)(L.fwd_units_max + 1));
+  L.b_nu = take(4 * (size_t)(L.n_lists + 1));
+  L.b_list = take(4 * (size_t)(L.bwd_units_max + 1));
+  L.b_start = take(4 * (size_t)(L.bwd_units_max + 1));
+  L.scan_tmp = take(4 * (size_t)index_scan_tmp_ints(L.n_counters));
+  L.total = o;
+  return L;
+}
+
+static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
+  Problem P;
+  P.T = s->total_tokens;
+  P.nseq = s->nseq;
+  P.hq = s->hq;
+  P.hkv = s->hkv;
+  P.g = s->hq / s->hkv;
+  P.topk = s->topk;
+  P.causal = s->causal ? 1 : 0;
+  P.b_cap = L.b_cap;
+  P.scale = s->scale > 0.f ? s->scale : 0.08838834764831845f;  // 1/sqrt(128)
+  return P;
+}
+
+static size_t fwd_ws_bytes(const nsa_sel_shape* s) {
+  const size_t rows = (size_t)s->total_tokens * s->hq * s->topk;
+  return align256(rows * kD * 2) + align256(rows * 4);
+}
+
+static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L) {
+  const size_t rows = (size_t)s->total_tokens * s->hq * s->topk;
+  return align256(rows * kD * 2) + align256((size_t)s->total_tokens * s->hq * 4) +
+         align256((size_t)L.bwd_units_max * 2 * kBlock * kD * 4);
+}
+}  // namespace nsa
+
+using namespace nsa;
+
+extern "C" {
+
+int nsa_sel_workspace_bytes(const nsa_sel_shape* shape, size_t* fwd_bytes, size_t* bwd_bytes, size_t* index_bytes) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  IndexLayout L = make_layout(shape);
+  if (fwd_bytes) *fwd_bytes = fwd_ws_bytes(shape);
+  if (bwd_bytes) *bwd_bytes = bwd_ws_bytes(shape, L);
+  if (index_bytes) *index_bytes = L.total;
+  return NSA_SEL_OK;
+}
+
+int nsa_sel_build_index(const nsa_sel_shape* shape, const int32_t* idx, const int32_t* cu_seqlens, void* index_ws,
+                        size_t index_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!idx || !index_ws) return NSA_SEL_EINVAL;
+  if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
+  IndexLayout L = make_layout(shape);
+  if (index_bytes < L.total) return NSA_SEL_EWORKSPACE;
+  if (shape->total_tokens == 0) return NSA_SEL_OK;
+  return launch_build_index(L, idx, cu_seqlens, index_ws, (hipStream_t)stream) == hipSuccess ? NSA_SEL_OK
+                                                                                            : NSA_SEL_EHIP;
+}
+
+int nsa_sel_index_view(const nsa_sel_shape* shape, const void* index_ws, const int32_t** cnt, const int32_t** off,
+                       const int32_t** qlist, const int32_t** qslot, const uint32_t** vmask, int32_t* b_cap) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!index_ws) return NSA_SEL_EINVAL;
+  IndexLayout L = make_layout(shape);
+  IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
+  if (cnt) *cnt = p.cnt;
+  if (off) *off = p.off;
+  if (qlist) *qlist = p.qlist;
+  if (qslot) *qslot = p.qslot;
+  if (vmask) *vmask = p.vmask;
+  if (b_cap) *b_cap = L.b_cap;
+  return NSA_SEL_OK;
+}
+
+int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O, float* LSE,
+                void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!Q || !K || !V || !index_ws || !O || !LSE || !ws) return NSA_SEL_EINVAL;
+  if (rebuild_index && !idx) return NSA_SEL_EINVAL;
+  if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
+  IndexLayout L = make_layout(shape);
+  if (index_bytes < L.total || ws_bytes < fwd_ws_bytes(shape)) return NSA_SEL_EWORKSPACE;
+  if (shape->total_tokens == 0) return NSA_SEL_OK;
+  hipStream_t st = (hipStream_t)stream;
+  if (rebuild_index && launch_build_index(L, idx, cu_seqlens, index_ws, st) != hipSuccess) return NSA_SEL_EHIP;
+  Problem P = make_problem(shape, L);
+  const size_t rows = (size_t)shape->total_tokens * shape->hq * shape->topk;
+  void* opart = ws;
+  float* lse_part = (float*)((char*)ws + align256(rows * kD * 2));
+  return launch_fwd(P, L, Q, K, V, index_ws, opart, lse_part, O, LSE, st) == hipSuccess ? NSA_SEL_OK : NSA_SEL_EHIP;
+}
+
+int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
+                const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws, size_t index_bytes,
+                void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!Q || !K || !V || !O || !LSE || !dO || !index_ws || !dQ || !dK || !dV || !ws) return NSA_SEL_EINVAL;
+  if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
+  IndexLayout L = make_layout(shape);
+  if (index_bytes < L.total || ws_bytes < bwd_ws_bytes(shape, L)) return NSA_SEL_EWORKSPACE;
+  if (shape->total_tokens == 0) return NSA_SEL_OK;
+  Problem P = make_problem(shape, L);
+  const size_t rows = (size_t)shape->total_tokens * shape->hq * shape->topk;
+  char* w = (char*)ws;
+  void* dqpart = w;
+  float* delta = (float*)(w + align256(rows * kD * 2));
+  float* dkv_part = (float*)((char*)delta + align256((size_t)shape->total_tokens * shape->hq * 4));
+  return launch_bwd(P, L, Q, K, V, O, LSE, dO, index_ws, dqpart, delta, dkv_part, dQ, dK, dV, (hipStream_t)stream) ==
+                 hipSuccess
+             ? NSA_SEL_OK
+             : NSA_SEL_EHIP;
+}
+
+const char* nsa_sel_strerror(int code) {
+  switch (code) {
+    case NSA_SEL_OK: return "ok";
+    case NSA_SEL_EINVAL: return "invalid argument (null pointer, head counts, nseq)";
+    case NSA_SEL_EUNSUPPORTED: return "unsupported shape (d must be 128, block 64, topk 1..32, size limits)";
+    case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes)";
+    case NSA_SEL_EHIP: return "HIP runtime error at launch";
+    default: return "unknown nsa_sel error code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+// Shared declarations of the gfx950 selected-attention library: workspace layout, launch prototypes and
+// small device helpers.  Everything here is internal; the public surface is include/nsa_sel.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/nsa_sel.h"
+
+namespace nsa {
+
+constexpr int kBlock = 64;         // B_K
+constexpr int kD = 128;            // head dimension
+constexpr int kChunkTokens = 512;  // token chunk of the inversion histogram / scatter
+constexpr int kFwdUnit = 512;      // list entries per forward work unit
+constexpr int kBwdUnit = 2048;     // list entries per backward work unit
+constexpr int kMaxTopk = 32;
+
+// Host-computed description of the index workspace (byte offsets from its base, all 256-aligned).
+struct IndexLayout {
+  int32_t T, nseq, hkv, topk, causal;
+  int32_t b_cap;        // list stride: T / 64 + nseq  (>= real number of blocks)
+  int32_t n_lists;      // hkv * b_cap
+  int32_t n_chunks;     // ceil(T / kChunkTokens)
+  int64_t n_counters;   // n_lists * n_chunks
+  int64_t p_max;        // T * hkv * topk
+  int32_t fwd_units_max, bwd_units_max;
+  size_t hdr, blk_base, blk_tok0, blk_len, chunk_off, cnt, off, qlist, qslot, vmask;
+  size_t f_nu, f_list, f_start, b_nu, b_list, b_start, scan_tmp;
+  size_t total;
+};
+
+// hdr words
+enum { HDR_BTOT = 0, HDR_NPAIRS = 1, HDR_FUNITS = 2, HDR_BUNITS = 3 };
+
+struct IndexPtrs {
+  int32_t* hdr;
+  int32_t* blk_base;
+  int32_t* blk_tok0;
+  int32_t* blk_len;
+  int32_t* chunk_off;
+  int32_t* cnt;
+  int32_t* off;
+  int32_t* qlist;
+  int32_t* qslot;
+  uint32_t* vmask;
+  int32_t *f_nu, *f_list, *f_start, *b_nu, *b_list, *b_start;
+  int32_t* scan_tmp;
+};
+
+inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
+  char* p = static_cast<char*>(base);
+  IndexPtrs r;
+  r.hdr = (int32_t*)(p + L.hdr);
+  r.blk_base = (int32_t*)(p + L.blk_base);
+  r.blk_tok0 = (int32_t*)(p + L.blk_tok0);
+  r.blk_len = (int32_t*)(p + L.blk_len);
+  r.chunk_off = (int32_t*)(p + L.chunk_off);
+  r.cnt = (int32_t*)(p + L.cnt);
+  r.off = (int32_t*)(p + L.off);
+  r.qlist = (int32_t*)(p + L.qlist);
+  r.qslot = (int32_t*)(p + L.qslot);
+  r.vmask = (uint32_t*)(p + L.vmask);
+  r.f_nu = (int32_t*)(p + L.f_nu);
+  r.f_list = (int32_t*)(p + L.f_list);
+  r.f_start = (int32_t*)(p + L.f_start);
+  r.b_nu = (int32_t*)(p + L.b_nu);
+  r.b_list = (int32_t*)(p + L.b_list);
+  r.b_start = (int32_t*)(p + L.b_start);
+  r.scan_tmp = (int32_t*)(p + L.scan_tmp);
+  return r;
+}
+
+// Problem description handed to the attention kernels.
+struct Problem {
+  int32_t T, nseq, hq, hkv, g, topk, causal, b_cap;
+  float scale;
+};
+
+// ---- launchers (each enqueues on `st` and returns hipGetLastError()) -------------------------------------
+hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
+                              hipStream_t st);
+hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
+                      const void* index_ws, void* opart, float* lse_part, void* O, float* LSE, hipStream_t st);
+hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
+                      const void* O, const float* LSE, const void* dO, const void* index_ws, void* dqpart,
+                      float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st);
+
+// ---- device helpers ------------------------------------------------------------------------------------
+#if defined(__HIPCC__)
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  f32x2 v = {a, b};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+
+// Sequence bounds of token t in a packed batch (cu may be null for a single sequence).
+__device__ __forceinline__ void seq_bounds(const int32_t* cu, int nseq, int T, int t, int& s, int& c0, int& c1) {
+  if (cu == nullptr || nseq == 1) {
+    s = 0;
+    c0 = 0;
+    c1 = T;
+    return;
+  }
+  int lo = 0, hi = nseq;  // invariant: cu[lo] <= t < cu[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (cu[mid] <= t) lo = mid; else hi = mid;
+  }
+  s = lo;
+  c0 = cu[lo];
+  c1 = cu[lo + 1];
+}
+#endif
+
+}  // namespace nsa

@@ -1,0 +1,317 @@
+// Index inversion for selected-block attention: from the selection table idx[token, kv head, slot] build, for
+// every (kv head, KV block), the ascending list of query tokens that select it (the paper's index tensor I_i,
+// Sec. 3.2 "FSA token selection kernel") together with the slot each entry came from (which fixes its place
+// in the partial-result buffer, the role of the paper's O_i), plus the work-unit tables of the attention
+// kernels.  Pipeline: per-(kv head, block, token chunk) histogram -> exclusive scan -> ordered scatter.
+// The scatter is deterministic: a chunk is walked by one wavefront in rounds of 64 tokens, and a token's rank
+// inside a round is a popcount over a 64-bit membership mask, so no ordering depends on atomics.
+#include "common.h"
+
+namespace nsa {
+
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 16;
+constexpr int kScanTile = kScanThreads * kScanItems;  // 4096
+
+// ------------------------------------------------------------------------------------------------ prep
+// blk_base[s] = number of blocks of sequences < s; per global block its first token and its key count.
+__global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int b_cap, int32_t* __restrict__ blk_base,
+                       int32_t* __restrict__ blk_tok0, int32_t* __restrict__ blk_len, int32_t* __restrict__ hdr) {
+  __shared__ int s_btot;
+  if (threadIdx.x == 0) {
+    int acc = 0;
+    for (int s = 0; s < nseq; ++s) {
+      int c0 = cu ? cu[s] : 0, c1 = cu ? cu[s + 1] : T;
+      blk_base[s] = acc;
+      acc += (c1 - c0 + kBlock - 1) / kBlock;
+    }
+    blk_base[nseq] = acc;
+    s_btot = acc;
+    hdr[HDR_BTOT] = acc;
+  }
+  __threadfence_block();
+  __syncthreads();
+  const int b_tot = s_btot;
+  for (int gb = threadIdx.x; gb < b_cap; gb += blockDim.x) {
+    int tok0 = 0, len = 0;
+    if (gb < b_tot) {
+      int lo = 0, hi = nseq;  // blk_base[lo] <= gb < blk_base[hi]
+      while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (blk_base[mid] <= gb) lo = mid; else hi = mid;
+      }
+      int c0 = cu ? cu[lo] : 0, c1 = cu ? cu[lo + 1] : T;
+      tok0 = c0 + (gb - blk_base[lo]) * kBlock;
+      len = min(kBlock, c1 - tok0);
+    }
+    blk_tok0[gb] = tok0;
+    blk_len[gb] = len;
+  }
+}
+
+__global__ void k_zero(int32_t* __restrict__ p, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0;
+}
+
+// Bit m of the result is set when column m of the row is a kept selection: in range for the sequence, not in
+// the token's future when causal, and not a repeat of an earlier column.
+__device__ __forceinline__ uint32_t kept_columns(const int32_t* row, int k, int b_s, int cur, int causal) {
+  uint32_t vm = 0;
+  for (int m = 0; m < k; ++m) {
+    int x = row[m];
+    bool ok = x >= 0 && x < b_s && (!causal || x <= cur);
+    for (int mp = 0; mp < m && ok; ++mp) ok = row[mp] != x;
+    if (ok) vm |= 1u << m;
+  }
+  return vm;
+}
+
+// Window of global blocks a token chunk can touch: all blocks of the sequences it overlaps.
+__device__ __forceinline__ void chunk_window(const int32_t* cu, const int32_t* blk_base, int nseq, int T, int t0,
+                                             int t1, int& gb_lo, int& gb_hi) {
+  int s0, s1, a, b;
+  seq_bounds(cu, nseq, T, t0, s0, a, b);
+  seq_bounds(cu, nseq, T, t1 - 1, s1, a, b);
+  gb_lo = blk_base[s0];
+  gb_hi = blk_base[s1 + 1];
+}
+
+// ------------------------------------------------------------------------------------------------ histogram
+// grid (n_chunks, hkv), 256 threads.  counters[(j*b_cap + gb)*n_chunks + chunk] = number of tokens of the
+// chunk that keep block gb for kv head j.  Dynamic LDS: b_cap ints + 256*(k+1) ints.
+__global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
+                                              const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
+                                              int causal, int b_cap, int n_chunks, int32_t* __restrict__ counters) {
+  extern __shared__ int32_t lds[];
+  int32_t* hist = lds;
+  int32_t* rows = lds + b_cap;
+  const int chunk = blockIdx.x, j = blockIdx.y;
+  const int t0 = chunk * kChunkTokens, t1 = min(t0 + kChunkTokens, T);
+  int gb_lo, gb_hi;
+  chunk_window(cu, blk_base, nseq, T, t0, t1, gb_lo, gb_hi);
+  const int win = gb_hi - gb_lo;
+  for (int i = threadIdx.x; i < win; i += blockDim.x) hist[i] = 0;
+  __syncthreads();
+  int32_t* row = rows + threadIdx.x * (k + 1);
+  for (int t = t0 + threadIdx.x; t < t1; t += blockDim.x) {
+    int s, c0, c1;
+    seq_bounds(cu, nseq, T, t, s, c0, c1);
+    const int32_t* src = idx + ((size_t)t * hkv + j) * k;
+    for (int m = 0; m < k; ++m) row[m] = src[m];
+    const int b_s = (c1 - c0 + kBlock - 1) / kBlock;
+    const int cur = (t - c0) / kBlock;
+    uint32_t vm = kept_columns(row, k, b_s, cur, causal);
+    const int base = blk_base[s] - gb_lo;
+    for (int m = 0; m < k; ++m)
+      if ((vm >> m) & 1u) atomicAdd(&hist[base + row[m]], 1);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < win; i += blockDim.x)
+    counters[((size_t)j * b_cap + gb_lo + i) * n_chunks + chunk] = hist[i];
+}
+
+// ------------------------------------------------------------------------------------------------ scan
+__global__ void __launch_bounds__(kScanThreads) k_scan_reduce(const int32_t* __restrict__ a, int64_t n,
+                                                              int32_t* __restrict__ sums) {
+  __shared__ int32_t part[kScanThreads];
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  int32_t acc = 0;
+  for (int i = 0; i < kScanItems; ++i)
+    if (base + i < n) acc += a[base + i];
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = kScanThreads / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) sums[blockIdx.x] = part[0];
+}
+
+// In-place exclusive scan of one 4096-item tile, plus offsets[blockIdx.x] when given.
+__global__ void __launch_bounds__(kScanThreads) k_scan_tile(int32_t* __restrict__ a, int64_t n,
+                                                            const int32_t* __restrict__ offsets) {
+  __shared__ int32_t part[2][kScanThreads];
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  int32_t v[kScanItems];
+  int32_t acc = 0;
+  for (int i = 0; i < kScanItems; ++i) {
+    v[i] = (base + i < n) ? a[base + i] : 0;
+    acc += v[i];
+  }
+  int cur = 0;
+  part[0][threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 1; s < kScanThreads; s <<= 1) {  // Hillis-Steele inclusive scan of the thread totals
+    int32_t x = part[cur][threadIdx.x];
+    if ((int)threadIdx.x >= s) x += part[cur][threadIdx.x - s];
+    part[cur ^ 1][threadIdx.x] = x;
+    cur ^= 1;
+    __syncthreads();
+  }
+  int32_t run = part[cur][threadIdx.x] - acc + (offsets ? offsets[blockIdx.x] : 0);
+  for (int i = 0; i < kScanItems; ++i) {
+    if (base + i < n) a[base + i] = run;
+    run += v[i];
+  }
+}
+
+static int64_t scan_tmp_ints(int64_t n) {
+  int64_t total = 0;
+  while (n > kScanTile) {
+    n = (n + kScanTile - 1) / kScanTile;
+    total += (n + 63) / 64 * 64;
+  }
+  return total + 64;
+}
+
+static void scan_exclusive(int32_t* a, int64_t n, int32_t* tmp, hipStream_t st) {
+  const int64_t nb = (n + kScanTile - 1) / kScanTile;
+  if (nb <= 1) {
+    hipLaunchKernelGGL(k_scan_tile, dim3(1), dim3(kScanThreads), 0, st, a, n, (const int32_t*)nullptr);
+    return;
+  }
+  hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)nb), dim3(kScanThreads), 0, st, a, n, tmp);
+  scan_exclusive(tmp, nb, tmp + (nb + 63) / 64 * 64, st);
+  hipLaunchKernelGGL(k_scan_tile, dim3((unsigned)nb), dim3(kScanThreads), 0, st, a, n, (const int32_t*)tmp);
+}
+
+// ------------------------------------------------------------------------------------------------ scatter
+// grid (n_chunks, hkv), ONE wavefront per group.  chunk_off holds the scanned counters, i.e. for every
+// (kv head, block, chunk) the position in qlist where that chunk's tokens start.  Dynamic LDS: b_cap u64
+// masks + b_cap int cursors + 64*(k+1) ints.
+__global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
+                                                const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
+                                                int causal, int b_cap, int n_chunks,
+                                                const int32_t* __restrict__ chunk_off, int32_t* __restrict__ qlist,
+                                                int32_t* __restrict__ qslot, uint32_t* __restrict__ vmask) {
+  extern __shared__ int32_t lds[];
+  unsigned long long* mask = reinterpret_cast<unsigned long long*>(lds);
+  int32_t* cursor = lds + 2 * b_cap;
+  int32_t* rows = cursor + b_cap;
+  const int chunk = blockIdx.x, j = blockIdx.y, lane = threadIdx.x;
+  const int t0 = chunk * kChunkTokens, t1 = min(t0 + kChunkTokens, T);
+  int gb_lo, gb_hi;
+  chunk_window(cu, blk_base, nseq, T, t0, t1, gb_lo, gb_hi);
+  const int win = gb_hi - gb_lo;
+  for (int i = lane; i < win; i += 64) {
+    mask[i] = 0ull;
+    cursor[i] = chunk_off[((size_t)j * b_cap + gb_lo + i) * n_chunks + chunk];
+  }
+  __syncthreads();
+  int32_t* row = rows + lane * (k + 1);
+  const unsigned long long below = (1ull << lane) - 1ull;
+  for (int r0 = t0; r0 < t1; r0 += 64) {
+    const int t = r0 + lane;
+    uint32_t vm = 0;
+    int base = 0;
+    if (t < t1) {
+      int s, c0, c1;
+      seq_bounds(cu, nseq, T, t, s, c0, c1);
+      const int32_t* src = idx + ((size_t)t * hkv + j) * k;
+      for (int m = 0; m < k; ++m) row[m] = src[m];
+      vm = kept_columns(row, k, (c1 - c0 + kBlock - 1) / kBlock, (t - c0) / kBlock, causal);
+      base = blk_base[s] - gb_lo;
+      vmask[(size_t)t * hkv + j] = vm;
+    }
+    // A: mark membership of this round's tokens in every block they keep
+    for (int m = 0; m < k; ++m)
+      if ((vm >> m) & 1u) atomicOr(&mask[base + row[m]], 1ull << lane);
+    __syncthreads();
+    // B: rank among the lower tokens of the round gives the position; lists come out ascending
+    for (int m = 0; m < k; ++m)
+      if ((vm >> m) & 1u) {
+        const int w = base + row[m];
+        const int pos = cursor[w] + __popcll(mask[w] & below);
+        qlist[pos] = t;
+        qslot[pos] = m;
+      }
+    __syncthreads();
+    // C: the lowest member of each touched block advances its cursor and clears the mask
+    for (int m = 0; m < k; ++m)
+      if ((vm >> m) & 1u) {
+        const int w = base + row[m];
+        const unsigned long long mk = mask[w];
+        if (mk != 0ull && (mk & below) == 0ull) {
+          cursor[w] += __popcll(mk);
+          mask[w] = 0ull;
+        }
+      }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ finalize
+// cnt/off per list from the scanned counters; number of work units per list for both unit sizes.
+__global__ void k_finalize(const int32_t* __restrict__ chunk_off, int n_lists, int n_chunks, int32_t* __restrict__ cnt,
+                           int32_t* __restrict__ off, int32_t* __restrict__ f_nu, int32_t* __restrict__ b_nu,
+                           int32_t* __restrict__ hdr) {
+  const int L = blockIdx.x * blockDim.x + threadIdx.x;
+  if (L > n_lists) return;
+  const int32_t o = chunk_off[(size_t)L * n_chunks];
+  off[L] = o;
+  if (L == n_lists) {
+    hdr[HDR_NPAIRS] = o;
+    f_nu[L] = 0;
+    b_nu[L] = 0;
+    return;
+  }
+  const int32_t c = chunk_off[(size_t)(L + 1) * n_chunks] - o;
+  cnt[L] = c;
+  f_nu[L] = (c + kFwdUnit - 1) / kFwdUnit;
+  b_nu[L] = (c + kBwdUnit - 1) / kBwdUnit;
+}
+
+// nu_scan is the exclusive scan of units per list (n_lists + 1 entries).
+__global__ void k_units(const int32_t* __restrict__ nu_scan, const int32_t* __restrict__ off, int n_lists, int unit,
+                        int32_t* __restrict__ u_list, int32_t* __restrict__ u_start, int32_t* __restrict__ hdr_slot) {
+  const int L = blockIdx.x * blockDim.x + threadIdx.x;
+  if (L >= n_lists) return;
+  const int u0 = nu_scan[L], u1 = nu_scan[L + 1];
+  for (int u = u0; u < u1; ++u) {
+    u_list[u] = L;
+    u_start[u] = off[L] + (u - u0) * unit;
+  }
+  if (L == n_lists - 1) *hdr_slot = u1;
+}
+
+hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
+                              hipStream_t st) {
+  IndexPtrs p = index_ptrs(L, index_ws);
+  const size_t lds_hist = (size_t)L.b_cap * 4 + 256 * (size_t)(L.topk + 1) * 4;
+  const size_t lds_scat = (size_t)L.b_cap * 12 + 64 * (size_t)(L.topk + 1) * 4;
+  if (lds_hist > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_hist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_hist);
+    if (e != hipSuccess) return e;
+  }
+  if (lds_scat > 64 * 1024) {
+    hipError_t e =
+        hipFuncSetAttribute((const void*)k_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_scat);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_prep, dim3(1), dim3(256), 0, st, cu, L.nseq, L.T, L.b_cap, p.blk_base, p.blk_tok0, p.blk_len,
+                     p.hdr);
+  const int64_t nc = L.n_counters + 1;
+  hipLaunchKernelGGL(k_zero, dim3((unsigned)((nc + 1023) / 1024 > 4096 ? 4096 : (nc + 1023) / 1024)), dim3(256), 0, st,
+                     p.chunk_off, nc);
+  hipLaunchKernelGGL(k_hist, dim3(L.n_chunks, L.hkv), dim3(256), lds_hist, st, idx, cu, p.blk_base, L.nseq, L.T, L.hkv,
+                     L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off);
+  scan_exclusive(p.chunk_off, nc, p.scan_tmp, st);
+  hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
+                     L.hkv, L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask);
+  const int nl1 = L.n_lists + 1;
+  hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.chunk_off, L.n_lists, L.n_chunks, p.cnt,
+                     p.off, p.f_nu, p.b_nu, p.hdr);
+  scan_exclusive(p.f_nu, nl1, p.scan_tmp, st);
+  scan_exclusive(p.b_nu, nl1, p.scan_tmp, st);
+  hipLaunchKernelGGL(k_units, dim3((L.n_lists + 255) / 256), dim3(256), 0, st, p.f_nu, p.off, L.n_lists, kFwdUnit,
+                     p.f_list, p.f_start, p.hdr + HDR_FUNITS);
+  hipLaunchKernelGGL(k_units, dim3((L.n_lists + 255) / 256), dim3(256), 0, st, p.b_nu, p.off, L.n_lists, kBwdUnit,
+                     p.b_list, p.b_start, p.hdr + HDR_BUNITS);
+  return hipGetLastError();
+}
+
+int64_t index_scan_tmp_ints(int64_t n_counters) { return scan_tmp_ints(n_counters + 1); }
+
+}  // namespace nsa

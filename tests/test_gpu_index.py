@@ -1,0 +1,53 @@
+"""Index inversion on the GPU must equal the oracle's sequential inversion bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import nsa_sel_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def _compare(w, idx_override=None):
+    import paper_2508_18224_amd as nsa
+    idx = w.idx if idx_override is None else idx_override
+    attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, bwd=False)
+    attn.build_index(torch.from_numpy(idx).cuda(), torch.from_numpy(w.cu_seqlens).cuda())
+    torch.cuda.synchronize()
+    cnt, off, qlist, qslot, vmask, bcap = attn.index_arrays()
+    rc, ro, rl, rs, rv = orc.invert_index(idx, w.cu_seqlens, causal=w.causal)
+    b_tot = rc.shape[1]
+    assert bcap >= b_tot
+    assert np.array_equal(cnt[:, :b_tot], rc) and not cnt[:, b_tot:].any()
+    for j in range(w.hkv):
+        assert np.array_equal(off[j * bcap: j * bcap + b_tot].astype(np.int64), ro[j * b_tot:(j + 1) * b_tot])
+    assert int(off[-1]) == int(ro[-1])
+    assert np.array_equal(qlist, rl)
+    assert np.array_equal(qslot, rs)
+    assert np.array_equal(vmask, rv)
+
+
+@pytest.mark.parametrize("name", wl.SMALL_NAMES + ["tiny"])
+def test_inversion_bit_exact(name):
+    print("case", name, flush=True)
+    w = wl.realise(wl.small(name) if name != "tiny" else wl.named("tiny"), tensors=False)
+    _compare(w)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_inversion_drop_rules(causal):
+    """Future, out-of-range, padding and repeated ids are dropped exactly as the oracle drops them."""
+    print("adversarial causal", causal, flush=True)
+    w = wl.Workload("adv", [1000, 77, 640], hq=4, hkv=2, topk=12, causal=causal, seed=5)
+    wl.realise(w, tensors=False)
+    idx = wl.draw_adversarial_indices(np.random.default_rng(8), w.seqlens, w.hkv, w.topk)
+    _compare(w, idx)
+
+
+def test_inversion_multi_chunk_scan():
+    """Enough lists x chunks that the scan needs more than one level, and chunks that straddle sequences."""
+    print("multi-level scan", flush=True)
+    w = wl.Workload("big", [5000, 3000, 4100], hq=4, hkv=4, topk=16, sink=True, seed=6)
+    wl.realise(w, tensors=False)
+    _compare(w)
