@@ -1,0 +1,140 @@
+#!/usr/bin/env python3
+"""Benchmark of the selected-attention hot path on one MI355X.
+
+A step is one pass of the whole path on the headline workload (N = 65536, hq = 32, hkv = 8, g = 4, top-k 16,
+block 64, d = 128, causal, seeded synthetic bf16 inputs already resident in HBM): index inversion, forward
+(main + merge), backward (delta, main, dQ reduce, dK/dV reduce).  Prints ONE JSON line: effective TFLOP/s
+(4 N hq k 64 d forward + 2.5x backward, per the paper's FLOP count for the selected kernel), a roofline object
+for the dominant kernel, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by
+# the copy-kernel calibration); see profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(w, budget_tokens: int):
+    """The fp64 oracle, as it stands, on evenly spaced tokens of the same workload (forward, then backward)."""
+    from threadpoolctl import threadpool_limits
+
+    import workloads as wl
+    from oracle import nsa_sel_oracle as orc
+    from paper_2508_18224_amd.cost_model import effective_flops
+    Q, K, V, dO = (wl.bf16_bits_to_f64(x) for x in (w.q, w.k, w.v, w.do))
+    T = w.total_tokens
+    tokens = [int(x) for x in np.linspace(0, T - 1, budget_tokens).astype(np.int64)]
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        orc.forward(Q, K, V, w.idx, w.cu_seqlens, causal=w.causal, tokens=tokens)
+        orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, causal=w.causal, tokens=tokens)
+        dt = time.perf_counter() - t0
+    f, b = effective_flops(len(tokens), w.hq, w.topk)
+    return {"value": (f + b) / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(tokens)} evenly spaced query tokens of the same workload, all heads, forward + "
+                      f"backward contributions of those rows, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="headline")
+    ap.add_argument("--cpu-tokens", type=int, default=192, help="query tokens of the CPU-oracle sample (0: skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards over KV heads with no "
+                 "communication; see DESIGN.md); run with --gpus 1")
+
+    import torch
+
+    import paper_2508_18224_amd as nsa
+    import workloads as wl
+    from paper_2508_18224_amd.cost_model import effective_flops
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    nsa.lib()  # fail loudly if the HIP library is missing
+    t0 = time.time()
+    w = wl.realise(wl.named(args.workload))
+    print(f"[bench] inputs drawn in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    T = w.total_tokens
+
+    def dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, v, do = (dev(x) for x in (w.q, w.k, w.v, w.do))
+    idx = torch.from_numpy(w.idx).cuda()
+    cu = torch.from_numpy(w.cu_seqlens).cuda()
+    attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal)
+    o = torch.empty_like(q)
+    lse = torch.empty(T, w.hq, dtype=torch.float32, device="cuda")
+    grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+
+    def step():
+        attn.forward(q, k, v, idx, cu, rebuild_index=True, out=o, lse=lse)
+        attn.backward(q, k, v, o, lse, do, cu, out=grads)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    nsa.profile_enable(args.steps * 24)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    prof = nsa.profile_collect()
+    nsa.profile_enable(0)
+
+    f, b = effective_flops(T, w.hq, w.topk)
+    per_kernel = {name: tot / n for name, (tot, n) in prof.items() if n}
+    for name, avg in sorted(per_kernel.items(), key=lambda kv: -kv[1]):
+        print(f"[bench] {name:16s} {avg:9.3f} ms/launch", file=sys.stderr)
+    fwd_ms = sum(per_kernel.get(n, 0.0) for n in ("fwd_main", "fwd_merge"))
+    bwd_ms = sum(per_kernel.get(n, 0.0) for n in ("bwd_delta", "bwd_main", "bwd_dq_reduce", "bwd_dkv_reduce"))
+    idx_ms = sum(vv for n, vv in per_kernel.items() if n.startswith("index_"))
+    dom = max(per_kernel, key=per_kernel.get)
+    # algorithmic work of the dominant kernel: the MFMA contractions it performs (forward main: QK^T and PV,
+    # 4 N hq k 64 d; backward main: five such products, 2.5x)
+    dom_flops = {"fwd_main": f, "bwd_main": b}.get(dom)
+    roof = None
+    if dom_flops is not None:
+        ach = dom_flops / (per_kernel[dom] * 1e-3) / 1e12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
+                "ms_per_launch": per_kernel[dom]}
+    out = {
+        "metric": "selected-attn fwd+bwd effective TFLOP/s & ms at N=64k, g=4 (frac of MFMA peak)",
+        "value": (f + b) / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: N={T}, hq={w.hq}, hkv={w.hkv}, g={w.g}, topk={w.topk}, block=64, "
+                               f"d=128, causal, seed {w.seed}",
+                   "step": "index inversion + forward (main, merge) + backward (delta, main, dQ reduce, dK/dV reduce)"},
+        "frac_of_bf16_mfma_peak": (f + b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "ms": {"index": idx_ms, "fwd": fwd_ms, "bwd": bwd_ms, "per_kernel": per_kernel},
+        "roofline": roof,
+    }
+    if args.cpu_tokens > 0:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_tokens)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

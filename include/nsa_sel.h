@@ -87,6 +87,16 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
                 const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws,
                 size_t index_bytes, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
 
+/* Optional per-kernel timing for benchmarks (not part of the paper's method).  After
+ * nsa_sel_profile_enable(capacity > 0) every kernel launch of the calls above is bracketed by a pair of HIP
+ * events on the caller's stream, up to `capacity` launches (later ones are not recorded); capacity <= 0 turns
+ * it off and frees the events.  nsa_sel_profile_collect waits for the recorded events, writes per kernel kind
+ * its name, the summed milliseconds and the number of launches into the HOST arrays (each of max_kernels
+ * entries), clears the record and returns the number of kinds written (or a negative code).  Not thread-safe;
+ * launches of a group that consists of several small kernels (the scans) are timed as one. */
+int nsa_sel_profile_enable(int capacity);
+int nsa_sel_profile_collect(int max_kernels, const char** names, float* total_ms, int* calls);
+
 /* Static text for a return code. */
 const char* nsa_sel_strerror(int code);
 

@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
 _lib = None
 
 SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd",
-           "nsa_sel_strerror"]
+           "nsa_sel_profile_enable", "nsa_sel_profile_collect", "nsa_sel_strerror"]
 
 
 class NsaSelError(RuntimeError):
@@ -38,6 +38,9 @@ def lib():
         L.nsa_sel_index_view.argtypes = [C.POINTER(Shape), vp] + [C.POINTER(vp)] * 5 + [C.POINTER(C.c_int32)]
         L.nsa_sel_fwd.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, sz, vp]
         L.nsa_sel_bwd.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, sz, vp]
+        L.nsa_sel_profile_enable.argtypes = [C.c_int]
+        L.nsa_sel_profile_collect.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
+                                              C.POINTER(C.c_int)]
         L.nsa_sel_strerror.argtypes = [C.c_int]
         L.nsa_sel_strerror.restype = C.c_char_p
         for name in SYMBOLS[:-1]:
@@ -94,6 +97,22 @@ def nsa_sel_bwd(shape, q, k, v, o, lse, do, cu, index_ws, dq, dk, dv, ws):
     _check(lib().nsa_sel_bwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(cu),
                              _ptr(index_ws), index_ws.numel(), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(),
                              _stream()), "nsa_sel_bwd")
+
+
+def profile_enable(capacity: int):
+    _check(lib().nsa_sel_profile_enable(int(capacity)), "nsa_sel_profile_enable")
+
+
+def profile_collect():
+    """{kernel name: (total ms, launches)} of the launches recorded since the last collect."""
+    n = 32
+    names = (C.c_char_p * n)()
+    ms = (C.c_float * n)()
+    calls = (C.c_int * n)()
+    got = lib().nsa_sel_profile_collect(n, names, ms, calls)
+    if got < 0:
+        _check(got, "nsa_sel_profile_collect")
+    return {names[i].decode(): (float(ms[i]), int(calls[i])) for i in range(got)}
 
 
 class SelAttention:

@@ -296,12 +296,16 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
   }
   const int64_t rows = (int64_t)P.T * P.hq;
   const unsigned row_blocks = (unsigned)((rows + 15) / 16);
-  hipLaunchKernelGGL(k_bwd_delta, dim3(row_blocks), dim3(256), 0, st, rows, (const bf16_t*)O, (const bf16_t*)dO, delta);
+  { ProfScope ps(KID_BWD_DELTA, st);
+  hipLaunchKernelGGL(k_bwd_delta, dim3(row_blocks), dim3(256), 0, st, rows, (const bf16_t*)O, (const bf16_t*)dO, delta); }
+  { ProfScope ps(KID_BWD_MAIN, st);
   hipLaunchKernelGGL(k_bwd_main, dim3(L.bwd_units_max), dim3(256), kLdsBwdBytes, st, P, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, (const float*)delta, p.hdr, p.b_list,
-                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.qslot, (bf16_t*)dqpart, dkv_part);
+                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.qslot, (bf16_t*)dqpart, dkv_part); }
+  { ProfScope ps(KID_BWD_DQ_REDUCE, st);
   hipLaunchKernelGGL(k_bwd_dq_reduce, dim3(row_blocks), dim3(256), 0, st, P, (const bf16_t*)dqpart, p.vmask,
-                     (bf16_t*)dQ);
+                     (bf16_t*)dQ); }
+  ProfScope ps(KID_BWD_DKV_REDUCE, st);
   hipLaunchKernelGGL(k_bwd_dkv_reduce, dim3(L.n_lists, 2), dim3(256), 0, st, P, p.b_nu, p.blk_tok0, p.blk_len,
                      (const float*)dkv_part, (bf16_t*)dK, (bf16_t*)dV);
   return hipGetLastError();

@@ -77,6 +77,20 @@ struct Problem {
   float scale;
 };
 
+// ---- optional per-kernel timing (off unless nsa_sel_profile_enable was called) ---------------------------
+enum KernelId {
+  KID_INDEX_PREP = 0, KID_INDEX_ZERO, KID_INDEX_HIST, KID_INDEX_SCAN, KID_INDEX_SCATTER, KID_INDEX_FINALIZE,
+  KID_INDEX_UNITS, KID_FWD_MAIN, KID_FWD_MERGE, KID_BWD_DELTA, KID_BWD_MAIN, KID_BWD_DQ_REDUCE, KID_BWD_DKV_REDUCE,
+  KID_COUNT
+};
+// Records a HIP event on `st` at construction and destruction when profiling is on; does nothing otherwise.
+struct ProfScope {
+  int slot;
+  hipStream_t st;
+  ProfScope(int kid, hipStream_t stream);
+  ~ProfScope();
+};
+
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) -------------------------------------
 hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
                               hipStream_t st);

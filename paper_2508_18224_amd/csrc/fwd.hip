@@ -205,10 +205,12 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
 hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
                       const void* index_ws, void* opart, float* lse_part, void* O, float* LSE, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
+  { ProfScope ps(KID_FWD_MAIN, st);
   hipLaunchKernelGGL(k_fwd_main, dim3(L.fwd_units_max), dim3(256), 0, st, P, (const bf16_t*)Q, (const bf16_t*)K,
                      (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.qslot,
-                     (bf16_t*)opart, lse_part);
+                     (bf16_t*)opart, lse_part); }
   const int64_t rows = (int64_t)P.T * P.hq;
+  ProfScope ps(KID_FWD_MERGE, st);
   hipLaunchKernelGGL(k_fwd_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P, (const bf16_t*)opart,
                      (const float*)lse_part, p.vmask, (bf16_t*)O, LSE);
   return hipGetLastError();

@@ -290,25 +290,33 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
         hipFuncSetAttribute((const void*)k_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_scat);
     if (e != hipSuccess) return e;
   }
+  { ProfScope ps(KID_INDEX_PREP, st);
   hipLaunchKernelGGL(k_prep, dim3(1), dim3(256), 0, st, cu, L.nseq, L.T, L.b_cap, p.blk_base, p.blk_tok0, p.blk_len,
-                     p.hdr);
+                     p.hdr); }
   const int64_t nc = L.n_counters + 1;
+  { ProfScope ps(KID_INDEX_ZERO, st);
   hipLaunchKernelGGL(k_zero, dim3((unsigned)((nc + 1023) / 1024 > 4096 ? 4096 : (nc + 1023) / 1024)), dim3(256), 0, st,
-                     p.chunk_off, nc);
+                     p.chunk_off, nc); }
+  { ProfScope ps(KID_INDEX_HIST, st);
   hipLaunchKernelGGL(k_hist, dim3(L.n_chunks, L.hkv), dim3(256), lds_hist, st, idx, cu, p.blk_base, L.nseq, L.T, L.hkv,
-                     L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off);
-  scan_exclusive(p.chunk_off, nc, p.scan_tmp, st);
+                     L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off); }
+  { ProfScope ps(KID_INDEX_SCAN, st);
+  scan_exclusive(p.chunk_off, nc, p.scan_tmp, st); }
+  { ProfScope ps(KID_INDEX_SCATTER, st);
   hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
-                     L.hkv, L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask);
+                     L.hkv, L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask); }
   const int nl1 = L.n_lists + 1;
+  { ProfScope ps(KID_INDEX_FINALIZE, st);
   hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.chunk_off, L.n_lists, L.n_chunks, p.cnt,
-                     p.off, p.f_nu, p.b_nu, p.hdr);
+                     p.off, p.f_nu, p.b_nu, p.hdr); }
+  { ProfScope ps(KID_INDEX_SCAN, st);
   scan_exclusive(p.f_nu, nl1, p.scan_tmp, st);
-  scan_exclusive(p.b_nu, nl1, p.scan_tmp, st);
+  scan_exclusive(p.b_nu, nl1, p.scan_tmp, st); }
+  { ProfScope ps(KID_INDEX_UNITS, st);
   hipLaunchKernelGGL(k_units, dim3((L.n_lists + 255) / 256), dim3(256), 0, st, p.f_nu, p.off, L.n_lists, kFwdUnit,
                      p.f_list, p.f_start, p.hdr + HDR_FUNITS);
   hipLaunchKernelGGL(k_units, dim3((L.n_lists + 255) / 256), dim3(256), 0, st, p.b_nu, p.off, L.n_lists, kBwdUnit,
-                     p.b_list, p.b_start, p.hdr + HDR_BUNITS);
+                     p.b_list, p.b_start, p.hdr + HDR_BUNITS); }
   return hipGetLastError();
 }
 

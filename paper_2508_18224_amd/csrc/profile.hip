@@ -1,0 +1,73 @@
+// Optional per-kernel timing with HIP events on the caller's stream (see nsa_sel_profile_enable in nsa_sel.h).
+#include <vector>
+
+#include "common.h"
+
+namespace nsa {
+namespace {
+struct Rec {
+  int kid;
+  hipEvent_t a, b;
+};
+std::vector<Rec> g_recs;
+int g_used = 0;
+bool g_on = false;
+const char* const kNames[KID_COUNT] = {"index_prep", "index_zero", "index_hist", "index_scan", "index_scatter",
+                                       "index_finalize", "index_units", "fwd_main", "fwd_merge", "bwd_delta",
+                                       "bwd_main", "bwd_dq_reduce", "bwd_dkv_reduce"};
+}  // namespace
+
+ProfScope::ProfScope(int kid, hipStream_t stream) : slot(-1), st(stream) {
+  if (!g_on || g_used >= (int)g_recs.size()) return;
+  slot = g_used++;
+  g_recs[slot].kid = kid;
+  (void)hipEventRecord(g_recs[slot].a, st);
+}
+ProfScope::~ProfScope() {
+  if (slot >= 0) (void)hipEventRecord(g_recs[slot].b, st);
+}
+}  // namespace nsa
+
+using namespace nsa;
+
+extern "C" {
+
+int nsa_sel_profile_enable(int capacity) {
+  for (auto& r : g_recs) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  g_recs.clear();
+  g_used = 0;
+  g_on = false;
+  if (capacity <= 0) return NSA_SEL_OK;
+  g_recs.resize(capacity);
+  for (auto& r : g_recs) {
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return NSA_SEL_EHIP;
+  }
+  g_on = true;
+  return NSA_SEL_OK;
+}
+
+int nsa_sel_profile_collect(int max_kernels, const char** names, float* total_ms, int* calls) {
+  if (max_kernels < 0 || (max_kernels > 0 && (!names || !total_ms || !calls))) return NSA_SEL_EINVAL;
+  const int n = max_kernels < KID_COUNT ? max_kernels : (int)KID_COUNT;
+  for (int i = 0; i < n; ++i) {
+    names[i] = kNames[i];
+    total_ms[i] = 0.f;
+    calls[i] = 0;
+  }
+  for (int i = 0; i < g_used; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(g_recs[i].b) != hipSuccess) return NSA_SEL_EHIP;
+    if (hipEventElapsedTime(&ms, g_recs[i].a, g_recs[i].b) != hipSuccess) return NSA_SEL_EHIP;
+    if (g_recs[i].kid < n) {
+      total_ms[g_recs[i].kid] += ms;
+      calls[g_recs[i].kid] += 1;
+    }
+  }
+  g_used = 0;
+  return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+"""Host-side checks that need no GPU: the C ABI exports what the header declares, argument validation, and the
+paper's cost model against the two ratios the paper prints."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lib():
+    import paper_2508_18224_amd as nsa
+    return nsa, nsa.lib()
+
+
+def test_library_exports_every_declared_symbol():
+    nsa, L = _lib()
+    header = open(os.path.join(ROOT, "include", "nsa_sel.h")).read()
+    declared = set(re.findall(r"\b(nsa_sel_[a-z_]+)\s*\(", header))
+    assert declared == set(nsa.SYMBOLS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_shape_validation_happens_on_the_host():
+    nsa, L = _lib()
+    ok = nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 1, 0.0, 0)
+    f, b, i = nsa.workspace_bytes(ok)
+    assert f >= 4096 * 8 * 16 * 128 * 2 and b > f and i > 0
+    bad = [
+        (nsa.Shape(4096, 1, 8, 3, 128, 64, 16, 1, 0.0, 0), -1),     # hq % hkv
+        (nsa.Shape(4096, 1, 18, 2, 128, 64, 16, 1, 0.0, 0), -1),    # g = 9
+        (nsa.Shape(4096, 0, 8, 2, 128, 64, 16, 1, 0.0, 0), -1),     # nseq
+        (nsa.Shape(4096, 1, 8, 2, 64, 64, 16, 1, 0.0, 0), -2),      # d
+        (nsa.Shape(4096, 1, 8, 2, 128, 128, 16, 1, 0.0, 0), -2),    # block
+        (nsa.Shape(4096, 1, 8, 2, 128, 64, 33, 1, 0.0, 0), -2),     # topk
+        (nsa.Shape(2 ** 30, 1, 8, 2, 128, 64, 16, 1, 0.0, 0), -2),  # too large
+    ]
+    sz = ctypes.c_size_t()
+    for shape, code in bad:
+        assert L.nsa_sel_workspace_bytes(ctypes.byref(shape), ctypes.byref(sz), None, None) == code
+    # null pointers are rejected before anything is launched (no GPU is touched)
+    assert L.nsa_sel_build_index(ctypes.byref(ok), None, None, None, 0, None) == -1
+    assert L.nsa_sel_fwd(ctypes.byref(ok), None, None, None, None, None, 1, None, 0, None, None, None, 0, None) == -1
+    assert b"workspace" in L.nsa_sel_strerror(-3)
+
+
+def test_paper_cost_ratios():
+    from paper_2508_18224_amd import cost_model as cm
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "paper_cost_ratios.txt"))
+            if l.strip() and not l.startswith("#")]
+    for g, B_K, T, mem_pct, flop_pct in rows:
+        g, B_K, T = int(g), int(B_K), int(T)
+        N, h_K, d = 65536, 8, 128
+        h = g * h_K
+        mem = cm.fsa_total_bytes(N, h, h_K, d, T) / cm.nsa_bytes(N, h, h_K, d, B_K, T)
+        fl = cm.fsa_total_flops(N, h, h_K, d, B_K, T) / cm.nsa_flops(N, h_K, d, B_K, T)
+        assert abs(100 * mem - float(mem_pct)) < 0.06
+        assert abs(100 * fl - float(flop_pct)) < 0.06
+    f, b = cm.effective_flops(65536, 32, 16)
+    assert f == 4.0 * 65536 * 32 * 16 * 64 * 128 and b == 2.5 * f
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2508_18224_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text, fn
