@@ -55,7 +55,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="headline")
-    ap.add_argument("--cpu-tokens", type=int, default=192, help="query tokens of the CPU-oracle sample (0: skip)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch the library's 1 GiB copy kernel once (for scaling rocprofv3 byte counters)")
+    ap.add_argument("--cpu-tokens", type=int, default=1280, help="query tokens of the CPU-oracle sample (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over KV heads with no "
@@ -89,6 +91,12 @@ def main():
         attn.forward(q, k, v, idx, cu, rebuild_index=True, out=o, lse=lse)
         attn.backward(q, k, v, o, lse, do, cu, out=grads)
 
+    if args.calibrate:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        nsa.calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -97,6 +97,11 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
 int nsa_sel_profile_enable(int capacity);
 int nsa_sel_profile_collect(int max_kernels, const char** names, float* total_ms, int* calls);
 
+/* Measurement aid: a plain streaming copy kernel (k_calib_copy) that reads `bytes` and writes `bytes`
+ * (device pointers, bytes a multiple of 16).  Hardware HBM byte counters of the attention kernels are scaled
+ * by what the same counters report for this kernel of known traffic. */
+int nsa_sel_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Static text for a return code. */
 const char* nsa_sel_strerror(int code);
 

@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
 _lib = None
 
 SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd",
-           "nsa_sel_profile_enable", "nsa_sel_profile_collect", "nsa_sel_strerror"]
+           "nsa_sel_profile_enable", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_strerror"]
 
 
 class NsaSelError(RuntimeError):
@@ -41,6 +41,7 @@ def lib():
         L.nsa_sel_profile_enable.argtypes = [C.c_int]
         L.nsa_sel_profile_collect.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                               C.POINTER(C.c_int)]
+        L.nsa_sel_calibration_copy.argtypes = [vp, vp, sz, vp]
         L.nsa_sel_strerror.argtypes = [C.c_int]
         L.nsa_sel_strerror.restype = C.c_char_p
         for name in SYMBOLS[:-1]:
@@ -113,6 +114,11 @@ def profile_collect():
     if got < 0:
         _check(got, "nsa_sel_profile_collect")
     return {names[i].decode(): (float(ms[i]), int(calls[i])) for i in range(got)}
+
+
+def calibration_copy(dst: torch.Tensor, src: torch.Tensor):
+    nbytes = src.numel() * src.element_size()
+    _check(lib().nsa_sel_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream()), "nsa_sel_calibration_copy")
 
 
 class SelAttention:

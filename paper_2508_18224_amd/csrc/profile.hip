@@ -30,7 +30,23 @@ ProfScope::~ProfScope() {
 
 using namespace nsa;
 
+// Plain streaming copy of 16-byte words: a kernel of known HBM traffic (bytes read + bytes written) against
+// which hardware byte counters can be scaled.
+__global__ void __launch_bounds__(256) k_calib_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+
 extern "C" {
+
+int nsa_sel_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || (bytes & 15) != 0) return NSA_SEL_EINVAL;
+  if (bytes == 0) return NSA_SEL_OK;
+  hipLaunchKernelGGL(k_calib_copy, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
+                     bytes / 16);
+  return hipGetLastError() == hipSuccess ? NSA_SEL_OK : NSA_SEL_EHIP;
+}
 
 int nsa_sel_profile_enable(int capacity) {
   for (auto& r : g_recs) {
