@@ -52,6 +52,7 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.qlist = take(4 * (size_t)(L.p_max + 1));
   L.qslot = take(4 * (size_t)(L.p_max + 1));
   L.vmask = take(4 * ((size_t)L.T * L.hkv + 1));
+  L.slotpos = take(4 * (size_t)(L.p_max + 1));
   L.f_nu = take(4 * (size_t)(L.n_lists + 1));
   L.f_list = take(4 * (size_t)(L.fwd_units_max + 1));
   L.f_start = take(4 * (size_t)(L.fwd_units_max + 1));

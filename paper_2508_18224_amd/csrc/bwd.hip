@@ -186,7 +186,7 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[sp], dqacc[db], 0, 0, 0);
       }
     if (valid) {
-      bf16_t* dst = dqpart + ((grow * P.topk + slot) * kD) + 4 * qh;
+      bf16_t* dst = dqpart + ((size_t)e0 * P.g + r) * kD + 4 * qh;  // compact: list position * g + head
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -233,23 +233,33 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 
 __global__ void __launch_bounds__(256)
 k_bwd_dq_reduce(Problem P, const bf16_t* __restrict__ dqpart, const uint32_t* __restrict__ vmask,
-                bf16_t* __restrict__ dQ) {
+                const int32_t* __restrict__ slotpos, bf16_t* __restrict__ dQ) {
   const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   const int sub = threadIdx.x & 15;
   if (row >= (int64_t)P.T * P.hq) return;
   const int t = (int)(row / P.hq);
   const int h = (int)(row - (int64_t)t * P.hq);
-  const uint32_t vm = vmask[(size_t)t * P.hkv + h / P.g];
+  const int j = h / P.g, hh = h - j * P.g;
+  const uint32_t vm = vmask[(size_t)t * P.hkv + j];
+  const int32_t* sp = slotpos + ((size_t)t * P.hkv + j) * P.topk;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  const bf16_t* prow = dqpart + row * P.topk * kD + 8 * sub;
-  for (int m = 0; m < P.topk; ++m)
-    if ((vm >> m) & 1u) {
-      const uint4 x = *reinterpret_cast<const uint4*>(prow + (size_t)m * kD);
-      acc[0] += bf16_lo(x.x); acc[1] += bf16_hi(x.x);
-      acc[2] += bf16_lo(x.y); acc[3] += bf16_hi(x.y);
-      acc[4] += bf16_lo(x.z); acc[5] += bf16_hi(x.z);
-      acc[6] += bf16_lo(x.w); acc[7] += bf16_hi(x.w);
+  for (int m0 = 0; m0 < P.topk; m0 += 16) {  // 16 independent 256-byte gathers in flight per row
+    uint4 x[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = m0 + i;
+      const bool on = m < P.topk && ((vm >> m) & 1u);
+      x[i] = on ? *reinterpret_cast<const uint4*>(dqpart + ((size_t)sp[on ? m : 0] * P.g + hh) * kD + 8 * sub)
+                : make_uint4(0, 0, 0, 0);
     }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      acc[0] += bf16_lo(x[i].x); acc[1] += bf16_hi(x[i].x);
+      acc[2] += bf16_lo(x[i].y); acc[3] += bf16_hi(x[i].y);
+      acc[4] += bf16_lo(x[i].z); acc[5] += bf16_hi(x[i].z);
+      acc[6] += bf16_lo(x[i].w); acc[7] += bf16_hi(x[i].w);
+    }
+  }
   uint4 o;
   o.x = pack_bf16x2(acc[0], acc[1]);
   o.y = pack_bf16x2(acc[2], acc[3]);
@@ -304,7 +314,7 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
                      p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.qslot, (bf16_t*)dqpart, dkv_part); }
   { ProfScope ps(KID_BWD_DQ_REDUCE, st);
   hipLaunchKernelGGL(k_bwd_dq_reduce, dim3(row_blocks), dim3(256), 0, st, P, (const bf16_t*)dqpart, p.vmask,
-                     (bf16_t*)dQ); }
+                     p.slotpos, (bf16_t*)dQ); }
   ProfScope ps(KID_BWD_DKV_REDUCE, st);
   hipLaunchKernelGGL(k_bwd_dkv_reduce, dim3(L.n_lists, 2), dim3(256), 0, st, P, p.b_nu, p.blk_tok0, p.blk_len,
                      (const float*)dkv_part, (bf16_t*)dK, (bf16_t*)dV);

@@ -25,7 +25,7 @@ struct IndexLayout {
   int64_t n_counters;   // n_lists * n_chunks
   int64_t p_max;        // T * hkv * topk
   int32_t fwd_units_max, bwd_units_max;
-  size_t hdr, blk_base, blk_tok0, blk_len, chunk_off, cnt, off, qlist, qslot, vmask;
+  size_t hdr, blk_base, blk_tok0, blk_len, chunk_off, cnt, off, qlist, qslot, vmask, slotpos;
   size_t f_nu, f_list, f_start, b_nu, b_list, b_start, scan_tmp;
   size_t total;
 };
@@ -44,6 +44,7 @@ struct IndexPtrs {
   int32_t* qlist;
   int32_t* qslot;
   uint32_t* vmask;
+  int32_t* slotpos;  // [T, hkv, topk]: position in qlist of the entry a kept column produced
   int32_t *f_nu, *f_list, *f_start, *b_nu, *b_list, *b_start;
   int32_t* scan_tmp;
 };
@@ -61,6 +62,7 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
   r.qlist = (int32_t*)(p + L.qlist);
   r.qslot = (int32_t*)(p + L.qslot);
   r.vmask = (uint32_t*)(p + L.vmask);
+  r.slotpos = (int32_t*)(p + L.slotpos);
   r.f_nu = (int32_t*)(p + L.f_nu);
   r.f_list = (int32_t*)(p + L.f_list);
   r.f_start = (int32_t*)(p + L.f_start);

@@ -10,14 +10,16 @@
 //   exchange with lane ^ 32 completes max and sum).  Because S^T leaves each lane holding keys of ONE query,
 //   the probabilities are already in B-operand layout for the PV product; no transposition of P is needed.
 //   The result of a (token, head, block) triple is a partial output normalised by its own sum, plus the
-//   log-sum-exp of its 64 scores; both go to the slot of the workspace given by the entry's idx column.
+//   log-sum-exp of its 64 scores; both are stored at the entry's own position in the list order (the compact
+//   buffer the paper addresses through O_i), so a tile's 32 rows are one contiguous 8 KB write.
 // k_fwd_merge: per (token, head) combines the kept slots: LSE = ln sum_s exp(lse_s), O = sum_s exp(lse_s-LSE) O_s.
 //   This replaces the paper's separate statistics pre-pass: per-slot (max, sum) make the merge exact.
 #include "common.h"
 
 namespace nsa {
 
-constexpr int kVtStride = 72;  // bf16 per row of the transposed V tile in LDS: 64 keys + 8 pad
+constexpr int kVtStride = 72;     // bf16 per row of the transposed V tile in LDS: 64 keys + 8 pad
+constexpr int kTileStride = 136;  // bf16 per row of a wave's private 32-row tile in LDS: 128 + 8 pad
 
 // Place of a key in the contraction order of the PV product.  The accumulator of a 32x32 MFMA gives lane
 // (col, q) the rows 8a + 4q + c (a, c in 0..3) of each 32-key half mb; contraction step s' = 2 mb + a / 2 takes
@@ -27,6 +29,14 @@ __device__ __forceinline__ int key_pos(int key) {
   return 16 * (2 * mb + (a >> 1)) + 8 * q + 4 * (a & 1) + c;
 }
 
+// Orders a wavefront's own LDS traffic (no cross-wave meaning): a wave-private tile is written by some lanes and
+// read by others of the same wave.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 __global__ void __launch_bounds__(256)
 k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
            const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
@@ -34,6 +44,8 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
            const int32_t* __restrict__ qlist, const int32_t* __restrict__ qslot, bf16_t* __restrict__ opart,
            float* __restrict__ lse_part) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kD * kVtStride];
+  __shared__ __attribute__((aligned(16))) bf16_t tiles[4][32 * kTileStride];
+  __shared__ int2 ent[kFwdUnit];  // (token, slot) of the unit's list entries
   const int u = blockIdx.x;
   if (u >= hdr[HDR_FUNITS]) return;
   const int L = u_list[u];
@@ -43,6 +55,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int ne = min(kFwdUnit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
+  const int crow = lane >> 4, cchunk = (lane & 15) * 8;  // coalesced layout: 16 lanes per row, 4 rows per access
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
   {  // V_i -> LDS, transposed and key-permuted
@@ -63,6 +76,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
     for (int s = 0; s < 8; ++s) kf[mb][s] = key < blen ? *reinterpret_cast<const bf16x8*>(src + 16 * s) : zero8;
   }
+  for (int i = tid; i < ne; i += 256) ent[i] = make_int2(qlist[e0 + i], qslot[e0 + i]);
   __syncthreads();
   bf16x8 vf[4][4];
 #pragma unroll
@@ -72,19 +86,37 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       vf[db][sp] = *reinterpret_cast<const bf16x8*>(&Vt[(32 * db + col) * kVtStride + 16 * sp + 8 * qh]);
 
   const int rows_total = ne * P.g;
+  const int n_tiles = (rows_total + 31) >> 5;
+  if (wave >= n_tiles) return;  // no block-wide barrier below this point
   const float c2 = P.scale * 1.4426950408889634f;  // scores in the log2 domain
-  for (int tile = wave; tile * 32 < rows_total; tile += 4) {
-    const int r = tile * 32 + col;
-    const bool valid = r < rows_total;
-    const int e = valid ? r / P.g : 0;
-    const int hh = valid ? r - e * P.g : 0;
-    const int t = qlist[e0 + e];
-    const int slot = qslot[e0 + e];
-    const int h = j * P.g + hh;
-    const bf16_t* qrow = Q + ((size_t)t * P.hq + h) * kD + 8 * qh;
+  bf16_t* tile_lds = tiles[wave];
+  const size_t hq = P.hq;
+  const int hbase = j * P.g;
+
+  // gather the 32 rows of Q of a tile in coalesced form (a row = 16 lanes x 16 bytes, 4 rows per access)
+  auto issue_q = [&](int tile, uint4 (&qc)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = tile * 32 + 4 * i + crow;
+      if (r < rows_total) {
+        const int e = r / P.g;
+        qc[i] = *reinterpret_cast<const uint4*>(Q + ((size_t)ent[e].x * hq + hbase + (r - e * P.g)) * kD + cchunk);
+      } else {
+        qc[i] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+
+  auto do_tile = [&](int tile, uint4 (&qc)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      *reinterpret_cast<uint4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
+    wave_sync();
     bf16x8 qf[8];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) qf[s] = valid ? *reinterpret_cast<const bf16x8*>(qrow + 16 * s) : zero8;
+    for (int s = 0; s < 8; ++s)
+      qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kTileStride + 16 * s + 8 * qh]);
+    if (tile + 8 < n_tiles) issue_q(tile + 8, qc);  // two of this wave's tiles ahead: rows fly during compute
 
     f32x16 sacc[2];
 #pragma unroll
@@ -98,6 +130,9 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][s], qf[s], sacc[mb], 0, 0, 0);
 
     // keys [0, lim) of the block are visible to this row
+    const int r = tile * 32 + col;
+    const bool valid = r < rows_total;
+    const int t = valid ? ent[r / P.g].x : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
     float m = -INFINITY;
@@ -140,66 +175,107 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       for (int db = 0; db < 4; ++db)
         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][sp], pf[sp], oacc[db], 0, 0, 0);
 
-    if (valid) {
-      const float inv = 1.f / l;
-      const size_t prow = ((size_t)t * P.hq + h) * P.topk + slot;
-      bf16_t* dst = opart + prow * kD + 4 * qh;
+    // normalised partial rows -> wave tile in LDS -> coalesced 256-byte row stores
+    const float inv = valid ? 1.f / l : 0.f;
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          uint2 w;
-          w.x = pack_bf16x2(oacc[db][4 * a + 0] * inv, oacc[db][4 * a + 1] * inv);
-          w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
-          *reinterpret_cast<uint2*>(dst + 32 * db + 8 * a) = w;
-        }
-      if (qh == 0) lse_part[prow] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+      for (int a = 0; a < 4; ++a) {
+        uint2 w;
+        w.x = pack_bf16x2(oacc[db][4 * a + 0] * inv, oacc[db][4 * a + 1] * inv);
+        w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
+        *reinterpret_cast<uint2*>(&tile_lds[col * kTileStride + 32 * db + 8 * a + 4 * qh]) = w;
+      }
+    wave_sync();
+    // partial rows live at the list position of their entry: a tile's 32 rows are one contiguous 8 KB run
+    const size_t prow0 = (size_t)e0 * P.g + (size_t)tile * 32;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = 4 * i + crow;
+      if (tile * 32 + row < rows_total)
+        *reinterpret_cast<uint4*>(opart + (prow0 + row) * kD + cchunk) =
+            *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]);
     }
+    if (valid && qh == 0) lse_part[prow0 + col] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    wave_sync();
+  };
+
+  uint4 qa[8], qb[8];
+  issue_q(wave, qa);
+  if (wave + 4 < n_tiles) issue_q(wave + 4, qb);
+  for (int tile = wave; tile < n_tiles; tile += 8) {
+    do_tile(tile, qa);
+    if (tile + 4 < n_tiles) do_tile(tile + 4, qb);
   }
 }
 
-// 16 lanes per (token, head) row, 8 output channels per lane.
+// 16 lanes per (token, head) row, 8 output channels per lane.  Slots are taken 16 at a time: positions, partial
+// log-sum-exps and partial rows of a batch are all requested before any of them is used, so one row keeps up to
+// 16 independent 256-byte gathers in flight; batches are chained by the usual running-max rescale.
 __global__ void __launch_bounds__(256)
 k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict__ lse_part,
-            const uint32_t* __restrict__ vmask, bf16_t* __restrict__ O, float* __restrict__ LSE) {
+            const uint32_t* __restrict__ vmask, const int32_t* __restrict__ slotpos, bf16_t* __restrict__ O,
+            float* __restrict__ LSE) {
   const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   const int sub = threadIdx.x & 15;
   if (row >= (int64_t)P.T * P.hq) return;
   const int t = (int)(row / P.hq);
   const int h = (int)(row - (int64_t)t * P.hq);
-  const uint32_t vm = vmask[(size_t)t * P.hkv + h / P.g];
+  const int j = h / P.g, hh = h - j * P.g;
+  const uint32_t vm = vmask[(size_t)t * P.hkv + j];
   bf16_t* orow = O + row * kD + 8 * sub;
   if (vm == 0u) {
     *reinterpret_cast<uint4*>(orow) = make_uint4(0, 0, 0, 0);
     if (sub == 0) LSE[row] = -INFINITY;
     return;
   }
-  const float* lp = lse_part + row * P.topk;
-  float M = -INFINITY;
-  for (int m = 0; m < P.topk; ++m)
-    if ((vm >> m) & 1u) M = fmaxf(M, lp[m]);
-  float Ls = 0.f;
-  for (int m = 0; m < P.topk; ++m)
-    if ((vm >> m) & 1u) Ls += __expf(lp[m] - M);
-  const float lse = M + __logf(Ls);
+  const int32_t* sp = slotpos + ((size_t)t * P.hkv + j) * P.topk;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  const bf16_t* prow = opart + row * P.topk * kD + 8 * sub;
-  for (int m = 0; m < P.topk; ++m)
-    if ((vm >> m) & 1u) {
-      const float w = __expf(lp[m] - lse);
-      const uint4 x = *reinterpret_cast<const uint4*>(prow + (size_t)m * kD);
-      acc[0] += w * bf16_lo(x.x); acc[1] += w * bf16_hi(x.x);
-      acc[2] += w * bf16_lo(x.y); acc[3] += w * bf16_hi(x.y);
-      acc[4] += w * bf16_lo(x.z); acc[5] += w * bf16_hi(x.z);
-      acc[6] += w * bf16_lo(x.w); acc[7] += w * bf16_hi(x.w);
+  float M = -INFINITY, Ls = 0.f;
+  for (int m0 = 0; m0 < P.topk; m0 += 16) {
+    size_t pr[16];
+    uint4 x[16];
+    float ls[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = m0 + i;
+      const bool on = m < P.topk && ((vm >> m) & 1u);
+      pr[i] = on ? (size_t)sp[m] * P.g + hh : (size_t)0;
     }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = m0 + i;
+      const bool on = m < P.topk && ((vm >> m) & 1u);
+      x[i] = on ? *reinterpret_cast<const uint4*>(opart + pr[i] * kD + 8 * sub) : make_uint4(0, 0, 0, 0);
+      ls[i] = on ? lse_part[pr[i]] : -INFINITY;
+    }
+    float Mb = M;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) Mb = fmaxf(Mb, ls[i]);
+    if (Mb == -INFINITY) continue;  // no kept slot in this batch or before it
+    const float rescale = __expf(M - Mb);  // 0 on the first non-empty batch
+    Ls *= rescale;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] *= rescale;
+    M = Mb;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float w = __expf(ls[i] - M);  // exp(-inf) = 0 for slots that are off
+      Ls += w;
+      acc[0] += w * bf16_lo(x[i].x); acc[1] += w * bf16_hi(x[i].x);
+      acc[2] += w * bf16_lo(x[i].y); acc[3] += w * bf16_hi(x[i].y);
+      acc[4] += w * bf16_lo(x[i].z); acc[5] += w * bf16_hi(x[i].z);
+      acc[6] += w * bf16_lo(x[i].w); acc[7] += w * bf16_hi(x[i].w);
+    }
+  }
+  const float inv = 1.f / Ls;
   uint4 o;
-  o.x = pack_bf16x2(acc[0], acc[1]);
-  o.y = pack_bf16x2(acc[2], acc[3]);
-  o.z = pack_bf16x2(acc[4], acc[5]);
-  o.w = pack_bf16x2(acc[6], acc[7]);
+  o.x = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+  o.y = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+  o.z = pack_bf16x2(acc[4] * inv, acc[5] * inv);
+  o.w = pack_bf16x2(acc[6] * inv, acc[7] * inv);
   *reinterpret_cast<uint4*>(orow) = o;
-  if (sub == 0) LSE[row] = lse;
+  if (sub == 0) LSE[row] = M + __logf(Ls);
 }
 
 hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
@@ -212,7 +288,7 @@ hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, con
   const int64_t rows = (int64_t)P.T * P.hq;
   ProfScope ps(KID_FWD_MERGE, st);
   hipLaunchKernelGGL(k_fwd_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P, (const bf16_t*)opart,
-                     (const float*)lse_part, p.vmask, (bf16_t*)O, LSE);
+                     (const float*)lse_part, p.vmask, p.slotpos, (bf16_t*)O, LSE);
   return hipGetLastError();
 }
 

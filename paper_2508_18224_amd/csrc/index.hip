@@ -1,7 +1,9 @@
 // Index inversion for selected-block attention: from the selection table idx[token, kv head, slot] build, for
 // every (kv head, KV block), the ascending list of query tokens that select it (the paper's index tensor I_i,
 // Sec. 3.2 "FSA token selection kernel") together with the slot each entry came from (which fixes its place
-// in the partial-result buffer, the role of the paper's O_i), plus the work-unit tables of the attention
+// in the selection table) and, per kept (token, kv head, slot), the entry's position in its list, which is
+// where its partial result lives in the compact partial buffers (the role of the paper's O_i), plus the
+// work-unit tables of the attention
 // kernels.  Pipeline: per-(kv head, block, token chunk) histogram -> exclusive scan -> ordered scatter.
 // The scatter is deterministic: a chunk is walked by one wavefront in rounds of 64 tokens, and a token's rank
 // inside a round is a popcount over a 64-bit membership mask, so no ordering depends on atomics.
@@ -185,7 +187,8 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
                                                 const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
                                                 int causal, int b_cap, int n_chunks,
                                                 const int32_t* __restrict__ chunk_off, int32_t* __restrict__ qlist,
-                                                int32_t* __restrict__ qslot, uint32_t* __restrict__ vmask) {
+                                                int32_t* __restrict__ qslot, uint32_t* __restrict__ vmask,
+                                                int32_t* __restrict__ slotpos) {
   extern __shared__ int32_t lds[];
   unsigned long long* mask = reinterpret_cast<unsigned long long*>(lds);
   int32_t* cursor = lds + 2 * b_cap;
@@ -226,6 +229,7 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
         const int pos = cursor[w] + __popcll(mask[w] & below);
         qlist[pos] = t;
         qslot[pos] = m;
+        slotpos[((size_t)t * hkv + j) * k + m] = pos;
       }
     __syncthreads();
     // C: the lowest member of each touched block advances its cursor and clears the mask
@@ -304,7 +308,7 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
   scan_exclusive(p.chunk_off, nc, p.scan_tmp, st); }
   { ProfScope ps(KID_INDEX_SCATTER, st);
   hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
-                     L.hkv, L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask); }
+                     L.hkv, L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask, p.slotpos); }
   const int nl1 = L.n_lists + 1;
   { ProfScope ps(KID_INDEX_FINALIZE, st);
   hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.chunk_off, L.n_lists, L.n_chunks, p.cnt,
