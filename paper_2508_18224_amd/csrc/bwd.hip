@@ -18,20 +18,33 @@
 
 namespace nsa {
 
-constexpr int kKtStride = 72;    // bf16 per row of K^T in LDS (64 keys + 8 pad)
-constexpr int kRowStride = 136;  // bf16 per row of the Q / dO / P^T / dS^T tiles in LDS (128 + 8 pad)
+constexpr int kRowStride = 136;  // bf16 per row of the K / V / Q / dO / P^T / dS^T tiles in LDS (128 + 8 pad)
 constexpr int kTileRows = 128;
 
-constexpr int kLdsKt = 0;
-constexpr int kLdsQ = kLdsKt + kD * kKtStride * 2;
+constexpr int kLdsK = 0;
+constexpr int kLdsV = kLdsK + kBlock * kRowStride * 2;
+constexpr int kLdsQ = kLdsV + kBlock * kRowStride * 2;
 constexpr int kLdsDO = kLdsQ + kTileRows * kRowStride * 2;
 constexpr int kLdsPt = kLdsDO + kTileRows * kRowStride * 2;
 constexpr int kLdsDSt = kLdsPt + kBlock * kRowStride * 2;
-constexpr int kLdsBwdBytes = kLdsDSt + kBlock * kRowStride * 2;  // 122880
+constexpr int kLdsEnt = kLdsDSt + kBlock * kRowStride * 2;
+constexpr int kLdsBwdBytes = kLdsEnt + kBwdUnit * 4;  // 147456
 
-__device__ __forceinline__ int key_pos_bwd(int key) {  // same contraction order as the forward's PV product
-  const int mb = key >> 5, a = (key >> 3) & 3, q = (key >> 2) & 1, c = key & 3;
-  return 16 * (2 * mb + (a >> 1)) + 8 * q + 4 * (a & 1) + c;
+// ds_read_b64_tr_b16: every lane passes the address of 8 bytes (four 16-bit elements); within each group of
+// 16 lanes, lane i receives element (i % 4) of the 8 bytes addressed by lanes 4e + i / 4, for e = 0..3.  With
+// lane s of a group pointing at row (s / 4), columns 4 (s % 4).. of a row-major tile, lane i gets column i of
+// four consecutive rows: the MFMA operand layout (lane = column, elements = rows) without a transposed copy.
+__device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)p);
+  return __builtin_bit_cast(bf16x4, v);
+}
+
+__device__ __forceinline__ void wave_sync_bwd() {  // orders a wavefront's own LDS traffic
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 __global__ void __launch_bounds__(256)
@@ -58,14 +71,15 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
            const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
            const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
-           const int32_t* __restrict__ qlist, const int32_t* __restrict__ qslot, bf16_t* __restrict__ dqpart,
-           float* __restrict__ dkv_part) {
+           const int32_t* __restrict__ qlist, bf16_t* __restrict__ dqpart, float* __restrict__ dkv_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* Kt = reinterpret_cast<bf16_t*>(smem + kLdsKt);
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kLdsK);
+  bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kLdsV);
   bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + kLdsQ);
   bf16_t* dOs = reinterpret_cast<bf16_t*>(smem + kLdsDO);
   bf16_t* Pt = reinterpret_cast<bf16_t*>(smem + kLdsPt);
   bf16_t* dSt = reinterpret_cast<bf16_t*>(smem + kLdsDSt);
+  int32_t* ent = reinterpret_cast<int32_t*>(smem + kLdsEnt);
 
   const int u = blockIdx.x;
   if (u >= hdr[HDR_BUNITS]) return;
@@ -76,29 +90,21 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int ne = min(kBwdUnit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
+  const int crow = lane >> 4, cchunk = (lane & 15) * 8;  // coalesced layout: 16 lanes per row, 4 rows per access
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-  {  // K_i -> LDS, transposed and key-permuted (A operand of dQ^T = K^T dS^T)
-    const int key = tid >> 2, d0 = (tid & 3) * 32, pos = key_pos_bwd(key);
-    const bf16_t* src = K + ((size_t)(tok0 + key) * P.hkv + j) * kD + d0;
+  {  // K_i, V_i -> LDS, row-major (rows past the end of a ragged block are zero)
+    const int key = tid >> 2, d0 = (tid & 3) * 32;
+    const size_t o = ((size_t)(tok0 + key) * P.hkv + j) * kD + d0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      bf16x8 v = key < blen ? *reinterpret_cast<const bf16x8*>(src + 8 * i) : zero8;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) Kt[(d0 + 8 * i + e) * kKtStride + pos] = v[e];
+      const bf16x8 kv = key < blen ? *reinterpret_cast<const bf16x8*>(K + o + 8 * i) : zero8;
+      const bf16x8 vv = key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
+      *reinterpret_cast<bf16x8*>(&Ks[key * kRowStride + d0 + 8 * i]) = kv;
+      *reinterpret_cast<bf16x8*>(&Vs[key * kRowStride + d0 + 8 * i]) = vv;
     }
   }
-  bf16x8 kf[2][8], vf[2][8];
-#pragma unroll
-  for (int mb = 0; mb < 2; ++mb) {
-    const int key = 32 * mb + col;
-    const size_t o = ((size_t)(tok0 + key) * P.hkv + j) * kD + 8 * qh;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      kf[mb][s] = key < blen ? *reinterpret_cast<const bf16x8*>(K + o + 16 * s) : zero8;
-      vf[mb][s] = key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 16 * s) : zero8;
-    }
-  }
+  for (int i = tid; i < ne; i += 256) ent[i] = qlist[e0 + i];
   f32x16 dkacc[2], dvacc[2];
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
@@ -111,32 +117,61 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 
   const int rows_total = ne * P.g;
   const float c2 = P.scale * 1.4426950408889634f;
-  for (int tile0 = 0; tile0 < rows_total; tile0 += kTileRows) {
-    const int r = tile0 + 32 * wave + col;
-    const bool valid = r < rows_total;
-    const int e = valid ? r / P.g : 0;
-    const int hh = valid ? r - e * P.g : 0;
-    const int t = qlist[e0 + e];
-    const int slot = qslot[e0 + e];
-    const int h = j * P.g + hh;
-    const size_t grow = (size_t)t * P.hq + h;
-    bf16x8 qf[8], dof[8];
+  const size_t hq = P.hq;
+  const int hbase = j * P.g;
+  const int wrow0 = 32 * wave;  // this wave's rows of the tile
+  bf16_t* Qw = Qs + wrow0 * kRowStride;
+  bf16_t* dOw = dOs + wrow0 * kRowStride;
+  // this lane's share of a transposing LDS read of four rows x 16 columns: its group's 16 columns start at
+  // 16 (grp & 1) of a 32-column slice, the group's lanes belong to MFMA lane half qh = grp / 2
+  const int grp = lane >> 4, sl = lane & 15;
+  const int tr_lane = (sl >> 2) * kRowStride + 16 * (grp & 1) + 4 * (sl & 3);
+
+  // gather this wave's 32 rows of Q and dO of the tile starting at row tile0 (coalesced: a row = 16 lanes x 16 B),
+  // plus LSE and delta of the row this lane owns in the MFMA column layout
+  uint4 qc[8], dc[8];
+  float lse2_n, dl_n;
+  auto issue_rows = [&](int tile0) {
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      qf[s] = valid ? *reinterpret_cast<const bf16x8*>(Q + grow * kD + 16 * s + 8 * qh) : zero8;
-      dof[s] = valid ? *reinterpret_cast<const bf16x8*>(dO + grow * kD + 16 * s + 8 * qh) : zero8;
-    }
-    const float lse2 = valid ? LSE[grow] * 1.4426950408889634f : 0.f;
-    const float dl = valid ? delta[grow] : 0.f;
-    {
-      bf16_t* qdst = Qs + (32 * wave + col) * kRowStride + 8 * qh;
-      bf16_t* ddst = dOs + (32 * wave + col) * kRowStride + 8 * qh;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        *reinterpret_cast<bf16x8*>(qdst + 16 * s) = qf[s];
-        *reinterpret_cast<bf16x8*>(ddst + 16 * s) = dof[s];
+    for (int i = 0; i < 8; ++i) {
+      const int r = tile0 + wrow0 + 4 * i + crow;
+      if (r < rows_total) {
+        const int e = r / P.g;
+        const size_t o = ((size_t)ent[e] * hq + hbase + (r - e * P.g)) * kD + cchunk;
+        qc[i] = *reinterpret_cast<const uint4*>(Q + o);
+        dc[i] = *reinterpret_cast<const uint4*>(dO + o);
+      } else {
+        qc[i] = make_uint4(0, 0, 0, 0);
+        dc[i] = make_uint4(0, 0, 0, 0);
       }
     }
+    const int r = tile0 + wrow0 + col;
+    if (r < rows_total) {
+      const int e = r / P.g;
+      const size_t grow = (size_t)ent[e] * hq + hbase + (r - e * P.g);
+      lse2_n = LSE[grow] * 1.4426950408889634f;
+      dl_n = delta[grow];
+    } else {
+      lse2_n = 0.f;
+      dl_n = 0.f;
+    }
+  };
+  issue_rows(0);
+
+  for (int tile0 = 0; tile0 < rows_total; tile0 += kTileRows) {
+    // stage this wave's rows; then let the next tile's rows fly while this one computes
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      *reinterpret_cast<uint4*>(&Qw[(4 * i + crow) * kRowStride + cchunk]) = qc[i];
+      *reinterpret_cast<uint4*>(&dOw[(4 * i + crow) * kRowStride + cchunk]) = dc[i];
+    }
+    const float lse2 = lse2_n, dl = dl_n;
+    wave_sync_bwd();
+    if (tile0 + kTileRows < rows_total) issue_rows(tile0 + kTileRows);
+
+    const int r = tile0 + wrow0 + col;
+    const bool valid = r < rows_total;
+    const int t = valid ? ent[r / P.g] : -1;
     f32x16 sacc[2], dpacc[2];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -145,18 +180,26 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         sacc[mb][v] = 0.f;
         dpacc[mb][v] = 0.f;
       }
+    // S^T = K_i Q^T and dP^T = V_i dO^T for this wave's 32 rows (all operands from LDS)
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
+    for (int s = 0; s < 8; ++s) {
+      const bf16x8 qf = *reinterpret_cast<const bf16x8*>(&Qw[col * kRowStride + 16 * s + 8 * qh]);
+      const bf16x8 dof = *reinterpret_cast<const bf16x8*>(&dOw[col * kRowStride + 16 * s + 8 * qh]);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
-        sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][s], qf[s], sacc[mb], 0, 0, 0);
-        dpacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mb][s], dof[s], dpacc[mb], 0, 0, 0);
+        const bf16x8 kfa = *reinterpret_cast<const bf16x8*>(&Ks[(32 * mb + col) * kRowStride + 16 * s + 8 * qh]);
+        const bf16x8 vfa = *reinterpret_cast<const bf16x8*>(&Vs[(32 * mb + col) * kRowStride + 16 * s + 8 * qh]);
+        sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa, qf, sacc[mb], 0, 0, 0);
+        dpacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa, dof, dpacc[mb], 0, 0, 0);
       }
+      if (s & 1) __builtin_amdgcn_sched_barrier(0);
+    }
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
     // P and dS (scaled) of this wave's 32 rows; P^T, dS^T to LDS for the dK/dV products
-    bf16_t* pdst = Pt + 32 * wave + col;
-    bf16_t* sdst = dSt + 32 * wave + col;
+    bf16_t* pdst = Pt + wrow0 + col;
+    bf16_t* sdst = dSt + wrow0 + col;
+    bf16x8 dsf[4];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -164,50 +207,24 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
         const float p = key < lim ? __builtin_amdgcn_exp2f(sacc[mb][v] * c2 - lse2) : 0.f;
         const float ds = p * (dpacc[mb][v] - dl) * P.scale;
-        sacc[mb][v] = ds;
+        const bf16_t dsb = (bf16_t)ds;
+        dsf[2 * mb + (v >> 3)][v & 7] = dsb;
         pdst[key * kRowStride] = (bf16_t)p;
-        sdst[key * kRowStride] = (bf16_t)ds;
+        sdst[key * kRowStride] = dsb;
       }
-    bf16x8 dsf[4];
-#pragma unroll
-    for (int sp = 0; sp < 4; ++sp)
-#pragma unroll
-      for (int e2 = 0; e2 < 8; ++e2) dsf[sp][e2] = (bf16_t)sacc[sp >> 1][8 * (sp & 1) + e2];
-    f32x16 dqacc[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
-#pragma unroll
-    for (int sp = 0; sp < 4; ++sp)
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const bf16x8 ktf = *reinterpret_cast<const bf16x8*>(&Kt[(32 * db + col) * kKtStride + 16 * sp + 8 * qh]);
-        dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[sp], dqacc[db], 0, 0, 0);
-      }
-    if (valid) {
-      bf16_t* dst = dqpart + ((size_t)e0 * P.g + r) * kD + 4 * qh;  // compact: list position * g + head
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          uint2 w;
-          w.x = pack_bf16x2(dqacc[db][4 * a + 0], dqacc[db][4 * a + 1]);
-          w.y = pack_bf16x2(dqacc[db][4 * a + 2], dqacc[db][4 * a + 3]);
-          *reinterpret_cast<uint2*>(dst + 32 * db + 8 * a) = w;
-        }
-    }
     __syncthreads();
-    // dV_i[:, 32w..32w+31] += P^T dO,  dK_i[:, 32w..32w+31] += dS^T Q  over the tile's 128 rows
-    const int dcol = 32 * wave + col;
+    // dV_i[:, 32w..32w+31] += P^T dO,  dK_i[:, 32w..32w+31] += dS^T Q  over the tile's 128 rows.  A operands
+    // (lane = key, elements = 8 rows) are plain reads of P^T / dS^T; B operands (lane = channel, elements = 8
+    // rows) are transposing reads of the row-major Q / dO tiles.
+    const int tr_row = tr_lane + 8 * (grp >> 1) * kRowStride + 32 * wave;
 #pragma unroll
     for (int qs = 0; qs < 8; ++qs) {
-      bf16x8 dob, qb;
-#pragma unroll
-      for (int e2 = 0; e2 < 8; ++e2) {
-        dob[e2] = dOs[(16 * qs + 8 * qh + e2) * kRowStride + dcol];
-        qb[e2] = Qs[(16 * qs + 8 * qh + e2) * kRowStride + dcol];
-      }
+      const bf16x4 d0 = lds_read_tr(&dOs[16 * qs * kRowStride + tr_row]);
+      const bf16x4 d1 = lds_read_tr(&dOs[(16 * qs + 4) * kRowStride + tr_row]);
+      const bf16x4 q0 = lds_read_tr(&Qs[16 * qs * kRowStride + tr_row]);
+      const bf16x4 q1 = lds_read_tr(&Qs[(16 * qs + 4) * kRowStride + tr_row]);
+      const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
+      const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
         const bf16x8 pa = *reinterpret_cast<const bf16x8*>(&Pt[(32 * mb + col) * kRowStride + 16 * qs + 8 * qh]);
@@ -215,8 +232,50 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         dvacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc[mb], 0, 0, 0);
         dkacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qb, dkacc[mb], 0, 0, 0);
       }
+      if (qs & 1) __builtin_amdgcn_sched_barrier(0);  // keep at most two steps of operands live
     }
     __syncthreads();
+    // dQ^T = K_i^T dS^T for this wave's rows: dS^T is still in registers in B-operand layout (lane half qh holds,
+    // for contraction step sp, keys 32 (sp / 2) + 16 (sp & 1) + 4 qh + {0..3} and the same + 8); K^T comes out
+    // of the row-major K tile by transposing reads with the same key order.
+    f32x16 dqacc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
+    const int tr_key = tr_lane + 4 * (grp >> 1) * kRowStride;
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp) {
+      const int k0 = 32 * (sp >> 1) + 16 * (sp & 1);
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const bf16x4 a0 = lds_read_tr(&Ks[k0 * kRowStride + tr_key + 32 * db]);
+        const bf16x4 a1 = lds_read_tr(&Ks[(k0 + 8) * kRowStride + tr_key + 32 * db]);
+        const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+        dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[sp], dqacc[db], 0, 0, 0);
+      }
+    }
+    // the rows go through the wave's (now free) rows of the Q tile into one contiguous 8 KB store at their
+    // list position
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        uint2 w;
+        w.x = pack_bf16x2(dqacc[db][4 * a + 0], dqacc[db][4 * a + 1]);
+        w.y = pack_bf16x2(dqacc[db][4 * a + 2], dqacc[db][4 * a + 3]);
+        *reinterpret_cast<uint2*>(&Qw[col * kRowStride + 32 * db + 8 * a + 4 * qh]) = w;
+      }
+    wave_sync_bwd();
+    const size_t prow0 = (size_t)e0 * P.g + (size_t)(tile0 + wrow0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = 4 * i + crow;
+      if (tile0 + wrow0 + row < rows_total)
+        *reinterpret_cast<uint4*>(dqpart + (prow0 + row) * kD + cchunk) =
+            *reinterpret_cast<const uint4*>(&Qw[row * kRowStride + cchunk]);
+    }
+    wave_sync_bwd();
   }
   // unit partial: [u][0 = dK, 1 = dV][key][d] fp32
   float* outk = dkv_part + (size_t)u * 2 * kBlock * kD + 32 * wave + col;
@@ -311,7 +370,7 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
   { ProfScope ps(KID_BWD_MAIN, st);
   hipLaunchKernelGGL(k_bwd_main, dim3(L.bwd_units_max), dim3(256), kLdsBwdBytes, st, P, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, (const float*)delta, p.hdr, p.b_list,
-                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.qslot, (bf16_t*)dqpart, dkv_part); }
+                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, (bf16_t*)dqpart, dkv_part); }
   { ProfScope ps(KID_BWD_DQ_REDUCE, st);
   hipLaunchKernelGGL(k_bwd_dq_reduce, dim3(row_blocks), dim3(256), 0, st, P, (const bf16_t*)dqpart, p.vmask,
                      p.slotpos, (bf16_t*)dQ); }
