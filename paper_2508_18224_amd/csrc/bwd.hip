@@ -66,7 +66,13 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
   if (row < rows && sub == 0) delta[row] = acc;
 }
 
-__global__ void __launch_bounds__(256)
+// 512 threads = 8 wavefronts = two per SIMD, so one wave's LDS and memory waits are covered by the other's issue.
+// Per 128-row tile the waves take three roles in turn (w = wave index):
+//   rows/keys   (rb = w / 2, mb = w % 2): S^T, dP^T, P, dS for rows 32 rb.. and keys 32 mb..; writes P^T, dS^T
+//   keys/chans  (mb = w / 4, ds = w % 4): dV_i, dK_i accumulators for keys 32 mb.. and channels 32 ds..
+//   rows/chans  (rb = w / 2, dh = w % 2): dQ^T for rows 32 rb.. and channels 64 dh..; also stages / prefetches
+//                                         exactly that part of the Q and dO tiles and stores that part of dQ
+__global__ void __launch_bounds__(512)
 k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
            const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
            const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
@@ -90,65 +96,71 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int ne = min(kBwdUnit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
-  const int crow = lane >> 4, cchunk = (lane & 15) * 8;  // coalesced layout: 16 lanes per row, 4 rows per access
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
   {  // K_i, V_i -> LDS, row-major (rows past the end of a ragged block are zero)
-    const int key = tid >> 2, d0 = (tid & 3) * 32;
+    const int key = tid >> 3, d0 = (tid & 7) * 16;
     const size_t o = ((size_t)(tok0 + key) * P.hkv + j) * kD + d0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2; ++i) {
       const bf16x8 kv = key < blen ? *reinterpret_cast<const bf16x8*>(K + o + 8 * i) : zero8;
       const bf16x8 vv = key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
       *reinterpret_cast<bf16x8*>(&Ks[key * kRowStride + d0 + 8 * i]) = kv;
       *reinterpret_cast<bf16x8*>(&Vs[key * kRowStride + d0 + 8 * i]) = vv;
     }
   }
-  for (int i = tid; i < ne; i += 256) ent[i] = qlist[e0 + i];
-  f32x16 dkacc[2], dvacc[2];
+  for (int i = tid; i < ne; i += 512) ent[i] = qlist[e0 + i];
+  f32x16 dkacc, dvacc;
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      dkacc[mb][v] = 0.f;
-      dvacc[mb][v] = 0.f;
-    }
+  for (int v = 0; v < 16; ++v) {
+    dkacc[v] = 0.f;
+    dvacc[v] = 0.f;
+  }
   __syncthreads();
 
   const int rows_total = ne * P.g;
   const float c2 = P.scale * 1.4426950408889634f;
   const size_t hq = P.hq;
   const int hbase = j * P.g;
-  const int wrow0 = 32 * wave;  // this wave's rows of the tile
-  bf16_t* Qw = Qs + wrow0 * kRowStride;
-  bf16_t* dOw = dOs + wrow0 * kRowStride;
+  const int rb = wave >> 1, half = wave & 1;   // roles rows/keys (half = mb) and rows/chans (half = dh)
+  const int mb2 = wave >> 2, dsl = wave & 3;   // role keys/chans
   // this lane's share of a transposing LDS read of four rows x 16 columns: its group's 16 columns start at
-  // 16 (grp & 1) of a 32-column slice, the group's lanes belong to MFMA lane half qh = grp / 2
+  // 16 (grp & 1) of a 32-column slice, the group's lanes belong to MFMA lane half grp / 2
   const int grp = lane >> 4, sl = lane & 15;
   const int tr_lane = (sl >> 2) * kRowStride + 16 * (grp & 1) + 4 * (sl & 3);
+  // staging layout of the rows/chans role: 8 lanes x 16 B cover the 64 channels of a row half, 8 rows per access
+  const int srow = lane >> 3, schunk = 64 * half + (lane & 7) * 8;
+  bf16_t* Qmine = Qs + (32 * rb) * kRowStride;
+  bf16_t* dOmine = dOs + (32 * rb) * kRowStride;
+  const int q4 = 8 / P.g, r4 = 8 - q4 * P.g;  // row -> (entry, head) stepping by 8 rows without dividing
 
-  // gather this wave's 32 rows of Q and dO of the tile starting at row tile0 (coalesced: a row = 16 lanes x 16 B),
-  // plus LSE and delta of the row this lane owns in the MFMA column layout
-  uint4 qc[8], dc[8];
+  uint4 qc[4], dc[4];
   float lse2_n, dl_n;
   auto issue_rows = [&](int tile0) {
+    int r = tile0 + 32 * rb + srow;
+    int e = r / P.g, hh = r - e * P.g;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = tile0 + wrow0 + 4 * i + crow;
+    for (int i = 0; i < 4; ++i) {
       if (r < rows_total) {
-        const int e = r / P.g;
-        const size_t o = ((size_t)ent[e] * hq + hbase + (r - e * P.g)) * kD + cchunk;
+        const size_t o = ((size_t)ent[e] * hq + hbase + hh) * kD + schunk;
         qc[i] = *reinterpret_cast<const uint4*>(Q + o);
         dc[i] = *reinterpret_cast<const uint4*>(dO + o);
       } else {
         qc[i] = make_uint4(0, 0, 0, 0);
         dc[i] = make_uint4(0, 0, 0, 0);
       }
+      r += 8;
+      e += q4;
+      hh += r4;
+      if (hh >= P.g) {
+        hh -= P.g;
+        e += 1;
+      }
     }
-    const int r = tile0 + wrow0 + col;
-    if (r < rows_total) {
-      const int e = r / P.g;
-      const size_t grow = (size_t)ent[e] * hq + hbase + (r - e * P.g);
+    const int rc = tile0 + 32 * rb + col;
+    if (rc < rows_total) {
+      const int ec = rc / P.g;
+      const size_t grow = (size_t)ent[ec] * hq + hbase + (rc - ec * P.g);
       lse2_n = LSE[grow] * 1.4426950408889634f;
       dl_n = delta[grow];
     } else {
@@ -159,135 +171,128 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   issue_rows(0);
 
   for (int tile0 = 0; tile0 < rows_total; tile0 += kTileRows) {
-    // stage this wave's rows; then let the next tile's rows fly while this one computes
+    // stage this wave's part of the tile; then let the next tile's rows fly while this one computes
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      *reinterpret_cast<uint4*>(&Qw[(4 * i + crow) * kRowStride + cchunk]) = qc[i];
-      *reinterpret_cast<uint4*>(&dOw[(4 * i + crow) * kRowStride + cchunk]) = dc[i];
+    for (int i = 0; i < 4; ++i) {
+      *reinterpret_cast<uint4*>(&Qmine[(8 * i + srow) * kRowStride + schunk]) = qc[i];
+      *reinterpret_cast<uint4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
     }
     const float lse2 = lse2_n, dl = dl_n;
-    wave_sync_bwd();
     if (tile0 + kTileRows < rows_total) issue_rows(tile0 + kTileRows);
+    __syncthreads();
 
-    const int r = tile0 + wrow0 + col;
-    const bool valid = r < rows_total;
-    const int t = valid ? ent[r / P.g] : -1;
-    f32x16 sacc[2], dpacc[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        sacc[mb][v] = 0.f;
-        dpacc[mb][v] = 0.f;
-      }
-    // S^T = K_i Q^T and dP^T = V_i dO^T for this wave's 32 rows (all operands from LDS)
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const bf16x8 qf = *reinterpret_cast<const bf16x8*>(&Qw[col * kRowStride + 16 * s + 8 * qh]);
-      const bf16x8 dof = *reinterpret_cast<const bf16x8*>(&dOw[col * kRowStride + 16 * s + 8 * qh]);
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        const bf16x8 kfa = *reinterpret_cast<const bf16x8*>(&Ks[(32 * mb + col) * kRowStride + 16 * s + 8 * qh]);
-        const bf16x8 vfa = *reinterpret_cast<const bf16x8*>(&Vs[(32 * mb + col) * kRowStride + 16 * s + 8 * qh]);
-        sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa, qf, sacc[mb], 0, 0, 0);
-        dpacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa, dof, dpacc[mb], 0, 0, 0);
-      }
-      if (s & 1) __builtin_amdgcn_sched_barrier(0);
-    }
-    int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
-    if (!valid) lim = 0;
-    // P and dS (scaled) of this wave's 32 rows; P^T, dS^T to LDS for the dK/dV products
-    bf16_t* pdst = Pt + wrow0 + col;
-    bf16_t* sdst = dSt + wrow0 + col;
-    bf16x8 dsf[4];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    {  // role rows/keys: S^T = K_i Q^T, dP^T = V_i dO^T, P, dS for rows 32 rb.., keys 32 half..
+      const int r = tile0 + 32 * rb + col;
+      const bool valid = r < rows_total;
+      const int t = valid ? ent[r / P.g] : -1;
+      f32x16 sacc, dpacc;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
-        const float p = key < lim ? __builtin_amdgcn_exp2f(sacc[mb][v] * c2 - lse2) : 0.f;
-        const float ds = p * (dpacc[mb][v] - dl) * P.scale;
-        const bf16_t dsb = (bf16_t)ds;
-        dsf[2 * mb + (v >> 3)][v & 7] = dsb;
+        sacc[v] = 0.f;
+        dpacc[v] = 0.f;
+      }
+      const bf16_t* qrow = Qmine + col * kRowStride + 8 * qh;
+      const bf16_t* drow = dOmine + col * kRowStride + 8 * qh;
+      const bf16_t* krow = Ks + (32 * half + col) * kRowStride + 8 * qh;
+      const bf16_t* vrow = Vs + (32 * half + col) * kRowStride + 8 * qh;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
+        const bf16x8 dof = *reinterpret_cast<const bf16x8*>(drow + 16 * s);
+        const bf16x8 kfa = *reinterpret_cast<const bf16x8*>(krow + 16 * s);
+        const bf16x8 vfa = *reinterpret_cast<const bf16x8*>(vrow + 16 * s);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa, qf, sacc, 0, 0, 0);
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa, dof, dpacc, 0, 0, 0);
+      }
+      int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
+      if (!valid) lim = 0;
+      bf16_t* pdst = Pt + 32 * rb + col;
+      bf16_t* sdst = dSt + 32 * rb + col;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = 32 * half + 8 * (v >> 2) + 4 * qh + (v & 3);
+        const float p = key < lim ? __builtin_amdgcn_exp2f(sacc[v] * c2 - lse2) : 0.f;
+        const float ds = p * (dpacc[v] - dl) * P.scale;
         pdst[key * kRowStride] = (bf16_t)p;
-        sdst[key * kRowStride] = dsb;
-      }
-    __syncthreads();
-    // dV_i[:, 32w..32w+31] += P^T dO,  dK_i[:, 32w..32w+31] += dS^T Q  over the tile's 128 rows.  A operands
-    // (lane = key, elements = 8 rows) are plain reads of P^T / dS^T; B operands (lane = channel, elements = 8
-    // rows) are transposing reads of the row-major Q / dO tiles.
-    const int tr_row = tr_lane + 8 * (grp >> 1) * kRowStride + 32 * wave;
-#pragma unroll
-    for (int qs = 0; qs < 8; ++qs) {
-      const bf16x4 d0 = lds_read_tr(&dOs[16 * qs * kRowStride + tr_row]);
-      const bf16x4 d1 = lds_read_tr(&dOs[(16 * qs + 4) * kRowStride + tr_row]);
-      const bf16x4 q0 = lds_read_tr(&Qs[16 * qs * kRowStride + tr_row]);
-      const bf16x4 q1 = lds_read_tr(&Qs[(16 * qs + 4) * kRowStride + tr_row]);
-      const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
-      const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        const bf16x8 pa = *reinterpret_cast<const bf16x8*>(&Pt[(32 * mb + col) * kRowStride + 16 * qs + 8 * qh]);
-        const bf16x8 sa = *reinterpret_cast<const bf16x8*>(&dSt[(32 * mb + col) * kRowStride + 16 * qs + 8 * qh]);
-        dvacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc[mb], 0, 0, 0);
-        dkacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qb, dkacc[mb], 0, 0, 0);
-      }
-      if (qs & 1) __builtin_amdgcn_sched_barrier(0);  // keep at most two steps of operands live
-    }
-    __syncthreads();
-    // dQ^T = K_i^T dS^T for this wave's rows: dS^T is still in registers in B-operand layout (lane half qh holds,
-    // for contraction step sp, keys 32 (sp / 2) + 16 (sp & 1) + 4 qh + {0..3} and the same + 8); K^T comes out
-    // of the row-major K tile by transposing reads with the same key order.
-    f32x16 dqacc[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
-    const int tr_key = tr_lane + 4 * (grp >> 1) * kRowStride;
-#pragma unroll
-    for (int sp = 0; sp < 4; ++sp) {
-      const int k0 = 32 * (sp >> 1) + 16 * (sp & 1);
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const bf16x4 a0 = lds_read_tr(&Ks[k0 * kRowStride + tr_key + 32 * db]);
-        const bf16x4 a1 = lds_read_tr(&Ks[(k0 + 8) * kRowStride + tr_key + 32 * db]);
-        const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-        dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[sp], dqacc[db], 0, 0, 0);
+        sdst[key * kRowStride] = (bf16_t)ds;
       }
     }
-    // the rows go through the wave's (now free) rows of the Q tile into one contiguous 8 KB store at their
-    // list position
+    __syncthreads();
+    {  // role keys/chans: dV_i += P^T dO, dK_i += dS^T Q over the tile's 128 rows.  A operands (lane = key,
+       // elements = 8 rows) are plain reads of P^T / dS^T; B operands (lane = channel, elements = 8 rows) are
+       // transposing reads of the row-major dO / Q tiles.
+      const int tr_row = tr_lane + 8 * (grp >> 1) * kRowStride + 32 * dsl;
+      const bf16_t* parow = Pt + (32 * mb2 + col) * kRowStride + 8 * qh;
+      const bf16_t* sarow = dSt + (32 * mb2 + col) * kRowStride + 8 * qh;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+      for (int qs = 0; qs < 8; ++qs) {
+        const bf16x4 d0 = lds_read_tr(&dOs[16 * qs * kRowStride + tr_row]);
+        const bf16x4 d1 = lds_read_tr(&dOs[(16 * qs + 4) * kRowStride + tr_row]);
+        const bf16x4 q0 = lds_read_tr(&Qs[16 * qs * kRowStride + tr_row]);
+        const bf16x4 q1 = lds_read_tr(&Qs[(16 * qs + 4) * kRowStride + tr_row]);
+        const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 pa = *reinterpret_cast<const bf16x8*>(parow + 16 * qs);
+        const bf16x8 sa = *reinterpret_cast<const bf16x8*>(sarow + 16 * qs);
+        dvacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc, 0, 0, 0);
+        dkacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qb, dkacc, 0, 0, 0);
+      }
+    }
+    f32x16 dqacc[2];
+    {  // role rows/chans: dQ^T[64 half.. , 32 rb..] = K_i^T dS^T, contraction over the 64 keys in natural order.
+       // A = K^T (lane = channel, elements = 8 keys) and B = dS^T (lane = row, elements = 8 keys) both come from
+       // row-major tiles (K [key][chan], dS^T [key][row]) by transposing reads.
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
+      const int tr_key = tr_lane + 8 * (grp >> 1) * kRowStride;
+#pragma unroll
+      for (int sp = 0; sp < 4; ++sp) {
+        const bf16x4 b0 = lds_read_tr(&dSt[16 * sp * kRowStride + tr_key + 32 * rb]);
+        const bf16x4 b1 = lds_read_tr(&dSt[(16 * sp + 4) * kRowStride + tr_key + 32 * rb]);
+        const bf16x8 dsb = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          const bf16x4 a0 = lds_read_tr(&Ks[16 * sp * kRowStride + tr_key + 64 * half + 32 * db]);
+          const bf16x4 a1 = lds_read_tr(&Ks[(16 * sp + 4) * kRowStride + tr_key + 64 * half + 32 * db]);
+          const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+          dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsb, dqacc[db], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();
+    // dQ rows (this wave's 32 rows x 64 channels) -> the part of the Q tile this wave staged -> 128-byte row
+    // segments at the rows' list position
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         uint2 w;
         w.x = pack_bf16x2(dqacc[db][4 * a + 0], dqacc[db][4 * a + 1]);
         w.y = pack_bf16x2(dqacc[db][4 * a + 2], dqacc[db][4 * a + 3]);
-        *reinterpret_cast<uint2*>(&Qw[col * kRowStride + 32 * db + 8 * a + 4 * qh]) = w;
+        *reinterpret_cast<uint2*>(&Qmine[col * kRowStride + 64 * half + 32 * db + 8 * a + 4 * qh]) = w;
       }
     wave_sync_bwd();
-    const size_t prow0 = (size_t)e0 * P.g + (size_t)(tile0 + wrow0);
+    const size_t prow0 = (size_t)e0 * P.g + (size_t)(tile0 + 32 * rb);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = 4 * i + crow;
-      if (tile0 + wrow0 + row < rows_total)
-        *reinterpret_cast<uint4*>(dqpart + (prow0 + row) * kD + cchunk) =
-            *reinterpret_cast<const uint4*>(&Qw[row * kRowStride + cchunk]);
+    for (int i = 0; i < 4; ++i) {
+      const int row = 8 * i + srow;
+      if (tile0 + 32 * rb + row < rows_total)
+        *reinterpret_cast<uint4*>(dqpart + (prow0 + row) * kD + schunk) =
+            *reinterpret_cast<const uint4*>(&Qmine[row * kRowStride + schunk]);
     }
     wave_sync_bwd();
   }
   // unit partial: [u][0 = dK, 1 = dV][key][d] fp32
-  float* outk = dkv_part + (size_t)u * 2 * kBlock * kD + 32 * wave + col;
+  float* outk = dkv_part + (size_t)u * 2 * kBlock * kD + 32 * dsl + col;
   float* outv = outk + kBlock * kD;
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
-      outk[key * kD] = dkacc[mb][v];
-      outv[key * kD] = dvacc[mb][v];
-    }
+  for (int v = 0; v < 16; ++v) {
+    const int key = 32 * mb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
+    outk[key * kD] = dkacc[v];
+    outv[key * kD] = dvacc[v];
+  }
 }
 
 __global__ void __launch_bounds__(256)
@@ -368,7 +373,7 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
   { ProfScope ps(KID_BWD_DELTA, st);
   hipLaunchKernelGGL(k_bwd_delta, dim3(row_blocks), dim3(256), 0, st, rows, (const bf16_t*)O, (const bf16_t*)dO, delta); }
   { ProfScope ps(KID_BWD_MAIN, st);
-  hipLaunchKernelGGL(k_bwd_main, dim3(L.bwd_units_max), dim3(256), kLdsBwdBytes, st, P, (const bf16_t*)Q,
+  hipLaunchKernelGGL(k_bwd_main, dim3(L.bwd_units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, (const float*)delta, p.hdr, p.b_list,
                      p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, (bf16_t*)dqpart, dkv_part); }
   { ProfScope ps(KID_BWD_DQ_REDUCE, st);
