@@ -118,9 +118,9 @@ def backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarray, idx: n
     hkv = K.shape[1]
     g = hq // hkv
     scale = 1.0 / math.sqrt(d) if scale is None else scale
-    dQ = np.zeros_like(Q, dtype=np.float64)
-    dK = np.zeros_like(K, dtype=np.float64)
-    dV = np.zeros_like(V, dtype=np.float64)
+    dQ = np.zeros(Q.shape, dtype=np.float64)
+    dK = np.zeros(K.shape, dtype=np.float64)
+    dV = np.zeros(V.shape, dtype=np.float64)
     for t in (range(T) if tokens is None else tokens):
         for j in range(hkv):
             keys = visible_keys(cu, t, idx[t, j], block, causal)

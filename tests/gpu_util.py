@@ -61,3 +61,16 @@ def assert_lse_close(got: np.ndarray, ref: np.ndarray):
     fin = np.isfinite(ref)
     err = np.abs(got[fin] - ref[fin])
     assert err.size == 0 or err.max() <= TOL_LSE, f"LSE: max-abs err {err.max():.4g} > {TOL_LSE}"
+
+
+class BitsF64:
+    """bf16 bit patterns presented as a read-only float64 array that widens (exactly) only what is indexed,
+    so that the oracle can sample a few rows of a multi-GB tensor."""
+
+    def __init__(self, bits: np.ndarray):
+        self.bits = bits
+        self.shape = bits.shape
+        self.dtype = np.dtype(np.float64)
+
+    def __getitem__(self, ix):
+        return wl.bf16_bits_to_f64(np.asarray(self.bits[ix]))

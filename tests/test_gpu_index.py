@@ -51,3 +51,29 @@ def test_inversion_multi_chunk_scan():
     w = wl.Workload("big", [5000, 3000, 4100], hq=4, hkv=4, topk=16, sink=True, seed=6)
     wl.realise(w, tensors=False)
     _compare(w)
+
+
+@pytest.mark.parametrize("name,heads", [("headline", [0, 5]), ("varlen_g1", [3]), ("llama70b_128k", [7])])
+def test_inversion_bit_exact_full_size(name, heads):
+    """Benchmark-size tables; the oracle's sequential pass is run for a few kv heads only (it is per-head)."""
+    import paper_2508_18224_amd as nsa
+    print("full-size inversion", name, flush=True)
+    w = wl.realise(wl.named(name), tensors=False)
+    attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=True, bwd=False)
+    attn.build_index(torch.from_numpy(w.idx).cuda(), torch.from_numpy(w.cu_seqlens).cuda())
+    torch.cuda.synchronize()
+    cnt, off, qlist, qslot, vmask, bcap = attn.index_arrays()
+    rc, ro, rl, rs, rv = orc.invert_index(w.idx, w.cu_seqlens, kv_heads=heads)
+    b_tot = rc.shape[1]
+    for j in heads:
+        assert np.array_equal(cnt[j, :b_tot], rc[j]) and not cnt[j, b_tot:].any()
+        lo, hi = int(off[j * bcap]), int(off[j * bcap + b_tot])
+        rlo, rhi = int(ro[j * b_tot]), int(ro[(j + 1) * b_tot])
+        assert hi - lo == rhi - rlo
+        assert np.array_equal(qlist[lo:hi], rl[rlo:rhi])
+        assert np.array_equal(qslot[lo:hi], rs[rlo:rhi])
+        assert np.array_equal(vmask[:, j], rv[:, j])
+    # sink pattern: block 0 of every head is selected by every token (App. E, attention sink)
+    if w.sink:
+        assert np.all(cnt[:, 0] == w.total_tokens)
+    assert int(off[-1]) == int(cnt.sum())
