@@ -25,7 +25,10 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by
 # the copy-kernel calibration); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    ("headline", "bwd_main"): 27.49e9,   # profiles/hot_path_headline_64k_g4.txt: fetch 18.35 GB + write 9.15 GB
+    ("headline", "fwd_main"): 17.02e9,
+}
 
 
 def cpu_baseline(w, budget_tokens: int):
