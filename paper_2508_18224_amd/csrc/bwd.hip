@@ -279,8 +279,8 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     for (int i = 0; i < 4; ++i) {
       const int row = 8 * i + srow;
       if (tile0 + 32 * rb + row < rows_total)
-        *reinterpret_cast<uint4*>(dqpart + (prow0 + row) * kD + schunk) =
-            *reinterpret_cast<const uint4*>(&Qmine[row * kRowStride + schunk]);
+        store_streaming(dqpart + (prow0 + row) * kD + schunk,
+                        *reinterpret_cast<const uint4*>(&Qmine[row * kRowStride + schunk]));
     }
     wave_sync_bwd();
   }

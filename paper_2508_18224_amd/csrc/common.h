@@ -121,6 +121,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 
+// 16-byte store with the non-temporal hint: partial rows are written once and read once much later, so they
+// should not displace the gathered Q / dO rows from the caches.
+__device__ __forceinline__ void store_streaming(bf16_t* dst, uint4 v) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<u32x4*>(dst));
+}
+
 // Sequence bounds of token t in a packed batch (cu may be null for a single sequence).
 __device__ __forceinline__ void seq_bounds(const int32_t* cu, int nseq, int T, int t, int& s, int& c0, int& c1) {
   if (cu == nullptr || nseq == 1) {

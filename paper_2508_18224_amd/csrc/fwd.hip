@@ -193,8 +193,8 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     for (int i = 0; i < 8; ++i) {
       const int row = 4 * i + crow;
       if (tile * 32 + row < rows_total)
-        *reinterpret_cast<uint4*>(opart + (prow0 + row) * kD + cchunk) =
-            *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]);
+        store_streaming(opart + (prow0 + row) * kD + cchunk,
+                        *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]));
     }
     if (valid && qh == 0) lse_part[prow0 + col] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
     wave_sync();
