@@ -124,8 +124,9 @@ def calibration_copy(dst: torch.Tensor, src: torch.Tensor):
 class SelAttention:
     """Owns the workspaces for one shape and calls the library (buffers are torch uint8 tensors)."""
 
-    def __init__(self, total_tokens, hq, hkv, topk, *, nseq=1, causal=True, scale=0.0, device="cuda:0", bwd=True):
-        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, 64, topk, int(causal), float(scale), 0)
+    def __init__(self, total_tokens, hq, hkv, topk, *, nseq=1, causal=True, scale=0.0, device="cuda:0", bwd=True,
+                 block=64):
+        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0)
         fb, bb, ib = workspace_bytes(self.shape)
         self.device = torch.device(device)
         self.index_ws = torch.empty(ib, dtype=torch.uint8, device=self.device)

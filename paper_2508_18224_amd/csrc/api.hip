@@ -12,13 +12,13 @@ static int check_shape(const nsa_sel_shape* s) {
   if (s->hq % s->hkv != 0) return NSA_SEL_EINVAL;
   const int g = s->hq / s->hkv;
   if (g < 1 || g > 8) return NSA_SEL_EINVAL;
-  if (s->d != kD || s->block != kBlock) return NSA_SEL_EUNSUPPORTED;
-  if (s->topk < 1 || s->topk > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
+  if (s->d != kD || (s->block != kBlock && s->block != 2 * kBlock)) return NSA_SEL_EUNSUPPORTED;
+  if (s->topk < 1 || s->topk * (s->block / kBlock) > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
   if (s->nseq > (1 << 20)) return NSA_SEL_EUNSUPPORTED;
   const int64_t b_cap = (int64_t)s->total_tokens / kBlock + s->nseq;
   // LDS tables of the inversion (12 bytes per block) must fit in one CU's 160 KB
   if (b_cap * 12 + 64 * (int64_t)(s->topk + 1) * 4 > 160 * 1024) return NSA_SEL_EUNSUPPORTED;
-  const int64_t p_max = (int64_t)s->total_tokens * s->hkv * s->topk;
+  const int64_t p_max = (int64_t)s->total_tokens * s->hkv * s->topk * (s->block / kBlock);
   if (p_max >= ((int64_t)1 << 31) - 4096) return NSA_SEL_EUNSUPPORTED;
   const int64_t n_chunks = ((int64_t)s->total_tokens + kChunkTokens - 1) / kChunkTokens;
   if (b_cap * s->hkv * (n_chunks > 0 ? n_chunks : 1) >= ((int64_t)1 << 31) - 4096) return NSA_SEL_EUNSUPPORTED;
@@ -30,14 +30,16 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.T = s->total_tokens;
   L.nseq = s->nseq;
   L.hkv = s->hkv;
-  L.topk = s->topk;
+  L.topk_in = s->topk;
+  L.sub = s->block / kBlock;
+  L.topk = s->topk * L.sub;
   L.causal = s->causal ? 1 : 0;
   L.b_cap = s->total_tokens / kBlock + s->nseq;
   L.n_lists = s->hkv * L.b_cap;
   L.n_chunks = (s->total_tokens + kChunkTokens - 1) / kChunkTokens;
   if (L.n_chunks < 1) L.n_chunks = 1;
   L.n_counters = (int64_t)L.n_lists * L.n_chunks;
-  L.p_max = (int64_t)s->total_tokens * s->hkv * s->topk;
+  L.p_max = (int64_t)s->total_tokens * s->hkv * L.topk;
   L.fwd_units_max = (int32_t)(L.n_lists + L.p_max / kFwdUnit);
   L.bwd_units_max = (int32_t)(L.n_lists + L.p_max / kBwdUnit);
   size_t o = 0;
@@ -71,20 +73,24 @@ static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
   P.hq = s->hq;
   P.hkv = s->hkv;
   P.g = s->hq / s->hkv;
-  P.topk = s->topk;
+  P.topk = L.topk;
   P.causal = s->causal ? 1 : 0;
   P.b_cap = L.b_cap;
   P.scale = s->scale > 0.f ? s->scale : 0.08838834764831845f;  // 1/sqrt(128)
   return P;
 }
 
+static size_t partial_rows(const nsa_sel_shape* s) {  // one per (token, query head, 64-token sub-block slot)
+  return (size_t)s->total_tokens * s->hq * s->topk * (s->block / kBlock);
+}
+
 static size_t fwd_ws_bytes(const nsa_sel_shape* s) {
-  const size_t rows = (size_t)s->total_tokens * s->hq * s->topk;
+  const size_t rows = partial_rows(s);
   return align256(rows * kD * 2) + align256(rows * 4);
 }
 
 static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L) {
-  const size_t rows = (size_t)s->total_tokens * s->hq * s->topk;
+  const size_t rows = partial_rows(s);
   return align256(rows * kD * 2) + align256((size_t)s->total_tokens * s->hq * 4) +
          align256((size_t)L.bwd_units_max * 2 * kBlock * kD * 4);
 }
@@ -147,7 +153,7 @@ int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   hipStream_t st = (hipStream_t)stream;
   if (rebuild_index && launch_build_index(L, idx, cu_seqlens, index_ws, st) != hipSuccess) return NSA_SEL_EHIP;
   Problem P = make_problem(shape, L);
-  const size_t rows = (size_t)shape->total_tokens * shape->hq * shape->topk;
+  const size_t rows = partial_rows(shape);
   void* opart = ws;
   float* lse_part = (float*)((char*)ws + align256(rows * kD * 2));
   return launch_fwd(P, L, Q, K, V, index_ws, opart, lse_part, O, LSE, st) == hipSuccess ? NSA_SEL_OK : NSA_SEL_EHIP;
@@ -164,7 +170,7 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   if (index_bytes < L.total || ws_bytes < bwd_ws_bytes(shape, L)) return NSA_SEL_EWORKSPACE;
   if (shape->total_tokens == 0) return NSA_SEL_OK;
   Problem P = make_problem(shape, L);
-  const size_t rows = (size_t)shape->total_tokens * shape->hq * shape->topk;
+  const size_t rows = partial_rows(shape);
   char* w = (char*)ws;
   void* dqpart = w;
   float* delta = (float*)(w + align256(rows * kD * 2));
@@ -179,7 +185,7 @@ const char* nsa_sel_strerror(int code) {
   switch (code) {
     case NSA_SEL_OK: return "ok";
     case NSA_SEL_EINVAL: return "invalid argument (null pointer, head counts, nseq)";
-    case NSA_SEL_EUNSUPPORTED: return "unsupported shape (d must be 128, block 64, topk 1..32, size limits)";
+    case NSA_SEL_EUNSUPPORTED: return "unsupported shape (d must be 128, block 64 or 128, topk * block / 64 in 1..32, size limits)";
     case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes)";
     case NSA_SEL_EHIP: return "HIP runtime error at launch";
     default: return "unknown nsa_sel error code";

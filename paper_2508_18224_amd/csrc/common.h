@@ -18,7 +18,10 @@ constexpr int kMaxTopk = 32;
 
 // Host-computed description of the index workspace (byte offsets from its base, all 256-aligned).
 struct IndexLayout {
-  int32_t T, nseq, hkv, topk, causal;
+  int32_t T, nseq, hkv, causal;
+  int32_t topk_in;      // columns of idx
+  int32_t sub;          // 64-token sub-blocks per selected block (B_K / 64: 1 or 2)
+  int32_t topk;         // virtual slots per row = topk_in * sub
   int32_t b_cap;        // list stride: T / 64 + nseq  (>= real number of blocks)
   int32_t n_lists;      // hkv * b_cap
   int32_t n_chunks;     // ceil(T / kChunkTokens)

@@ -57,17 +57,28 @@ __global__ void k_zero(int32_t* __restrict__ p, int64_t n) {
   for (; i < n; i += stride) p[i] = 0;
 }
 
-// Bit m of the result is set when column m of the row is a kept selection: in range for the sequence, not in
-// the token's future when causal, and not a repeat of an earlier column.
-__device__ __forceinline__ uint32_t kept_columns(const int32_t* row, int k, int b_s, int cur, int causal) {
+// A selected block of B_K = 64 * sub tokens is handled as `sub` consecutive 64-token sub-blocks; column m of a row
+// therefore owns the virtual slots m * sub .. m * sub + sub - 1 (sub is 1 or 2).  Bit v of the result is set when
+// virtual slot v is kept: its column's id is in range for the sequence and not a repeat of an earlier column,
+// and the sub-block exists (ragged sequence end) and is not in the token's future when causal.
+// b_s / cur are counted in 64-token sub-blocks.
+__device__ __forceinline__ uint32_t kept_slots(const int32_t* row, int k, int sub, int b_s, int cur, int causal) {
   uint32_t vm = 0;
   for (int m = 0; m < k; ++m) {
-    int x = row[m];
-    bool ok = x >= 0 && x < b_s && (!causal || x <= cur);
+    const int x = row[m];
+    bool ok = x >= 0 && (int64_t)x * sub < b_s;
     for (int mp = 0; mp < m && ok; ++mp) ok = row[mp] != x;
-    if (ok) vm |= 1u << m;
+    if (!ok) continue;
+    for (int hf = 0; hf < sub; ++hf) {
+      const int id = x * sub + hf;
+      if (id < b_s && (!causal || id <= cur)) vm |= 1u << (m * sub + hf);
+    }
   }
   return vm;
+}
+// 64-token sub-block id (local to the sequence) of virtual slot v of a row
+__device__ __forceinline__ int slot_block(const int32_t* row, int sub, int v) {
+  return sub == 1 ? row[v] : row[v >> 1] * 2 + (v & 1);
 }
 
 // Window of global blocks a token chunk can touch: all blocks of the sequences it overlaps.
@@ -85,7 +96,8 @@ __device__ __forceinline__ void chunk_window(const int32_t* cu, const int32_t* b
 // chunk that keep block gb for kv head j.  Dynamic LDS: b_cap ints + 256*(k+1) ints.
 __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                               const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
-                                              int causal, int b_cap, int n_chunks, int32_t* __restrict__ counters) {
+                                              int sub, int causal, int b_cap, int n_chunks,
+                                              int32_t* __restrict__ counters) {
   extern __shared__ int32_t lds[];
   int32_t* hist = lds;
   int32_t* rows = lds + b_cap;
@@ -104,10 +116,10 @@ __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, c
     for (int m = 0; m < k; ++m) row[m] = src[m];
     const int b_s = (c1 - c0 + kBlock - 1) / kBlock;
     const int cur = (t - c0) / kBlock;
-    uint32_t vm = kept_columns(row, k, b_s, cur, causal);
+    uint32_t vm = kept_slots(row, k, sub, b_s, cur, causal);
     const int base = blk_base[s] - gb_lo;
-    for (int m = 0; m < k; ++m)
-      if ((vm >> m) & 1u) atomicAdd(&hist[base + row[m]], 1);
+    for (int v = 0; v < k * sub; ++v)
+      if ((vm >> v) & 1u) atomicAdd(&hist[base + slot_block(row, sub, v)], 1);
   }
   __syncthreads();
   for (int i = threadIdx.x; i < win; i += blockDim.x)
@@ -185,7 +197,7 @@ static void scan_exclusive(int32_t* a, int64_t n, int32_t* tmp, hipStream_t st) 
 // masks + b_cap int cursors + 64*(k+1) ints.
 __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                                 const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
-                                                int causal, int b_cap, int n_chunks,
+                                                int sub, int causal, int b_cap, int n_chunks,
                                                 const int32_t* __restrict__ chunk_off, int32_t* __restrict__ qlist,
                                                 int32_t* __restrict__ qslot, uint32_t* __restrict__ vmask,
                                                 int32_t* __restrict__ slotpos) {
@@ -214,28 +226,29 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
       seq_bounds(cu, nseq, T, t, s, c0, c1);
       const int32_t* src = idx + ((size_t)t * hkv + j) * k;
       for (int m = 0; m < k; ++m) row[m] = src[m];
-      vm = kept_columns(row, k, (c1 - c0 + kBlock - 1) / kBlock, (t - c0) / kBlock, causal);
+      vm = kept_slots(row, k, sub, (c1 - c0 + kBlock - 1) / kBlock, (t - c0) / kBlock, causal);
       base = blk_base[s] - gb_lo;
       vmask[(size_t)t * hkv + j] = vm;
     }
     // A: mark membership of this round's tokens in every block they keep
-    for (int m = 0; m < k; ++m)
-      if ((vm >> m) & 1u) atomicOr(&mask[base + row[m]], 1ull << lane);
+    const int kv = k * sub;  // virtual slots per row
+    for (int m = 0; m < kv; ++m)
+      if ((vm >> m) & 1u) atomicOr(&mask[base + slot_block(row, sub, m)], 1ull << lane);
     __syncthreads();
     // B: rank among the lower tokens of the round gives the position; lists come out ascending
-    for (int m = 0; m < k; ++m)
+    for (int m = 0; m < kv; ++m)
       if ((vm >> m) & 1u) {
-        const int w = base + row[m];
+        const int w = base + slot_block(row, sub, m);
         const int pos = cursor[w] + __popcll(mask[w] & below);
         qlist[pos] = t;
         qslot[pos] = m;
-        slotpos[((size_t)t * hkv + j) * k + m] = pos;
+        slotpos[((size_t)t * hkv + j) * kv + m] = pos;
       }
     __syncthreads();
     // C: the lowest member of each touched block advances its cursor and clears the mask
-    for (int m = 0; m < k; ++m)
+    for (int m = 0; m < kv; ++m)
       if ((vm >> m) & 1u) {
-        const int w = base + row[m];
+        const int w = base + slot_block(row, sub, m);
         const unsigned long long mk = mask[w];
         if (mk != 0ull && (mk & below) == 0ull) {
           cursor[w] += __popcll(mk);
@@ -283,8 +296,8 @@ __global__ void k_units(const int32_t* __restrict__ nu_scan, const int32_t* __re
 hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
                               hipStream_t st) {
   IndexPtrs p = index_ptrs(L, index_ws);
-  const size_t lds_hist = (size_t)L.b_cap * 4 + 256 * (size_t)(L.topk + 1) * 4;
-  const size_t lds_scat = (size_t)L.b_cap * 12 + 64 * (size_t)(L.topk + 1) * 4;
+  const size_t lds_hist = (size_t)L.b_cap * 4 + 256 * (size_t)(L.topk_in + 1) * 4;
+  const size_t lds_scat = (size_t)L.b_cap * 12 + 64 * (size_t)(L.topk_in + 1) * 4;
   if (lds_hist > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)k_hist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_hist);
     if (e != hipSuccess) return e;
@@ -303,12 +316,13 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
                      p.chunk_off, nc); }
   { ProfScope ps(KID_INDEX_HIST, st);
   hipLaunchKernelGGL(k_hist, dim3(L.n_chunks, L.hkv), dim3(256), lds_hist, st, idx, cu, p.blk_base, L.nseq, L.T, L.hkv,
-                     L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off); }
+                     L.topk_in, L.sub, L.causal, L.b_cap, L.n_chunks, p.chunk_off); }
   { ProfScope ps(KID_INDEX_SCAN, st);
   scan_exclusive(p.chunk_off, nc, p.scan_tmp, st); }
   { ProfScope ps(KID_INDEX_SCATTER, st);
   hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
-                     L.hkv, L.topk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask, p.slotpos); }
+                     L.hkv, L.topk_in, L.sub, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask,
+                     p.slotpos); }
   const int nl1 = L.n_lists + 1;
   { ProfScope ps(KID_INDEX_FINALIZE, st);
   hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.chunk_off, L.n_lists, L.n_chunks, p.cnt,

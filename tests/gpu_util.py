@@ -28,7 +28,7 @@ class Case:
         self.idx = torch.from_numpy(w.idx).cuda()
         self.cu = torch.from_numpy(w.cu_seqlens).cuda()
         self.attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal,
-                                     scale=scale, bwd=bwd)
+                                     scale=scale, bwd=bwd, block=w.block)
 
     def host_f64(self):
         w = self.w

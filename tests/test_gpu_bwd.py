@@ -15,7 +15,7 @@ def _run(w, scale=0.0, oracle_scale=None):
     o, lse = c.forward()
     dq, dk, dv = c.backward(o, lse)
     Q, K, V, dO = c.host_f64()
-    rq, rk, rv = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, causal=w.causal, scale=oracle_scale)
+    rq, rk, rv = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, causal=w.causal, scale=oracle_scale, block=w.block)
     assert_close("dQ", to_f64(dq), rq, TOL_GRAD)
     assert_close("dK", to_f64(dk), rk, TOL_GRAD)
     assert_close("dV", to_f64(dv), rv, TOL_GRAD)

@@ -17,7 +17,7 @@ def test_forward_matches_oracle(name):
     c = Case(w, bwd=False)
     o, lse = c.forward()
     Q, K, V, _ = c.host_f64()
-    O_ref, LSE_ref = orc.forward(Q, K, V, w.idx, w.cu_seqlens, causal=w.causal)
+    O_ref, LSE_ref = orc.forward(Q, K, V, w.idx, w.cu_seqlens, causal=w.causal, block=w.block)
     assert_close("O", to_f64(o), O_ref, TOL_O)
     assert_lse_close(to_f64(lse), LSE_ref)
 

@@ -12,11 +12,13 @@ pytestmark = pytest.mark.gpu
 def _compare(w, idx_override=None):
     import paper_2508_18224_amd as nsa
     idx = w.idx if idx_override is None else idx_override
-    attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, bwd=False)
+    attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, bwd=False,
+                            block=w.block)
     attn.build_index(torch.from_numpy(idx).cuda(), torch.from_numpy(w.cu_seqlens).cuda())
     torch.cuda.synchronize()
     cnt, off, qlist, qslot, vmask, bcap = attn.index_arrays()
-    rc, ro, rl, rs, rv = orc.invert_index(idx, w.cu_seqlens, causal=w.causal)
+    # a 128-token block is its two 64-token halves: the library's lists are those of the re-indexed table
+    rc, ro, rl, rs, rv = orc.invert_index(wl.expand_blocks(idx, w.block // 64), w.cu_seqlens, causal=w.causal)
     b_tot = rc.shape[1]
     assert bcap >= b_tot
     assert np.array_equal(cnt[:, :b_tot], rc) and not cnt[:, b_tot:].any()
@@ -42,6 +44,8 @@ def test_inversion_drop_rules(causal):
     w = wl.Workload("adv", [1000, 77, 640], hq=4, hkv=2, topk=12, causal=causal, seed=5)
     wl.realise(w, tensors=False)
     idx = wl.draw_adversarial_indices(np.random.default_rng(8), w.seqlens, w.hkv, w.topk)
+    _compare(w, idx)
+    w.block = 128                                   # same rows read as ids of 128-token blocks
     _compare(w, idx)
 
 

@@ -12,7 +12,7 @@ def test_rows_are_causal_distinct_and_forced(name):
     assert idx.shape == (w.total_tokens, w.hkv, w.topk) and idx.dtype == np.int32
     tok = np.arange(w.total_tokens)
     seq = np.searchsorted(cu, tok, side="right") - 1
-    cur = (tok - cu[seq]) // 64
+    cur = (tok - cu[seq]) // w.block
     for t in range(0, w.total_tokens, 7):
         for j in range(w.hkv):
             row = idx[t, j]

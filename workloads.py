@@ -73,6 +73,16 @@ class Workload:
         return self.hq // self.hkv
 
 
+def expand_blocks(idx: np.ndarray, sub: int) -> np.ndarray:
+    """Rewrite a table of B_K = 64*sub block ids as the equivalent table of 64-token block ids (each id x becomes
+    x*sub .. x*sub + sub - 1, negative ids stay negative); pure re-indexing, used to state what a 128-token
+    selection means in 64-token blocks."""
+    T, hkv, k = idx.shape
+    out = np.repeat(idx.astype(np.int64), sub, axis=2) * sub + np.tile(np.arange(sub), k)[None, None, :]
+    out[np.repeat(idx, sub, axis=2) < 0] = -1
+    return out.astype(np.int32)
+
+
 def _floyd_subsets(rng: np.random.Generator, n: np.ndarray, m: int) -> np.ndarray:
     """Uniform random subsets without replacement, one per row (Floyd's algorithm, vectorised over rows).
 
@@ -177,6 +187,8 @@ def named(name: str) -> Workload:
         return Workload(name, varlen_lengths(1004), hq=16, hkv=16, topk=16, seed=1004)
     if name == "llama70b_128k":   # config 5
         return Workload(name, [131072], hq=64, hkv=8, topk=16, sink=True, recent=2, seed=1005)
+    if name == "headline_b128":   # the headline shape at the paper's second setting (B_K, T) = (128, 8)
+        return Workload(name, [65536], hq=32, hkv=8, topk=8, sink=True, block=128, seed=1006)
     raise KeyError(name)
 
 
@@ -200,10 +212,14 @@ def small(name: str) -> Workload:
         return Workload(name, [2500], hq=4, hkv=1, topk=32, sink=True, seed=16)
     if name == "g3_k1":
         return Workload(name, [777], hq=3, hkv=1, topk=1, seed=17)
+    if name == "b128_g4":       # the paper's second setting (B_K, T) = (128, 8)
+        return Workload(name, [2100], hq=8, hkv=2, topk=8, sink=True, block=128, seed=18)
+    if name == "b128_varlen":
+        return Workload(name, [700, 129, 128, 1, 515], hq=2, hkv=2, topk=4, block=128, seed=19)
     raise KeyError(name)
 
 
-SMALL_NAMES = ["g4", "g7", "g1_varlen", "g8", "g2_noncausal", "g4_k32", "g3_k1"]
+SMALL_NAMES = ["g4", "g7", "g1_varlen", "g8", "g2_noncausal", "g4_k32", "g3_k1", "b128_g4", "b128_varlen"]
 
 
 def draw_adversarial_indices(rng: np.random.Generator, seqlens: Sequence[int], hkv: int, topk: int,
