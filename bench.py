@@ -43,10 +43,10 @@ def cpu_baseline(w, budget_tokens: int):
     tokens = [int(x) for x in np.linspace(0, T - 1, budget_tokens).astype(np.int64)]
     with threadpool_limits(limits=1):
         t0 = time.perf_counter()
-        orc.forward(Q, K, V, w.idx, w.cu_seqlens, causal=w.causal, tokens=tokens)
-        orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, causal=w.causal, tokens=tokens)
+        orc.forward(Q, K, V, w.idx, w.cu_seqlens, causal=w.causal, tokens=tokens, block=w.block)
+        orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, causal=w.causal, tokens=tokens, block=w.block)
         dt = time.perf_counter() - t0
-    f, b = effective_flops(len(tokens), w.hq, w.topk)
+    f, b = effective_flops(len(tokens), w.hq, w.topk, block=w.block)
     return {"value": (f + b) / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
             "sample": f"{len(tokens)} evenly spaced query tokens of the same workload, all heads, forward + "
                       f"backward contributions of those rows, {dt:.1f} s"}
@@ -85,7 +85,7 @@ def main():
     q, k, v, do = (dev(x) for x in (w.q, w.k, w.v, w.do))
     idx = torch.from_numpy(w.idx).cuda()
     cu = torch.from_numpy(w.cu_seqlens).cuda()
-    attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal)
+    attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, block=w.block)
     o = torch.empty_like(q)
     lse = torch.empty(T, w.hq, dtype=torch.float32, device="cuda")
     grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
@@ -113,7 +113,7 @@ def main():
     prof = nsa.profile_collect()
     nsa.profile_enable(0)
 
-    f, b = effective_flops(T, w.hq, w.topk)
+    f, b = effective_flops(T, w.hq, w.topk, block=w.block)
     per_kernel = {name: tot / n for name, (tot, n) in prof.items() if n}
     for name, avg in sorted(per_kernel.items(), key=lambda kv: -kv[1]):
         print(f"[bench] {name:16s} {avg:9.3f} ms/launch", file=sys.stderr)
@@ -135,7 +135,7 @@ def main():
         "value": (f + b) / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: N={T}, hq={w.hq}, hkv={w.hkv}, g={w.g}, topk={w.topk}, block=64, "
+        "config": {"workload": f"{args.workload}: N={T}, hq={w.hq}, hkv={w.hkv}, g={w.g}, topk={w.topk}, block={w.block}, "
                                f"d=128, causal, seed {w.seed}",
                    "step": "index inversion + forward (main, merge) + backward (delta, main, dQ reduce, dK/dV reduce)"},
         "frac_of_bf16_mfma_peak": (f + b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

@@ -189,6 +189,11 @@ def named(name: str) -> Workload:
         return Workload(name, [131072], hq=64, hkv=8, topk=16, sink=True, recent=2, seed=1005)
     if name == "headline_b128":   # the headline shape at the paper's second setting (B_K, T) = (128, 8)
         return Workload(name, [65536], hq=32, hkv=8, topk=8, sink=True, block=128, seed=1006)
+    if name.startswith("grid_"):  # the paper's kernel grid (Sec. 4.1): grid_g<g>_b<B_K>_n<N in K>, 32 query heads
+        parts = dict((p[0], int(p[1:])) for p in name.split("_")[1:])
+        g, block, n = parts["g"], parts["b"], parts["n"] * 1024
+        return Workload(name, [n], hq=32, hkv=32 // g, topk=1024 // block, sink=True, block=block,
+                        seed=2000 + 100 * g + block + parts["n"])
     raise KeyError(name)
 
 
