@@ -44,3 +44,30 @@ def test_backward_adversarial_rows_and_scale():
     w.idx[100:140] = -1
     _, _, (dq, _, _) = _run(w, scale=0.05, oracle_scale=0.05)
     assert np.all(to_f64(dq)[100:140] == 0)
+
+
+@pytest.mark.parametrize("hq,hkv", [(2, 1), (6, 2), (5, 1), (18, 3), (24, 4)])
+def test_other_group_sizes(hq, hkv):
+    """g = 2, 3, 5, 6 and kv-head counts that do not divide the number of XCDs."""
+    print("case heads", hq, hkv, flush=True)
+    _run(wl.realise(wl.Workload("g", [1111], hq=hq, hkv=hkv, topk=12, sink=True, recent=2, seed=100 + hq)))
+
+
+def test_empty_sequences_in_a_packed_batch():
+    """Zero-length sequences own no blocks and no tokens; their neighbours are unaffected."""
+    print("case empty sequences", flush=True)
+    w = wl.Workload("e", [300, 0, 0, 129, 0, 64, 1], hq=4, hkv=2, topk=5, seed=41)
+    _run(wl.realise(w))
+
+
+def test_two_calls_share_nothing_but_the_index():
+    """Forward with a cached index (rebuild_index = 0) equals forward with a rebuild; backward twice is bit-equal."""
+    print("case cached index", flush=True)
+    w = wl.realise(wl.small("g4"))
+    c = Case(w)
+    o1, l1 = c.forward(rebuild=True)
+    o2, l2 = c.forward(rebuild=False)
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+    g1 = c.backward(o1, l1)
+    g2 = c.backward(o1, l1)
+    assert all(torch.equal(a, b) for a, b in zip(g1, g2))
