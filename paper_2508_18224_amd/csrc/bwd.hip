@@ -18,7 +18,11 @@
 
 namespace nsa {
 
-constexpr int kRowStride = 136;  // bf16 per row of the K / V / Q / dO / P^T / dS^T tiles in LDS (128 + 8 pad)
+// bf16 per row of the K / V / Q / dO / P^T / dS^T tiles in LDS: 128 + 24 pad.  A 304-byte row pitch puts the rows
+// of both access shapes used here (16-byte operand reads down a column of rows, and the 4-row x 32-byte footprint
+// of a transposing read) on disjoint banks; with 128 + 8 the transposing reads conflicted two-way (measured:
+// 45 % of LDS cycles were bank conflicts, 8 % kernel time).
+constexpr int kRowStride = 152;
 constexpr int kTileRows = 128;
 
 constexpr int kLdsK = 0;
@@ -28,7 +32,8 @@ constexpr int kLdsDO = kLdsQ + kTileRows * kRowStride * 2;
 constexpr int kLdsPt = kLdsDO + kTileRows * kRowStride * 2;
 constexpr int kLdsDSt = kLdsPt + kBlock * kRowStride * 2;
 constexpr int kLdsEnt = kLdsDSt + kBlock * kRowStride * 2;
-constexpr int kLdsBwdBytes = kLdsEnt + kBwdUnit * 4;  // 147456
+constexpr int kLdsBwdBytes = kLdsEnt + kBwdUnit * 4;  // 163840: all of the CU's 160 KB
+static_assert(kLdsBwdBytes <= 160 * 1024, "backward tile set must fit the CU's LDS");
 
 // ds_read_b64_tr_b16: every lane passes the address of 8 bytes (four 16-bit elements); within each group of
 // 16 lanes, lane i receives element (i % 4) of the 8 bytes addressed by lanes 4e + i / 4, for e = 0..3.  With
