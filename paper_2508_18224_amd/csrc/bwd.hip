@@ -13,7 +13,8 @@
 //                     through LDS copies of P^T, dS^T, Q and dO.  Partial dQ rows go to the (token, head, slot)
 //                     workspace; the unit's dK_i, dV_i go to a per-unit fp32 buffer.
 //   k_bwd_dq_reduce   dQ[t,h] = sum over kept slots of the partial rows
-//   k_bwd_dkv_reduce  dK_i, dV_i = sum over the list's units in unit order (fixed order: bit-reproducible)
+//   k_bwd_dkv_reduce  dK_i, dV_i = sum over the list's units in unit order (fixed order: bit-reproducible); a list
+//                     that fitted one unit was already written by that unit, a list with no entry gets zeros
 #include "common.h"
 
 namespace nsa {
@@ -82,7 +83,8 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
            const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
            const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
-           const int32_t* __restrict__ qlist, bf16_t* __restrict__ dqpart, float* __restrict__ dkv_part) {
+           const int32_t* __restrict__ qlist, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
+           float* __restrict__ dkv_part, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kLdsK);
   bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kLdsV);
@@ -289,7 +291,21 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     }
     wave_sync_bwd();
   }
-  // unit partial: [u][0 = dK, 1 = dV][key][d] fp32
+  if (nu_scan[L + 1] - nu_scan[L] == 1) {
+    // the whole list fitted this unit: dK_i, dV_i are final, write them as bf16 (keys of a ragged tail excluded)
+    bf16_t* outk = dK + ((size_t)tok0 * P.hkv + j) * kD + 32 * dsl + col;
+    bf16_t* outv = dV + ((size_t)tok0 * P.hkv + j) * kD + 32 * dsl + col;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = 32 * mb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
+      if (key < blen) {
+        outk[(size_t)key * P.hkv * kD] = (bf16_t)dkacc[v];
+        outv[(size_t)key * P.hkv * kD] = (bf16_t)dvacc[v];
+      }
+    }
+    return;
+  }
+  // unit partial: [u][0 = dK, 1 = dV][key][d] fp32, summed by k_bwd_dkv_reduce in unit order
   float* outk = dkv_part + (size_t)u * 2 * kBlock * kD + 32 * dsl + col;
   float* outv = outk + kBlock * kD;
 #pragma unroll
@@ -348,6 +364,7 @@ k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* 
   if (blen == 0) return;
   const int tok0 = blk_tok0[gb];
   const int u0 = nu_scan[L], u1 = nu_scan[L + 1];
+  if (u1 - u0 == 1) return;  // a single unit wrote the final values itself
   bf16_t* out = which ? dV : dK;
   const int d4 = (threadIdx.x & 31) * 4;
   for (int key = threadIdx.x >> 5; key < blen; key += 8) {
@@ -380,7 +397,7 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
   { ProfScope ps(KID_BWD_MAIN, st);
   hipLaunchKernelGGL(k_bwd_main, dim3(L.bwd_units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, (const float*)delta, p.hdr, p.b_list,
-                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, (bf16_t*)dqpart, dkv_part); }
+                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.b_nu, (bf16_t*)dqpart, dkv_part, (bf16_t*)dK, (bf16_t*)dV); }
   { ProfScope ps(KID_BWD_DQ_REDUCE, st);
   hipLaunchKernelGGL(k_bwd_dq_reduce, dim3(row_blocks), dim3(256), 0, st, P, (const bf16_t*)dqpart, p.vmask,
                      p.slotpos, (bf16_t*)dQ); }
