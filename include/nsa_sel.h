@@ -35,7 +35,7 @@ extern "C" {
 
 #define NSA_SEL_OK            0
 #define NSA_SEL_EINVAL       -1   /* null pointer, g outside [1,8], hq % hkv != 0, nseq < 1, negative sizes    */
-#define NSA_SEL_EUNSUPPORTED -2   /* d != 128, block not 64/128, topk*block/64 outside [1,32], too many tokens */
+#define NSA_SEL_EUNSUPPORTED -2   /* d != 128, block not 64 or 128, topk outside [1,32], too many tokens      */
 #define NSA_SEL_EWORKSPACE   -3   /* a workspace is smaller than nsa_sel_workspace_bytes reports              */
 #define NSA_SEL_EHIP         -4   /* the HIP runtime refused a launch or attribute                            */
 
@@ -44,9 +44,8 @@ typedef struct {
   int32_t nseq;           /* number of packed sequences, >= 1                                                */
   int32_t hq, hkv;        /* query / KV heads; g = hq / hkv must be an integer in [1, 8]                     */
   int32_t d;              /* head dimension; 128 only (every experiment of the paper uses d = 128)           */
-  int32_t block;          /* B_K; 64 or 128 (the paper's two settings, Sec. 4.1).  A 128-token block is handled
-                             as its two 64-token halves, each with a partial-result slot of its own          */
-  int32_t topk;           /* T, selected blocks per (token, KV head); topk * block / 64 must be in 1..32     */
+  int32_t block;          /* B_K; 64 or 128 (the paper's two settings, Sec. 4.1)                             */
+  int32_t topk;           /* T, selected blocks per (token, KV head); 1..32                                  */
   int32_t causal;         /* 1: key u visible to token t only if u <= t (per sequence); 0: no mask           */
   float   scale;          /* softmax scale; <= 0 selects 1/sqrt(d) (Eq. (1))                                 */
   int32_t max_seqlen;     /* upper bound of the longest sequence; informational, may be 0                    */
@@ -62,17 +61,15 @@ int nsa_sel_workspace_bytes(const nsa_sel_shape* shape, size_t* fwd_bytes, size_
 
 /* Index inversion (Sec. 3.2, "index tensors ... pre-computed from the NSA sparse selection tensor T"):
  * histogram -> exclusive scan -> ordered scatter.  For every list L = kv_head * b_cap + global_block
- * (b_cap = total_tokens / 64 + nseq; global blocks are 64-token blocks numbered consecutively over the packed
- * sequences; lists past the real block count are empty) the result holds the ascending tokens that validly
- * select the block and, per entry, its slot: the column of idx of the first occurrence when block == 64, and
- * 2 * column + half when block == 128 (half 0/1 = first/second 64 tokens of the selected block).
- * Deterministic and bit-reproducible. */
+ * (b_cap = total_tokens / block + nseq; global blocks number the blocks of the packed sequences consecutively;
+ * lists past the real block count are empty) the result holds the ascending tokens that validly select the
+ * block and, per entry, the column of idx of the first occurrence.  Deterministic and bit-reproducible. */
 int nsa_sel_build_index(const nsa_sel_shape* shape, const int32_t* idx, const int32_t* cu_seqlens,
                         void* index_ws, size_t index_bytes, void* stream);
 
 /* Device pointers into a built index workspace (for inspection and tests): cnt int32 [hkv * b_cap],
  * off int32 [hkv * b_cap + 1] (exclusive prefix of cnt), qlist int32 [off[last]] token ids, qslot int32
- * [off[last]] slots, vmask uint32 [total_tokens * hkv] (bit v set: slot v of the row was kept).
+ * [off[last]] columns, vmask uint32 [total_tokens * hkv] (bit m set: column m of the row was kept).
  * *b_cap receives the list stride.  Any output pointer may be NULL. */
 int nsa_sel_index_view(const nsa_sel_shape* shape, const void* index_ws, const int32_t** cnt, const int32_t** off,
                        const int32_t** qlist, const int32_t** qslot, const uint32_t** vmask, int32_t* b_cap);

@@ -13,12 +13,12 @@ static int check_shape(const nsa_sel_shape* s) {
   const int g = s->hq / s->hkv;
   if (g < 1 || g > 8) return NSA_SEL_EINVAL;
   if (s->d != kD || (s->block != kBlock && s->block != 2 * kBlock)) return NSA_SEL_EUNSUPPORTED;
-  if (s->topk < 1 || s->topk * (s->block / kBlock) > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
+  if (s->topk < 1 || s->topk > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
   if (s->nseq > (1 << 20)) return NSA_SEL_EUNSUPPORTED;
-  const int64_t b_cap = (int64_t)s->total_tokens / kBlock + s->nseq;
+  const int64_t b_cap = (int64_t)s->total_tokens / s->block + s->nseq;
   // LDS tables of the inversion (12 bytes per block) must fit in one CU's 160 KB
   if (b_cap * 12 + 64 * (int64_t)(s->topk + 1) * 4 > 160 * 1024) return NSA_SEL_EUNSUPPORTED;
-  const int64_t p_max = (int64_t)s->total_tokens * s->hkv * s->topk * (s->block / kBlock);
+  const int64_t p_max = (int64_t)s->total_tokens * s->hkv * s->topk;
   if (p_max >= ((int64_t)1 << 31) - 4096) return NSA_SEL_EUNSUPPORTED;
   const int64_t n_chunks = ((int64_t)s->total_tokens + kChunkTokens - 1) / kChunkTokens;
   if (b_cap * s->hkv * (n_chunks > 0 ? n_chunks : 1) >= ((int64_t)1 << 31) - 4096) return NSA_SEL_EUNSUPPORTED;
@@ -30,11 +30,10 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.T = s->total_tokens;
   L.nseq = s->nseq;
   L.hkv = s->hkv;
-  L.topk_in = s->topk;
-  L.sub = s->block / kBlock;
-  L.topk = s->topk * L.sub;
+  L.topk = s->topk;
+  L.bk = s->block;
   L.causal = s->causal ? 1 : 0;
-  L.b_cap = s->total_tokens / kBlock + s->nseq;
+  L.b_cap = s->total_tokens / s->block + s->nseq;
   L.n_lists = s->hkv * L.b_cap;
   L.n_chunks = (s->total_tokens + kChunkTokens - 1) / kChunkTokens;
   if (L.n_chunks < 1) L.n_chunks = 1;
@@ -76,12 +75,13 @@ static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
   P.topk = L.topk;
   P.causal = s->causal ? 1 : 0;
   P.b_cap = L.b_cap;
+  P.bk = L.bk;
   P.scale = s->scale > 0.f ? s->scale : 0.08838834764831845f;  // 1/sqrt(128)
   return P;
 }
 
-static size_t partial_rows(const nsa_sel_shape* s) {  // one per (token, query head, 64-token sub-block slot)
-  return (size_t)s->total_tokens * s->hq * s->topk * (s->block / kBlock);
+static size_t partial_rows(const nsa_sel_shape* s) {  // one per (token, query head, selected block)
+  return (size_t)s->total_tokens * s->hq * s->topk;
 }
 
 static size_t fwd_ws_bytes(const nsa_sel_shape* s) {
@@ -92,7 +92,7 @@ static size_t fwd_ws_bytes(const nsa_sel_shape* s) {
 static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L) {
   const size_t rows = partial_rows(s);
   return align256(rows * kD * 2) + align256((size_t)s->total_tokens * s->hq * 4) +
-         align256((size_t)L.bwd_units_max * 2 * kBlock * kD * 4);
+         align256((size_t)L.bwd_units_max * 2 * L.bk * kD * 4);
 }
 }  // namespace nsa
 
@@ -185,7 +185,7 @@ const char* nsa_sel_strerror(int code) {
   switch (code) {
     case NSA_SEL_OK: return "ok";
     case NSA_SEL_EINVAL: return "invalid argument (null pointer, head counts, nseq)";
-    case NSA_SEL_EUNSUPPORTED: return "unsupported shape (d must be 128, block 64 or 128, topk * block / 64 in 1..32, size limits)";
+    case NSA_SEL_EUNSUPPORTED: return "unsupported shape (d must be 128, block 64 or 128, topk 1..32, size limits)";
     case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes)";
     case NSA_SEL_EHIP: return "HIP runtime error at launch";
     default: return "unknown nsa_sel error code";

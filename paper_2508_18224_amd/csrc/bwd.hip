@@ -78,6 +78,11 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
 //   keys/chans  (mb = w / 4, ds = w % 4): dV_i, dK_i accumulators for keys 32 mb.. and channels 32 ds..
 //   rows/chans  (rb = w / 2, dh = w % 2): dQ^T for rows 32 rb.. and channels 64 dh..; also stages / prefetches
 //                                         exactly that part of the Q and dO tiles and stores that part of dQ
+// NH = B_K / 64.  With B_K = 128 the block is worked through as two 64-key halves per tile: the K/V tiles in LDS hold
+// one half at a time (re-staged from registers that were loaded one half ahead; the block stays L2-resident), the
+// Q and dO tiles are gathered once per tile, dQ^T accumulates over both halves, and each half has its own dK/dV
+// accumulators.
+template <int NH>
 __global__ void __launch_bounds__(512)
 k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
            const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
@@ -102,27 +107,41 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int e0 = u_start[u];
   const int ne = min(kBwdUnit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int col = lane & 31, qh = lane >> 5;  // not const: see the top of the tile loop
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-  {  // K_i, V_i -> LDS, row-major (rows past the end of a ragged block are zero)
-    const int key = tid >> 3, d0 = (tid & 7) * 16;
-    const size_t o = ((size_t)(tok0 + key) * P.hkv + j) * kD + d0;
+  // K/V staging: thread -> (key of the half, 16 channels); rows past the end of a ragged block are zero
+  const int skey = tid >> 3, sd0 = (tid & 7) * 16;
+  bf16x8 kreg[2], vreg[2];
+  auto load_kv = [&](int hf) {
+    int key = 64 * hf + skey;
+    asm volatile("" : "+v"(key));  // recompute the addresses at each use instead of keeping them in registers
+    const size_t o = ((size_t)(tok0 + key) * P.hkv + j) * kD + sd0;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const bf16x8 kv = key < blen ? *reinterpret_cast<const bf16x8*>(K + o + 8 * i) : zero8;
-      const bf16x8 vv = key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
-      *reinterpret_cast<bf16x8*>(&Ks[key * kRowStride + d0 + 8 * i]) = kv;
-      *reinterpret_cast<bf16x8*>(&Vs[key * kRowStride + d0 + 8 * i]) = vv;
+      kreg[i] = key < blen ? *reinterpret_cast<const bf16x8*>(K + o + 8 * i) : zero8;
+      vreg[i] = key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
     }
-  }
-  for (int i = tid; i < ne; i += 512) ent[i] = qlist[e0 + i];
-  f32x16 dkacc, dvacc;
+  };
+  auto stage_kv = [&]() {
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    dkacc[v] = 0.f;
-    dvacc[v] = 0.f;
-  }
+    for (int i = 0; i < 2; ++i) {
+      *reinterpret_cast<bf16x8*>(&Ks[skey * kRowStride + sd0 + 8 * i]) = kreg[i];
+      *reinterpret_cast<bf16x8*>(&Vs[skey * kRowStride + sd0 + 8 * i]) = vreg[i];
+    }
+  };
+  load_kv(0);
+  if (NH == 1) stage_kv();
+  for (int i = tid; i < ne; i += 512) ent[i] = qlist[e0 + i];
+  f32x16 dkacc[NH], dvacc[NH];
+#pragma unroll
+  for (int hf = 0; hf < NH; ++hf)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      dkacc[hf][v] = 0.f;
+      dvacc[hf][v] = 0.f;
+    }
   __syncthreads();
 
   const int rows_total = ne * P.g;
@@ -134,9 +153,9 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // this lane's share of a transposing LDS read of four rows x 16 columns: its group's 16 columns start at
   // 16 (grp & 1) of a 32-column slice, the group's lanes belong to MFMA lane half grp / 2
   const int grp = lane >> 4, sl = lane & 15;
-  const int tr_lane = (sl >> 2) * kRowStride + 16 * (grp & 1) + 4 * (sl & 3);
+  int tr_lane = (sl >> 2) * kRowStride + 16 * (grp & 1) + 4 * (sl & 3);
   // staging layout of the rows/chans role: 8 lanes x 16 B cover the 64 channels of a row half, 8 rows per access
-  const int srow = lane >> 3, schunk = 64 * half + (lane & 7) * 8;
+  int srow = lane >> 3, schunk = 64 * half + (lane & 7) * 8;
   bf16_t* Qmine = Qs + (32 * rb) * kRowStride;
   bf16_t* dOmine = dOs + (32 * rb) * kRowStride;
   const int q4 = 8 / P.g, r4 = 8 - q4 * P.g;  // row -> (entry, head) stepping by 8 rows without dividing
@@ -178,6 +197,10 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   issue_rows(0);
 
   for (int tile0 = 0; tile0 < rows_total; tile0 += kTileRows) {
+    // Register budget of the two-half variant: the lane-dependent index pieces are made opaque here so that the
+    // ~100 LDS addresses derived from them are recomputed where they are used instead of being kept in registers
+    // across the whole loop (the one-half variant has the room and keeps them).
+    if (NH == 2) asm volatile("" : "+v"(col), "+v"(qh), "+v"(tr_lane), "+v"(srow), "+v"(schunk));
     // stage this wave's part of the tile; then let the next tile's rows fly while this one computes
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -185,90 +208,108 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       *reinterpret_cast<uint4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
     }
     const float lse2 = lse2_n, dl = dl_n;
-    if (tile0 + kTileRows < rows_total) issue_rows(tile0 + kTileRows);
-    __syncthreads();
-
-    {  // role rows/keys: S^T = K_i Q^T, dP^T = V_i dO^T, P, dS for rows 32 rb.., keys 32 half..
-      const int r = tile0 + 32 * rb + col;
-      const bool valid = r < rows_total;
-      const int t = valid ? ent[r / P.g] : -1;
-      f32x16 sacc, dpacc;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        sacc[v] = 0.f;
-        dpacc[v] = 0.f;
-      }
-      const bf16_t* qrow = Qmine + col * kRowStride + 8 * qh;
-      const bf16_t* drow = dOmine + col * kRowStride + 8 * qh;
-      const bf16_t* krow = Ks + (32 * half + col) * kRowStride + 8 * qh;
-      const bf16_t* vrow = Vs + (32 * half + col) * kRowStride + 8 * qh;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
-        const bf16x8 dof = *reinterpret_cast<const bf16x8*>(drow + 16 * s);
-        const bf16x8 kfa = *reinterpret_cast<const bf16x8*>(krow + 16 * s);
-        const bf16x8 vfa = *reinterpret_cast<const bf16x8*>(vrow + 16 * s);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa, qf, sacc, 0, 0, 0);
-        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa, dof, dpacc, 0, 0, 0);
-      }
-      int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
-      if (!valid) lim = 0;
-      bf16_t* pdst = Pt + 32 * rb + col;
-      bf16_t* sdst = dSt + 32 * rb + col;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = 32 * half + 8 * (v >> 2) + 4 * qh + (v & 3);
-        const float p = key < lim ? __builtin_amdgcn_exp2f(sacc[v] * c2 - lse2) : 0.f;
-        const float ds = p * (dpacc[v] - dl) * P.scale;
-        pdst[key * kRowStride] = (bf16_t)p;
-        sdst[key * kRowStride] = (bf16_t)ds;
-      }
-    }
-    __syncthreads();
-    {  // role keys/chans: dV_i += P^T dO, dK_i += dS^T Q over the tile's 128 rows.  A operands (lane = key,
-       // elements = 8 rows) are plain reads of P^T / dS^T; B operands (lane = channel, elements = 8 rows) are
-       // transposing reads of the row-major dO / Q tiles.
-      const int tr_row = tr_lane + 8 * (grp >> 1) * kRowStride + 32 * dsl;
-      const bf16_t* parow = Pt + (32 * mb2 + col) * kRowStride + 8 * qh;
-      const bf16_t* sarow = dSt + (32 * mb2 + col) * kRowStride + 8 * qh;
-#pragma unroll
-      for (int qs = 0; qs < 8; ++qs) {
-        const bf16x4 d0 = lds_read_tr(&dOs[16 * qs * kRowStride + tr_row]);
-        const bf16x4 d1 = lds_read_tr(&dOs[(16 * qs + 4) * kRowStride + tr_row]);
-        const bf16x4 q0 = lds_read_tr(&Qs[16 * qs * kRowStride + tr_row]);
-        const bf16x4 q1 = lds_read_tr(&Qs[(16 * qs + 4) * kRowStride + tr_row]);
-        const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 pa = *reinterpret_cast<const bf16x8*>(parow + 16 * qs);
-        const bf16x8 sa = *reinterpret_cast<const bf16x8*>(sarow + 16 * qs);
-        dvacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc, 0, 0, 0);
-        dkacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qb, dkacc, 0, 0, 0);
-      }
-    }
+    const bool more = tile0 + kTileRows < rows_total;
+    if (NH == 1 && more) issue_rows(tile0 + kTileRows);
+    const int r = tile0 + 32 * rb + col;
+    const bool valid = r < rows_total;
+    const int t = valid ? ent[r / P.g] : -1;
+    int lim = P.causal ? min(blen, t - tok0 + 1) : blen;  // keys [0, lim) of the block are visible to this row
+    if (!valid) lim = 0;
     f32x16 dqacc[2];
-    {  // role rows/chans: dQ^T[64 half.. , 32 rb..] = K_i^T dS^T, contraction over the 64 keys in natural order.
-       // A = K^T (lane = channel, elements = 8 keys) and B = dS^T (lane = row, elements = 8 keys) both come from
-       // row-major tiles (K [key][chan], dS^T [key][row]) by transposing reads.
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < 2; ++db)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
-      const int tr_key = tr_lane + 8 * (grp >> 1) * kRowStride;
+      for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
+
 #pragma unroll
-      for (int sp = 0; sp < 4; ++sp) {
-        const bf16x4 b0 = lds_read_tr(&dSt[16 * sp * kRowStride + tr_key + 32 * rb]);
-        const bf16x4 b1 = lds_read_tr(&dSt[(16 * sp + 4) * kRowStride + tr_key + 32 * rb]);
-        const bf16x8 dsb = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+    for (int hf = 0; hf < NH; ++hf) {
+      if (NH == 2) stage_kv();  // this half's K/V (loaded ahead into registers) -> LDS
+      __syncthreads();
+      // register budget (two waves per SIMD): the first half carries the second half's K/V in flight, the second
+      // half carries the next tile's Q / dO rows; the first half's K/V is re-fetched (L2) behind the dQ store
+      if (NH == 2 && hf == 0) load_kv(1);
+      if (NH == 2 && hf == 1 && more) issue_rows(tile0 + kTileRows);
+
+      {  // role rows/keys: S^T = K_i Q^T, dP^T = V_i dO^T, P, dS for rows 32 rb.., keys 64 hf + 32 half..
+        f32x16 sacc, dpacc;
 #pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          const bf16x4 a0 = lds_read_tr(&Ks[16 * sp * kRowStride + tr_key + 64 * half + 32 * db]);
-          const bf16x4 a1 = lds_read_tr(&Ks[(16 * sp + 4) * kRowStride + tr_key + 64 * half + 32 * db]);
-          const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-          dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsb, dqacc[db], 0, 0, 0);
+        for (int v = 0; v < 16; ++v) {
+          sacc[v] = 0.f;
+          dpacc[v] = 0.f;
+        }
+        const bf16_t* qrow = Qmine + col * kRowStride + 8 * qh;
+        const bf16_t* drow = dOmine + col * kRowStride + 8 * qh;
+        const bf16_t* krow = Ks + (32 * half + col) * kRowStride + 8 * qh;
+        const bf16_t* vrow = Vs + (32 * half + col) * kRowStride + 8 * qh;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
+          const bf16x8 dof = *reinterpret_cast<const bf16x8*>(drow + 16 * s);
+          const bf16x8 kfa = *reinterpret_cast<const bf16x8*>(krow + 16 * s);
+          const bf16x8 vfa = *reinterpret_cast<const bf16x8*>(vrow + 16 * s);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa, qf, sacc, 0, 0, 0);
+          dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa, dof, dpacc, 0, 0, 0);
+          if (NH == 2 && (s & 1)) __builtin_amdgcn_sched_barrier(0);  // bound the operands in flight (register budget)
+        }
+        bf16_t* pdst = Pt + 32 * rb + col;
+        bf16_t* sdst = dSt + 32 * rb + col;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = 32 * half + 8 * (v >> 2) + 4 * qh + (v & 3);
+          const float p = 64 * hf + key < lim ? __builtin_amdgcn_exp2f(sacc[v] * c2 - lse2) : 0.f;
+          const float ds = p * (dpacc[v] - dl) * P.scale;
+          pdst[key * kRowStride] = (bf16_t)p;
+          sdst[key * kRowStride] = (bf16_t)ds;
         }
       }
+      __syncthreads();
+      {  // role keys/chans: dV_i += P^T dO, dK_i += dS^T Q over the tile's 128 rows.  A operands (lane = key,
+         // elements = 8 rows) are plain reads of P^T / dS^T; B operands (lane = channel, elements = 8 rows) are
+         // transposing reads of the row-major dO / Q tiles.
+        // (the transposing read takes no immediate offset; keeping its addresses opaque per phase stops the compiler
+        // from precomputing all of them outside the tile loop, which cost ~56 registers)
+        int tr_row = tr_lane + 8 * (grp >> 1) * kRowStride + 32 * dsl;
+        asm volatile("" : "+v"(tr_row));
+        const bf16_t* parow = Pt + (32 * mb2 + col) * kRowStride + 8 * qh;
+        const bf16_t* sarow = dSt + (32 * mb2 + col) * kRowStride + 8 * qh;
+#pragma unroll
+        for (int qs = 0; qs < 8; ++qs) {
+          const bf16x4 d0 = lds_read_tr(&dOs[16 * qs * kRowStride + tr_row]);
+          const bf16x4 d1 = lds_read_tr(&dOs[(16 * qs + 4) * kRowStride + tr_row]);
+          const bf16x4 q0 = lds_read_tr(&Qs[16 * qs * kRowStride + tr_row]);
+          const bf16x4 q1 = lds_read_tr(&Qs[(16 * qs + 4) * kRowStride + tr_row]);
+          const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 pa = *reinterpret_cast<const bf16x8*>(parow + 16 * qs);
+          const bf16x8 sa = *reinterpret_cast<const bf16x8*>(sarow + 16 * qs);
+          dvacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc[hf], 0, 0, 0);
+          dkacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qb, dkacc[hf], 0, 0, 0);
+          if (NH == 2 && (qs & 1)) __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      {  // role rows/chans: dQ^T[64 half.. , 32 rb..] += K_i^T dS^T, contraction over this half's 64 keys in natural
+         // order.  A = K^T (lane = channel, elements = 8 keys) and B = dS^T (lane = row, elements = 8 keys) both
+         // come from row-major tiles (K [key][chan], dS^T [key][row]) by transposing reads.
+        int tr_key = tr_lane + 8 * (grp >> 1) * kRowStride;
+        asm volatile("" : "+v"(tr_key));
+#pragma unroll
+        for (int sp = 0; sp < 4; ++sp) {
+          const bf16x4 b0 = lds_read_tr(&dSt[16 * sp * kRowStride + tr_key + 32 * rb]);
+          const bf16x4 b1 = lds_read_tr(&dSt[(16 * sp + 4) * kRowStride + tr_key + 32 * rb]);
+          const bf16x8 dsb = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+          for (int db = 0; db < 2; ++db) {
+            const bf16x4 a0 = lds_read_tr(&Ks[16 * sp * kRowStride + tr_key + 64 * half + 32 * db]);
+            const bf16x4 a1 = lds_read_tr(&Ks[(16 * sp + 4) * kRowStride + tr_key + 64 * half + 32 * db]);
+            const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+            dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsb, dqacc[db], 0, 0, 0);
+          }
+          if (NH == 2) __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      __syncthreads();
     }
-    __syncthreads();
+    if (NH == 2 && more) load_kv(0);
     // dQ rows (this wave's 32 rows x 64 channels) -> the part of the Q tile this wave staged -> 128-byte row
     // segments at the rows' list position
 #pragma unroll
@@ -296,24 +337,28 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     bf16_t* outk = dK + ((size_t)tok0 * P.hkv + j) * kD + 32 * dsl + col;
     bf16_t* outv = dV + ((size_t)tok0 * P.hkv + j) * kD + 32 * dsl + col;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int key = 32 * mb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
-      if (key < blen) {
-        outk[(size_t)key * P.hkv * kD] = (bf16_t)dkacc[v];
-        outv[(size_t)key * P.hkv * kD] = (bf16_t)dvacc[v];
+    for (int hf = 0; hf < NH; ++hf)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = 64 * hf + 32 * mb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
+        if (key < blen) {
+          outk[(size_t)key * P.hkv * kD] = (bf16_t)dkacc[hf][v];
+          outv[(size_t)key * P.hkv * kD] = (bf16_t)dvacc[hf][v];
+        }
       }
-    }
     return;
   }
   // unit partial: [u][0 = dK, 1 = dV][key][d] fp32, summed by k_bwd_dkv_reduce in unit order
-  float* outk = dkv_part + (size_t)u * 2 * kBlock * kD + 32 * dsl + col;
-  float* outv = outk + kBlock * kD;
+  float* outk = dkv_part + (size_t)u * 2 * (NH * kBlock) * kD + 32 * dsl + col;
+  float* outv = outk + (NH * kBlock) * kD;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int key = 32 * mb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
-    outk[key * kD] = dkacc[v];
-    outv[key * kD] = dvacc[v];
-  }
+  for (int hf = 0; hf < NH; ++hf)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = 64 * hf + 32 * mb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
+      outk[key * kD] = dkacc[hf][v];
+      outv[key * kD] = dvacc[hf][v];
+    }
 }
 
 __global__ void __launch_bounds__(256)
@@ -371,7 +416,7 @@ k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* 
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int u = u0; u < u1; ++u) {
       const float4 x =
-          *reinterpret_cast<const float4*>(dkv_part + ((size_t)u * 2 + which) * kBlock * kD + key * kD + d4);
+          *reinterpret_cast<const float4*>(dkv_part + ((size_t)u * 2 + which) * P.bk * kD + key * kD + d4);
       acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
     }
     uint2 w;
@@ -385,9 +430,9 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
                       const void* O, const float* LSE, const void* dO, const void* index_ws, void* dqpart,
                       float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
+  auto* main_kernel = P.bk == 128 ? k_bwd_main<2> : k_bwd_main<1>;
   {
-    hipError_t e =
-        hipFuncSetAttribute((const void*)k_bwd_main, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBwdBytes);
+    hipError_t e = hipFuncSetAttribute((const void*)main_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBwdBytes);
     if (e != hipSuccess) return e;
   }
   const int64_t rows = (int64_t)P.T * P.hq;
@@ -395,7 +440,7 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
   { ProfScope ps(KID_BWD_DELTA, st);
   hipLaunchKernelGGL(k_bwd_delta, dim3(row_blocks), dim3(256), 0, st, rows, (const bf16_t*)O, (const bf16_t*)dO, delta); }
   { ProfScope ps(KID_BWD_MAIN, st);
-  hipLaunchKernelGGL(k_bwd_main, dim3(L.bwd_units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
+  hipLaunchKernelGGL(main_kernel, dim3(L.bwd_units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, (const float*)delta, p.hdr, p.b_list,
                      p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.b_nu, (bf16_t*)dqpart, dkv_part, (bf16_t*)dK, (bf16_t*)dV); }
   { ProfScope ps(KID_BWD_DQ_REDUCE, st);

@@ -9,7 +9,7 @@
 
 namespace nsa {
 
-constexpr int kBlock = 64;         // B_K
+constexpr int kBlock = 64;         // keys per MFMA key tile (B_K = 64 is one tile, B_K = 128 two)
 constexpr int kD = 128;            // head dimension
 constexpr int kChunkTokens = 512;  // token chunk of the inversion histogram / scatter
 constexpr int kFwdUnit = 1024;      // list entries per forward work unit
@@ -18,11 +18,9 @@ constexpr int kMaxTopk = 32;
 
 // Host-computed description of the index workspace (byte offsets from its base, all 256-aligned).
 struct IndexLayout {
-  int32_t T, nseq, hkv, causal;
-  int32_t topk_in;      // columns of idx
-  int32_t sub;          // 64-token sub-blocks per selected block (B_K / 64: 1 or 2)
-  int32_t topk;         // virtual slots per row = topk_in * sub
-  int32_t b_cap;        // list stride: T / 64 + nseq  (>= real number of blocks)
+  int32_t T, nseq, hkv, topk, causal;
+  int32_t bk;           // B_K: tokens per KV block, 64 or 128
+  int32_t b_cap;        // list stride: T / bk + nseq  (>= real number of blocks)
   int32_t n_lists;      // hkv * b_cap
   int32_t n_chunks;     // ceil(T / kChunkTokens)
   int64_t n_counters;   // n_lists * n_chunks
@@ -78,7 +76,7 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
 
 // Problem description handed to the attention kernels.
 struct Problem {
-  int32_t T, nseq, hq, hkv, g, topk, causal, b_cap;
+  int32_t T, nseq, hq, hkv, g, topk, causal, b_cap, bk;
   float scale;
 };
 

@@ -209,6 +209,191 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   }
 }
 
+// ---- B_K = 128 -----------------------------------------------------------------------------------------------
+// Same work split, but a 128-key block does not fit the register file next to the tile state, so K_i and V_i sit
+// row-major in LDS: K fragments are plain 16-byte reads, V^T fragments are LDS transpose reads (no transposed
+// copy).  A tile computes S^T for all 128 keys (4 x 8 MFMA), one softmax over the 128 scores of a row, and
+// O^T = V_i^T P^T (8 x 4 MFMA); one partial row and one log-sum-exp per (token, head, selected 128-block).
+constexpr int kPitch128 = 152;  // bf16 per LDS row (128 + 24 pad): conflict-free for operand reads and transpose reads
+constexpr int kF128K = 0;
+constexpr int kF128V = kF128K + 128 * kPitch128 * 2;
+constexpr int kF128Tiles = kF128V + 128 * kPitch128 * 2;
+constexpr int kF128Ent = kF128Tiles + 4 * 32 * kPitch128 * 2;
+constexpr int kF128Bytes = kF128Ent + kFwdUnit * 8;  // 124928
+
+// ds_read_b64_tr_b16: every lane passes the address of 8 bytes (four 16-bit elements); within each group of 16
+// lanes, lane i receives element (i % 4) of the 8 bytes addressed by lanes 4e + i / 4, e = 0..3.
+__device__ __forceinline__ bf16x4 lds_read_tr_f(const bf16_t* p) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)p);
+  return __builtin_bit_cast(bf16x4, v);
+}
+
+__global__ void __launch_bounds__(256)
+k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+              const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list,
+              const int32_t* __restrict__ u_start, const int32_t* __restrict__ off,
+              const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
+              const int32_t* __restrict__ qlist, const int32_t* __restrict__ qslot, bf16_t* __restrict__ opart,
+              float* __restrict__ lse_part) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kF128K);
+  bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kF128V);
+  int2* ent = reinterpret_cast<int2*>(smem + kF128Ent);
+  const int u = blockIdx.x;
+  if (u >= hdr[HDR_FUNITS]) return;
+  const int L = u_list[u];
+  const int j = L / P.b_cap;
+  const int gb = L - j * P.b_cap;
+  const int e0 = u_start[u];
+  const int ne = min(kFwdUnit, off[L + 1] - e0);
+  const int tok0 = blk_tok0[gb], blen = blk_len[gb];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
+  const int crow = lane >> 4, cchunk = (lane & 15) * 8;
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  bf16_t* tile_lds = reinterpret_cast<bf16_t*>(smem + kF128Tiles) + wave * 32 * kPitch128;
+
+  {  // K_i, V_i -> LDS, row-major (rows past the end of a ragged block are zero)
+    const int key = tid >> 1, d0 = (tid & 1) * 64;
+    const size_t o = ((size_t)(tok0 + key) * P.hkv + j) * kD + d0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      *reinterpret_cast<bf16x8*>(&Ks[key * kPitch128 + d0 + 8 * i]) =
+          key < blen ? *reinterpret_cast<const bf16x8*>(K + o + 8 * i) : zero8;
+      *reinterpret_cast<bf16x8*>(&Vs[key * kPitch128 + d0 + 8 * i]) =
+          key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
+    }
+  }
+  for (int i = tid; i < ne; i += 256) ent[i] = make_int2(qlist[e0 + i], qslot[e0 + i]);
+  __syncthreads();
+
+  const int rows_total = ne * P.g;
+  const int n_tiles = (rows_total + 31) >> 5;
+  if (wave >= n_tiles) return;  // no block-wide barrier below this point
+  const float c2 = P.scale * 1.4426950408889634f;
+  const size_t hq = P.hq;
+  const int hbase = j * P.g;
+  // this lane's share of a transposing read of four key rows x 16 channels; lane half qh = grp / 2 holds keys
+  // k0 + 4 qh + {0..3} (first read) and the same + 8 (second read) of contraction step sp, k0 = 32 (sp/2) + 16 (sp&1)
+  const int grp = lane >> 4, sl = lane & 15;
+  const int tr_v = ((sl >> 2) + 4 * (grp >> 1)) * kPitch128 + 16 * (grp & 1) + 4 * (sl & 3);
+
+  auto issue_q = [&](int tile, uint4 (&qc)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = tile * 32 + 4 * i + crow;
+      if (r < rows_total) {
+        const int e = r / P.g;
+        qc[i] = *reinterpret_cast<const uint4*>(Q + ((size_t)ent[e].x * hq + hbase + (r - e * P.g)) * kD + cchunk);
+      } else {
+        qc[i] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+
+  auto do_tile = [&](int tile, uint4 (&qc)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      *reinterpret_cast<uint4*>(&tile_lds[(4 * i + crow) * kPitch128 + cchunk]) = qc[i];
+    wave_sync();
+    bf16x8 qf[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kPitch128 + 16 * s + 8 * qh]);
+    if (tile + 8 < n_tiles) issue_q(tile + 8, qc);
+
+    f32x16 sacc[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sacc[mb][v] = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Ks[(32 * mb + col) * kPitch128 + 16 * s + 8 * qh]);
+        sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[mb], 0, 0, 0);
+      }
+
+    const int r = tile * 32 + col;
+    const bool valid = r < rows_total;
+    const int t = valid ? ent[r / P.g].x : -1;
+    int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
+    if (!valid) lim = 0;
+    float m = -INFINITY;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
+        const float x = key < lim ? sacc[mb][v] * c2 : -INFINITY;
+        sacc[mb][v] = x;
+        m = fmaxf(m, x);
+      }
+    m = fmaxf(m, __shfl_xor(m, 32));
+    const float msafe = (m == -INFINITY) ? 0.f : m;
+    float l = 0.f;
+    bf16x8 pf[8];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __builtin_amdgcn_exp2f(sacc[mb][v] - msafe);
+        l += p;
+        pf[2 * mb + (v >> 3)][v & 7] = (bf16_t)p;
+      }
+    l += __shfl_xor(l, 32);
+
+    f32x16 oacc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+#pragma unroll
+    for (int sp = 0; sp < 8; ++sp) {
+      const int k0 = 32 * (sp >> 1) + 16 * (sp & 1);
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const bf16x4 a0 = lds_read_tr_f(&Vs[k0 * kPitch128 + tr_v + 32 * db]);
+        const bf16x4 a1 = lds_read_tr_f(&Vs[(k0 + 8) * kPitch128 + tr_v + 32 * db]);
+        const bf16x8 vf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], oacc[db], 0, 0, 0);
+      }
+    }
+
+    const float inv = valid ? 1.f / l : 0.f;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        uint2 w;
+        w.x = pack_bf16x2(oacc[db][4 * a + 0] * inv, oacc[db][4 * a + 1] * inv);
+        w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
+        *reinterpret_cast<uint2*>(&tile_lds[col * kPitch128 + 32 * db + 8 * a + 4 * qh]) = w;
+      }
+    wave_sync();
+    const size_t prow0 = (size_t)e0 * P.g + (size_t)tile * 32;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = 4 * i + crow;
+      if (tile * 32 + row < rows_total)
+        store_streaming(opart + (prow0 + row) * kD + cchunk,
+                        *reinterpret_cast<const uint4*>(&tile_lds[row * kPitch128 + cchunk]));
+    }
+    if (valid && qh == 0) lse_part[prow0 + col] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    wave_sync();
+  };
+
+  uint4 qa[8], qb[8];
+  issue_q(wave, qa);
+  if (wave + 4 < n_tiles) issue_q(wave + 4, qb);
+  for (int tile = wave; tile < n_tiles; tile += 8) {
+    do_tile(tile, qa);
+    if (tile + 4 < n_tiles) do_tile(tile + 4, qb);
+  }
+}
+
 // 16 lanes per (token, head) row, 8 output channels per lane.  Slots are taken 16 at a time: positions, partial
 // log-sum-exps and partial rows of a batch are all requested before any of them is used, so one row keeps up to
 // 16 independent 256-byte gathers in flight; batches are chained by the usual running-max rescale.
@@ -281,7 +466,14 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
 hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
                       const void* index_ws, void* opart, float* lse_part, void* O, float* LSE, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
-  { ProfScope ps(KID_FWD_MAIN, st);
+  if (P.bk == 128) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_fwd_main128, hipFuncAttributeMaxDynamicSharedMemorySize, kF128Bytes);
+    if (e != hipSuccess) return e;
+    ProfScope ps(KID_FWD_MAIN, st);
+    hipLaunchKernelGGL(k_fwd_main128, dim3(L.fwd_units_max), dim3(256), kF128Bytes, st, P, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len,
+                       p.qlist, p.qslot, (bf16_t*)opart, lse_part);
+  } else { ProfScope ps(KID_FWD_MAIN, st);
   hipLaunchKernelGGL(k_fwd_main, dim3(L.fwd_units_max), dim3(256), 0, st, P, (const bf16_t*)Q, (const bf16_t*)K,
                      (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.qslot,
                      (bf16_t*)opart, lse_part); }

@@ -16,8 +16,10 @@ constexpr int kScanItems = 16;
 constexpr int kScanTile = kScanThreads * kScanItems;  // 4096
 
 // ------------------------------------------------------------------------------------------------ prep
-// blk_base[s] = number of blocks of sequences < s; per global block its first token and its key count.
-__global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int b_cap, int32_t* __restrict__ blk_base,
+// blk_base[s] = number of blocks (of bk = B_K tokens) of sequences < s; per global block its first token and its
+// key count.
+__global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int bk, int b_cap,
+                       int32_t* __restrict__ blk_base,
                        int32_t* __restrict__ blk_tok0, int32_t* __restrict__ blk_len, int32_t* __restrict__ hdr) {
   __shared__ int s_btot;
   if (threadIdx.x == 0) {
@@ -25,7 +27,7 @@ __global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int b_ca
     for (int s = 0; s < nseq; ++s) {
       int c0 = cu ? cu[s] : 0, c1 = cu ? cu[s + 1] : T;
       blk_base[s] = acc;
-      acc += (c1 - c0 + kBlock - 1) / kBlock;
+      acc += (c1 - c0 + bk - 1) / bk;
     }
     blk_base[nseq] = acc;
     s_btot = acc;
@@ -43,8 +45,8 @@ __global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int b_ca
         if (blk_base[mid] <= gb) lo = mid; else hi = mid;
       }
       int c0 = cu ? cu[lo] : 0, c1 = cu ? cu[lo + 1] : T;
-      tok0 = c0 + (gb - blk_base[lo]) * kBlock;
-      len = min(kBlock, c1 - tok0);
+      tok0 = c0 + (gb - blk_base[lo]) * bk;
+      len = min(bk, c1 - tok0);
     }
     blk_tok0[gb] = tok0;
     blk_len[gb] = len;
@@ -57,28 +59,17 @@ __global__ void k_zero(int32_t* __restrict__ p, int64_t n) {
   for (; i < n; i += stride) p[i] = 0;
 }
 
-// A selected block of B_K = 64 * sub tokens is handled as `sub` consecutive 64-token sub-blocks; column m of a row
-// therefore owns the virtual slots m * sub .. m * sub + sub - 1 (sub is 1 or 2).  Bit v of the result is set when
-// virtual slot v is kept: its column's id is in range for the sequence and not a repeat of an earlier column,
-// and the sub-block exists (ragged sequence end) and is not in the token's future when causal.
-// b_s / cur are counted in 64-token sub-blocks.
-__device__ __forceinline__ uint32_t kept_slots(const int32_t* row, int k, int sub, int b_s, int cur, int causal) {
+// Bit m of the result is set when column m of the row is a kept selection: in range for the sequence, not in
+// the token's future when causal, and not a repeat of an earlier column.
+__device__ __forceinline__ uint32_t kept_columns(const int32_t* row, int k, int b_s, int cur, int causal) {
   uint32_t vm = 0;
   for (int m = 0; m < k; ++m) {
-    const int x = row[m];
-    bool ok = x >= 0 && (int64_t)x * sub < b_s;
+    int x = row[m];
+    bool ok = x >= 0 && x < b_s && (!causal || x <= cur);
     for (int mp = 0; mp < m && ok; ++mp) ok = row[mp] != x;
-    if (!ok) continue;
-    for (int hf = 0; hf < sub; ++hf) {
-      const int id = x * sub + hf;
-      if (id < b_s && (!causal || id <= cur)) vm |= 1u << (m * sub + hf);
-    }
+    if (ok) vm |= 1u << m;
   }
   return vm;
-}
-// 64-token sub-block id (local to the sequence) of virtual slot v of a row
-__device__ __forceinline__ int slot_block(const int32_t* row, int sub, int v) {
-  return sub == 1 ? row[v] : row[v >> 1] * 2 + (v & 1);
 }
 
 // Window of global blocks a token chunk can touch: all blocks of the sequences it overlaps.
@@ -96,7 +87,7 @@ __device__ __forceinline__ void chunk_window(const int32_t* cu, const int32_t* b
 // chunk that keep block gb for kv head j.  Dynamic LDS: b_cap ints + 256*(k+1) ints.
 __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                               const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
-                                              int sub, int causal, int b_cap, int n_chunks,
+                                              int bk, int causal, int b_cap, int n_chunks,
                                               int32_t* __restrict__ counters) {
   extern __shared__ int32_t lds[];
   int32_t* hist = lds;
@@ -114,12 +105,12 @@ __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, c
     seq_bounds(cu, nseq, T, t, s, c0, c1);
     const int32_t* src = idx + ((size_t)t * hkv + j) * k;
     for (int m = 0; m < k; ++m) row[m] = src[m];
-    const int b_s = (c1 - c0 + kBlock - 1) / kBlock;
-    const int cur = (t - c0) / kBlock;
-    uint32_t vm = kept_slots(row, k, sub, b_s, cur, causal);
+    const int b_s = (c1 - c0 + bk - 1) / bk;
+    const int cur = (t - c0) / bk;
+    uint32_t vm = kept_columns(row, k, b_s, cur, causal);
     const int base = blk_base[s] - gb_lo;
-    for (int v = 0; v < k * sub; ++v)
-      if ((vm >> v) & 1u) atomicAdd(&hist[base + slot_block(row, sub, v)], 1);
+    for (int m = 0; m < k; ++m)
+      if ((vm >> m) & 1u) atomicAdd(&hist[base + row[m]], 1);
   }
   __syncthreads();
   for (int i = threadIdx.x; i < win; i += blockDim.x)
@@ -197,7 +188,7 @@ static void scan_exclusive(int32_t* a, int64_t n, int32_t* tmp, hipStream_t st) 
 // masks + b_cap int cursors + 64*(k+1) ints.
 __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                                 const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
-                                                int sub, int causal, int b_cap, int n_chunks,
+                                                int bk, int causal, int b_cap, int n_chunks,
                                                 const int32_t* __restrict__ chunk_off, int32_t* __restrict__ qlist,
                                                 int32_t* __restrict__ qslot, uint32_t* __restrict__ vmask,
                                                 int32_t* __restrict__ slotpos) {
@@ -226,29 +217,28 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
       seq_bounds(cu, nseq, T, t, s, c0, c1);
       const int32_t* src = idx + ((size_t)t * hkv + j) * k;
       for (int m = 0; m < k; ++m) row[m] = src[m];
-      vm = kept_slots(row, k, sub, (c1 - c0 + kBlock - 1) / kBlock, (t - c0) / kBlock, causal);
+      vm = kept_columns(row, k, (c1 - c0 + bk - 1) / bk, (t - c0) / bk, causal);
       base = blk_base[s] - gb_lo;
       vmask[(size_t)t * hkv + j] = vm;
     }
     // A: mark membership of this round's tokens in every block they keep
-    const int kv = k * sub;  // virtual slots per row
-    for (int m = 0; m < kv; ++m)
-      if ((vm >> m) & 1u) atomicOr(&mask[base + slot_block(row, sub, m)], 1ull << lane);
+    for (int m = 0; m < k; ++m)
+      if ((vm >> m) & 1u) atomicOr(&mask[base + row[m]], 1ull << lane);
     __syncthreads();
     // B: rank among the lower tokens of the round gives the position; lists come out ascending
-    for (int m = 0; m < kv; ++m)
+    for (int m = 0; m < k; ++m)
       if ((vm >> m) & 1u) {
-        const int w = base + slot_block(row, sub, m);
+        const int w = base + row[m];
         const int pos = cursor[w] + __popcll(mask[w] & below);
         qlist[pos] = t;
         qslot[pos] = m;
-        slotpos[((size_t)t * hkv + j) * kv + m] = pos;
+        slotpos[((size_t)t * hkv + j) * k + m] = pos;
       }
     __syncthreads();
     // C: the lowest member of each touched block advances its cursor and clears the mask
-    for (int m = 0; m < kv; ++m)
+    for (int m = 0; m < k; ++m)
       if ((vm >> m) & 1u) {
-        const int w = base + slot_block(row, sub, m);
+        const int w = base + row[m];
         const unsigned long long mk = mask[w];
         if (mk != 0ull && (mk & below) == 0ull) {
           cursor[w] += __popcll(mk);
@@ -296,8 +286,8 @@ __global__ void k_units(const int32_t* __restrict__ nu_scan, const int32_t* __re
 hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
                               hipStream_t st) {
   IndexPtrs p = index_ptrs(L, index_ws);
-  const size_t lds_hist = (size_t)L.b_cap * 4 + 256 * (size_t)(L.topk_in + 1) * 4;
-  const size_t lds_scat = (size_t)L.b_cap * 12 + 64 * (size_t)(L.topk_in + 1) * 4;
+  const size_t lds_hist = (size_t)L.b_cap * 4 + 256 * (size_t)(L.topk + 1) * 4;
+  const size_t lds_scat = (size_t)L.b_cap * 12 + 64 * (size_t)(L.topk + 1) * 4;
   if (lds_hist > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)k_hist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_hist);
     if (e != hipSuccess) return e;
@@ -308,7 +298,7 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
     if (e != hipSuccess) return e;
   }
   { ProfScope ps(KID_INDEX_PREP, st);
-  hipLaunchKernelGGL(k_prep, dim3(1), dim3(256), 0, st, cu, L.nseq, L.T, L.b_cap, p.blk_base, p.blk_tok0, p.blk_len,
+  hipLaunchKernelGGL(k_prep, dim3(1), dim3(256), 0, st, cu, L.nseq, L.T, L.bk, L.b_cap, p.blk_base, p.blk_tok0, p.blk_len,
                      p.hdr); }
   const int64_t nc = L.n_counters + 1;
   { ProfScope ps(KID_INDEX_ZERO, st);
@@ -316,12 +306,12 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
                      p.chunk_off, nc); }
   { ProfScope ps(KID_INDEX_HIST, st);
   hipLaunchKernelGGL(k_hist, dim3(L.n_chunks, L.hkv), dim3(256), lds_hist, st, idx, cu, p.blk_base, L.nseq, L.T, L.hkv,
-                     L.topk_in, L.sub, L.causal, L.b_cap, L.n_chunks, p.chunk_off); }
+                     L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off); }
   { ProfScope ps(KID_INDEX_SCAN, st);
   scan_exclusive(p.chunk_off, nc, p.scan_tmp, st); }
   { ProfScope ps(KID_INDEX_SCATTER, st);
   hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
-                     L.hkv, L.topk_in, L.sub, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask,
+                     L.hkv, L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask,
                      p.slotpos); }
   const int nl1 = L.n_lists + 1;
   { ProfScope ps(KID_INDEX_FINALIZE, st);

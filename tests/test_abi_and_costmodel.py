@@ -28,14 +28,14 @@ def test_shape_validation_happens_on_the_host():
     ok = nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 1, 0.0, 0)
     f, b, i = nsa.workspace_bytes(ok)
     assert f >= 4096 * 8 * 16 * 128 * 2 and b > f and i > 0
-    assert nsa.workspace_bytes(nsa.Shape(4096, 1, 8, 2, 128, 128, 8, 1, 0.0, 0))[0] == f   # (128, 8) = 16 half-slots
+    assert nsa.workspace_bytes(nsa.Shape(4096, 1, 8, 2, 128, 128, 8, 1, 0.0, 0))[0] * 2 == f   # half the slots
     bad = [
         (nsa.Shape(4096, 1, 8, 3, 128, 64, 16, 1, 0.0, 0), -1),     # hq % hkv
         (nsa.Shape(4096, 1, 18, 2, 128, 64, 16, 1, 0.0, 0), -1),    # g = 9
         (nsa.Shape(4096, 0, 8, 2, 128, 64, 16, 1, 0.0, 0), -1),     # nseq
         (nsa.Shape(4096, 1, 8, 2, 64, 64, 16, 1, 0.0, 0), -2),      # d
         (nsa.Shape(4096, 1, 8, 2, 128, 256, 16, 1, 0.0, 0), -2),    # block
-        (nsa.Shape(4096, 1, 8, 2, 128, 128, 17, 1, 0.0, 0), -2),    # topk * block / 64 > 32
+        (nsa.Shape(4096, 1, 8, 2, 128, 128, 33, 1, 0.0, 0), -2),    # topk
         (nsa.Shape(4096, 1, 8, 2, 128, 64, 33, 1, 0.0, 0), -2),     # topk
         (nsa.Shape(2 ** 30, 1, 8, 2, 128, 64, 16, 1, 0.0, 0), -2),  # too large
     ]

@@ -17,8 +17,7 @@ def _compare(w, idx_override=None):
     attn.build_index(torch.from_numpy(idx).cuda(), torch.from_numpy(w.cu_seqlens).cuda())
     torch.cuda.synchronize()
     cnt, off, qlist, qslot, vmask, bcap = attn.index_arrays()
-    # a 128-token block is its two 64-token halves: the library's lists are those of the re-indexed table
-    rc, ro, rl, rs, rv = orc.invert_index(wl.expand_blocks(idx, w.block // 64), w.cu_seqlens, causal=w.causal)
+    rc, ro, rl, rs, rv = orc.invert_index(idx, w.cu_seqlens, causal=w.causal, block=w.block)
     b_tot = rc.shape[1]
     assert bcap >= b_tot
     assert np.array_equal(cnt[:, :b_tot], rc) and not cnt[:, b_tot:].any()

@@ -73,16 +73,6 @@ class Workload:
         return self.hq // self.hkv
 
 
-def expand_blocks(idx: np.ndarray, sub: int) -> np.ndarray:
-    """Rewrite a table of B_K = 64*sub block ids as the equivalent table of 64-token block ids (each id x becomes
-    x*sub .. x*sub + sub - 1, negative ids stay negative); pure re-indexing, used to state what a 128-token
-    selection means in 64-token blocks."""
-    T, hkv, k = idx.shape
-    out = np.repeat(idx.astype(np.int64), sub, axis=2) * sub + np.tile(np.arange(sub), k)[None, None, :]
-    out[np.repeat(idx, sub, axis=2) < 0] = -1
-    return out.astype(np.int32)
-
-
 def _floyd_subsets(rng: np.random.Generator, n: np.ndarray, m: int) -> np.ndarray:
     """Uniform random subsets without replacement, one per row (Floyd's algorithm, vectorised over rows).
 
