@@ -214,12 +214,14 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 // row-major in LDS: K fragments are plain 16-byte reads, V^T fragments are LDS transpose reads (no transposed
 // copy).  A tile computes S^T for all 128 keys (4 x 8 MFMA), one softmax over the 128 scores of a row, and
 // O^T = V_i^T P^T (8 x 4 MFMA); one partial row and one log-sum-exp per (token, head, selected 128-block).
-constexpr int kPitch128 = 152;  // bf16 per LDS row (128 + 24 pad): conflict-free for operand reads and transpose reads
+constexpr int kPitch128 = 152;  // bf16 per LDS row of K / V (128 + 24 pad): conflict-free operand and transpose reads
+constexpr int kWaves128 = 8;    // two wavefronts per SIMD: one wave's LDS / memory waits are covered by the other
 constexpr int kF128K = 0;
 constexpr int kF128V = kF128K + 128 * kPitch128 * 2;
 constexpr int kF128Tiles = kF128V + 128 * kPitch128 * 2;
-constexpr int kF128Ent = kF128Tiles + 4 * 32 * kPitch128 * 2;
-constexpr int kF128Bytes = kF128Ent + kFwdUnit * 8;  // 124928
+constexpr int kF128Ent = kF128Tiles + kWaves128 * 32 * kTileStride * 2;
+constexpr int kF128Bytes = kF128Ent + kFwdUnit * 8;  // 155648
+static_assert(kF128Bytes <= 160 * 1024, "forward 128-key tile set must fit the CU's LDS");
 
 // ds_read_b64_tr_b16: every lane passes the address of 8 bytes (four 16-bit elements); within each group of 16
 // lanes, lane i receives element (i % 4) of the 8 bytes addressed by lanes 4e + i / 4, e = 0..3.
@@ -230,7 +232,7 @@ __device__ __forceinline__ bf16x4 lds_read_tr_f(const bf16_t* p) {
   return __builtin_bit_cast(bf16x4, v);
 }
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * kWaves128)
 k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
               const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list,
               const int32_t* __restrict__ u_start, const int32_t* __restrict__ off,
@@ -249,23 +251,24 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   const int e0 = u_start[u];
   const int ne = min(kFwdUnit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
-  const int crow = lane >> 4, cchunk = (lane & 15) * 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int col = lane & 31, qh = lane >> 5;                 // not const: see the top of the tile loop
+  int crow = lane >> 4, cchunk = (lane & 15) * 8;
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-  bf16_t* tile_lds = reinterpret_cast<bf16_t*>(smem + kF128Tiles) + wave * 32 * kPitch128;
+  bf16_t* tile_lds = reinterpret_cast<bf16_t*>(smem + kF128Tiles) + wave * 32 * kTileStride;
 
   {  // K_i, V_i -> LDS, row-major (rows past the end of a ragged block are zero)
-    const int key = tid >> 1, d0 = (tid & 1) * 64;
+    const int key = tid >> 2, d0 = (tid & 3) * 32;
     const size_t o = ((size_t)(tok0 + key) * P.hkv + j) * kD + d0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 4; ++i) {
       *reinterpret_cast<bf16x8*>(&Ks[key * kPitch128 + d0 + 8 * i]) =
           key < blen ? *reinterpret_cast<const bf16x8*>(K + o + 8 * i) : zero8;
       *reinterpret_cast<bf16x8*>(&Vs[key * kPitch128 + d0 + 8 * i]) =
           key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
     }
   }
-  for (int i = tid; i < ne; i += 256) ent[i] = make_int2(qlist[e0 + i], qslot[e0 + i]);
+  for (int i = tid; i < ne; i += 64 * kWaves128) ent[i] = make_int2(qlist[e0 + i], qslot[e0 + i]);
   __syncthreads();
 
   const int rows_total = ne * P.g;
@@ -277,9 +280,10 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   // this lane's share of a transposing read of four key rows x 16 channels; lane half qh = grp / 2 holds keys
   // k0 + 4 qh + {0..3} (first read) and the same + 8 (second read) of contraction step sp, k0 = 32 (sp/2) + 16 (sp&1)
   const int grp = lane >> 4, sl = lane & 15;
-  const int tr_v = ((sl >> 2) + 4 * (grp >> 1)) * kPitch128 + 16 * (grp & 1) + 4 * (sl & 3);
+  int tr_v = ((sl >> 2) + 4 * (grp >> 1)) * kPitch128 + 16 * (grp & 1) + 4 * (sl & 3);
 
-  auto issue_q = [&](int tile, uint4 (&qc)[8]) {
+  uint4 qc[8];
+  auto issue_q = [&](int tile) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = tile * 32 + 4 * i + crow;
@@ -291,17 +295,20 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
       }
     }
   };
+  issue_q(wave);
 
-  auto do_tile = [&](int tile, uint4 (&qc)[8]) {
+  for (int tile = wave; tile < n_tiles; tile += kWaves128) {
+    // register budget (256 per wave): keep the lane-derived LDS addresses from being precomputed across the loop
+    asm volatile("" : "+v"(col), "+v"(qh), "+v"(crow), "+v"(cchunk), "+v"(tr_v));
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<uint4*>(&tile_lds[(4 * i + crow) * kPitch128 + cchunk]) = qc[i];
+      *reinterpret_cast<uint4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
     wave_sync();
     bf16x8 qf[8];
 #pragma unroll
     for (int s = 0; s < 8; ++s)
-      qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kPitch128 + 16 * s + 8 * qh]);
-    if (tile + 8 < n_tiles) issue_q(tile + 8, qc);
+      qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kTileStride + 16 * s + 8 * qh]);
+    if (tile + kWaves128 < n_tiles) issue_q(tile + kWaves128);  // next rows fly during this tile's compute
 
     f32x16 sacc[4];
 #pragma unroll
@@ -370,7 +377,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
         uint2 w;
         w.x = pack_bf16x2(oacc[db][4 * a + 0] * inv, oacc[db][4 * a + 1] * inv);
         w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
-        *reinterpret_cast<uint2*>(&tile_lds[col * kPitch128 + 32 * db + 8 * a + 4 * qh]) = w;
+        *reinterpret_cast<uint2*>(&tile_lds[col * kTileStride + 32 * db + 8 * a + 4 * qh]) = w;
       }
     wave_sync();
     const size_t prow0 = (size_t)e0 * P.g + (size_t)tile * 32;
@@ -379,18 +386,10 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
       const int row = 4 * i + crow;
       if (tile * 32 + row < rows_total)
         store_streaming(opart + (prow0 + row) * kD + cchunk,
-                        *reinterpret_cast<const uint4*>(&tile_lds[row * kPitch128 + cchunk]));
+                        *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]));
     }
     if (valid && qh == 0) lse_part[prow0 + col] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
     wave_sync();
-  };
-
-  uint4 qa[8], qb[8];
-  issue_q(wave, qa);
-  if (wave + 4 < n_tiles) issue_q(wave + 4, qb);
-  for (int tile = wave; tile < n_tiles; tile += 8) {
-    do_tile(tile, qa);
-    if (tile + 4 < n_tiles) do_tile(tile + 4, qb);
   }
 }
 
@@ -470,7 +469,7 @@ hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, con
     hipError_t e = hipFuncSetAttribute((const void*)k_fwd_main128, hipFuncAttributeMaxDynamicSharedMemorySize, kF128Bytes);
     if (e != hipSuccess) return e;
     ProfScope ps(KID_FWD_MAIN, st);
-    hipLaunchKernelGGL(k_fwd_main128, dim3(L.fwd_units_max), dim3(256), kF128Bytes, st, P, (const bf16_t*)Q,
+    hipLaunchKernelGGL(k_fwd_main128, dim3(L.fwd_units_max), dim3(64 * kWaves128), kF128Bytes, st, P, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len,
                        p.qlist, p.qslot, (bf16_t*)opart, lse_part);
   } else { ProfScope ps(KID_FWD_MAIN, st);
