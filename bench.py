@@ -64,7 +64,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over KV heads with no "
-                 "communication; see DESIGN.md); run with --gpus 1")
+                 "communication, so N GPUs would each run this same kernel on hkv / N heads); run with --gpus 1")
 
     import torch
 
