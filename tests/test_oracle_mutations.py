@@ -1,0 +1,104 @@
+"""The pins must be able to fail: each plausible mistake planted in the oracle (on the CPU, by patching it) has to
+trip at least one of the pin tests."""
+import math
+
+import numpy as np
+import pytest
+
+import test_oracle_pins as pins
+from oracle import nsa_sel_oracle as orc
+
+
+def _pins():
+    case = pins.CASES[1]
+    yield lambda: pins.test_forward_equals_dense_masked_attention(case)
+    yield lambda: pins.test_backward_equals_autograd_of_dense_masked_attention(case)
+    yield lambda: pins.test_forward_equals_dense_masked_attention(pins.CASES[3])
+    yield lambda: pins.test_all_blocks_selected_is_full_attention(True)
+    yield pins.test_backward_matches_central_finite_differences
+    yield pins.test_closed_forms
+    yield lambda: pins.test_inversion_against_mask_and_invariants(pins.CASES[4])
+
+
+def _some_pin_fails():
+    for pin in _pins():
+        try:
+            pin()
+        except (AssertionError, ValueError, IndexError):
+            return True
+    return False
+
+
+def _row_forward_no_scale(q, Kv, Vv, scale):
+    return orc_row_forward(q, Kv, Vv, 1.0)
+
+
+def _visible_keys_no_inblock_mask(cu, t, idx_row, block, causal):
+    s = orc._seq_of(cu, t)
+    c0, c1 = int(cu[s]), int(cu[s + 1])
+    keys = []
+    for x in orc.selected_set(idx_row, (t - c0) // block, -(-(c1 - c0) // block), causal):
+        keys.extend(range(c0 + x * block, min(c0 + (x + 1) * block, c1)))        # forgets u <= t
+    return np.asarray(keys, dtype=np.int64)
+
+
+def _selected_set_drops_current(idx_row, cur, b_s, causal):
+    return sorted({int(x) for x in idx_row if 0 <= int(x) < b_s and (not causal or int(x) < cur)})   # < for <=
+
+
+def _selected_set_multiset(idx_row, cur, b_s, causal):
+    return sorted(int(x) for x in idx_row if 0 <= int(x) < b_s and (not causal or int(x) <= cur))   # repeats kept
+
+
+orc_row_forward = orc._row_forward
+orc_backward = orc.backward
+
+
+def _backward_mutated(kind):
+    def backward(Q, K, V, dO, idx, cu, *, block=64, causal=True, scale=None, tokens=None):
+        dQ, dK, dV = orc_backward(Q, K, V, dO, idx, cu, block=block, causal=causal, scale=scale, tokens=tokens)
+        sc = 1.0 / math.sqrt(Q.shape[2]) if scale is None else scale
+        if kind == "dk_unscaled":
+            dK = dK / sc
+        elif kind == "dq_sign":
+            dQ = -dQ
+        elif kind == "dv_one_head":                      # sums one head of the group instead of all g
+            g = Q.shape[1] // K.shape[1]
+            dV = dV / g
+        return dQ, dK, dV
+    return backward
+
+
+MUTATIONS = [
+    ("_row_forward", _row_forward_no_scale),
+    ("visible_keys", _visible_keys_no_inblock_mask),
+    ("selected_set", _selected_set_drops_current),
+    ("selected_set", _selected_set_multiset),
+    ("backward", _backward_mutated("dk_unscaled")),
+    ("backward", _backward_mutated("dq_sign")),
+    ("backward", _backward_mutated("dv_one_head")),
+]
+
+
+def test_unmutated_oracle_passes_the_selected_pins():
+    assert not _some_pin_fails()
+
+
+@pytest.mark.parametrize("name,replacement", MUTATIONS, ids=[f"{n}-{i}" for i, (n, _) in enumerate(MUTATIONS)])
+def test_planted_mistake_is_caught(monkeypatch, name, replacement):
+    monkeypatch.setattr(orc, name, replacement)
+    assert _some_pin_fails(), f"no pin noticed a broken {name}"
+
+
+def test_inversion_mistake_is_caught(monkeypatch):
+    real = orc.invert_index
+
+    def descending(idx, cu, **kw):                      # lists in the wrong order
+        cnt, off, qlist, qslot, vmask = real(idx, cu, **kw)
+        for a, b in zip(off[:-1], off[1:]):
+            qlist[a:b] = qlist[a:b][::-1].copy()
+            qslot[a:b] = qslot[a:b][::-1].copy()
+        return cnt, off, qlist, qslot, vmask
+    monkeypatch.setattr(orc, "invert_index", descending)
+    with pytest.raises(AssertionError):
+        pins.test_inversion_against_mask_and_invariants(pins.CASES[0])
