@@ -100,6 +100,26 @@ def main():
         nsa.calibration_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
+    # what this chip delivers to plain kernels of this build: a register-resident MFMA loop and a streaming copy
+    def _timed(fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        torch.cuda.synchronize()
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    probe_flops = nsa.mfma_probe(20000, sink)
+    mfma_measured = probe_flops / _timed(lambda: nsa.mfma_probe(20000, sink)) / 1e12
+    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+    cp_dst = torch.empty_like(cp_src)
+    copy_measured = 2 * (1 << 30) / _timed(lambda: nsa.calibration_copy(cp_dst, cp_src)) / 1e9
+    del cp_src, cp_dst
+    print(f"[bench] measured on this chip: MFMA loop {mfma_measured:.0f} TFLOP/s, streaming copy {copy_measured:.0f} GB/s",
+          file=sys.stderr, flush=True)
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -130,6 +150,10 @@ def main():
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                 "ms_per_launch": per_kernel[dom]}
+        tr = MEASURED_TRAFFIC_BYTES.get((args.workload, dom))
+        if tr is not None:   # the same kernel against the HBM roofline, from its measured traffic
+            roof["hbm_achieved_GBps"] = tr / (per_kernel[dom] * 1e-3) / 1e9
+            roof["hbm_frac"] = roof["hbm_achieved_GBps"] / PEAK_HBM_GBS
     out = {
         "metric": "selected-attn fwd+bwd effective TFLOP/s & ms at N=64k, g=4 (frac of MFMA peak)",
         "value": (f + b) / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -141,6 +165,8 @@ def main():
         "frac_of_bf16_mfma_peak": (f + b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "ms": {"index": idx_ms, "fwd": fwd_ms, "bwd": bwd_ms, "per_kernel": per_kernel},
         "roofline": roof,
+        "measured_peaks": {"mfma_loop_TFLOPs": mfma_measured, "stream_copy_GBps": copy_measured,
+                           "frac_of_measured_mfma": (f + b) / (ms * 1e-3) / 1e12 / mfma_measured},
     }
     if args.cpu_tokens > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_tokens)

@@ -102,6 +102,12 @@ int nsa_sel_profile_collect(int max_kernels, const char** names, float* total_ms
  * by what the same counters report for this kernel of known traffic. */
 int nsa_sel_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Measurement aid: a register-resident loop of independent bf16 MFMA chains on every CU (no memory traffic).
+ * Launches it with `iters` rounds per wavefront on `stream`; *flops (HOST, may be NULL) receives the number of
+ * floating-point operations the launch performs, so that FLOPs / elapsed time is the matrix-core rate reachable
+ * on the chip.  `sink` is a DEVICE float the kernel may write (never read back). */
+int nsa_sel_mfma_probe(int iters, float* sink, double* flops, void* stream);
+
 /* Static text for a return code. */
 const char* nsa_sel_strerror(int code);
 

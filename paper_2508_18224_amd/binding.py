@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
 _lib = None
 
 SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd",
-           "nsa_sel_profile_enable", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_strerror"]
+           "nsa_sel_profile_enable", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_mfma_probe", "nsa_sel_strerror"]
 
 
 class NsaSelError(RuntimeError):
@@ -42,6 +42,7 @@ def lib():
         L.nsa_sel_profile_collect.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                               C.POINTER(C.c_int)]
         L.nsa_sel_calibration_copy.argtypes = [vp, vp, sz, vp]
+        L.nsa_sel_mfma_probe.argtypes = [C.c_int, vp, C.POINTER(C.c_double), vp]
         L.nsa_sel_strerror.argtypes = [C.c_int]
         L.nsa_sel_strerror.restype = C.c_char_p
         for name in SYMBOLS[:-1]:
@@ -119,6 +120,13 @@ def profile_collect():
 def calibration_copy(dst: torch.Tensor, src: torch.Tensor):
     nbytes = src.numel() * src.element_size()
     _check(lib().nsa_sel_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream()), "nsa_sel_calibration_copy")
+
+
+def mfma_probe(iters: int, sink: torch.Tensor) -> float:
+    """Enqueue the MFMA probe kernel; returns the FLOPs it performs."""
+    fl = C.c_double()
+    _check(lib().nsa_sel_mfma_probe(int(iters), _ptr(sink), C.byref(fl), _stream()), "nsa_sel_mfma_probe")
+    return fl.value
 
 
 class SelAttention:

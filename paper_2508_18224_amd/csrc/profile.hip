@@ -38,12 +38,44 @@ __global__ void __launch_bounds__(256) k_calib_copy(const uint4* __restrict__ sr
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
+// Register-resident MFMA loop: every wavefront runs `iters` rounds of 8 independent v_mfma_f32_32x32x16_bf16
+// chains (no memory traffic), so elapsed time gives the matrix-core rate this build can reach on the chip.
+__global__ void __launch_bounds__(256) k_mfma_probe(int iters, float* __restrict__ sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (bf16_t)(0.001f * (float)(threadIdx.x + i));
+    b[i] = (bf16_t)(0.002f * (float)(threadIdx.x ^ i));
+  }
+  f32x16 acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) t += acc[c][0];
+  if (t == 12345.678f) sink[0] = t;  // keeps the loop alive
+}
+
 extern "C" {
+
+int nsa_sel_mfma_probe(int iters, float* sink, double* flops, void* stream) {
+  if (iters <= 0 || !sink) return NSA_SEL_EINVAL;
+  const int blocks = 256 * 2;  // two 4-wave workgroups per CU
+  hipLaunchKernelGGL(k_mfma_probe, dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, sink);
+  if (flops) *flops = (double)blocks * 4.0 * (double)iters * 8.0 * 2.0 * 32.0 * 32.0 * 16.0;
+  return hipGetLastError() == hipSuccess ? NSA_SEL_OK : NSA_SEL_EHIP;
+}
 
 int nsa_sel_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || (bytes & 15) != 0) return NSA_SEL_EINVAL;
   if (bytes == 0) return NSA_SEL_OK;
-  hipLaunchKernelGGL(k_calib_copy, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
+  hipLaunchKernelGGL(k_calib_copy, dim3(256 * 32), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
                      bytes / 16);
   return hipGetLastError() == hipSuccess ? NSA_SEL_OK : NSA_SEL_EHIP;
 }
