@@ -91,7 +91,7 @@ static size_t fwd_ws_bytes(const nsa_sel_shape* s) {
 
 static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L) {
   const size_t rows = partial_rows(s);
-  return align256(rows * kD * 2) + align256((size_t)s->total_tokens * s->hq * 4) +
+  return align256(rows * kD * 2) + align256((size_t)s->total_tokens * s->hq * 8) +
          align256((size_t)L.bwd_units_max * 2 * L.bk * kD * 4);
 }
 }  // namespace nsa
@@ -174,7 +174,7 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   char* w = (char*)ws;
   void* dqpart = w;
   float* delta = (float*)(w + align256(rows * kD * 2));
-  float* dkv_part = (float*)((char*)delta + align256((size_t)shape->total_tokens * shape->hq * 4));
+  float* dkv_part = (float*)((char*)delta + align256((size_t)shape->total_tokens * shape->hq * 8));
   return launch_bwd(P, L, Q, K, V, O, LSE, dO, index_ws, dqpart, delta, dkv_part, dQ, dK, dV, (hipStream_t)stream) ==
                  hipSuccess
              ? NSA_SEL_OK

@@ -3,7 +3,8 @@
 // intermediate query gradients to a buffer that a reduction kernel sums; dK/dV accumulation is not described.
 // This file is that pass, with dK/dV accumulated without atomics:
 //
-//   k_bwd_delta       delta[t,h] = <dO[t,h], O[t,h]>
+//   k_bwd_delta       delta[t,h] = <dO[t,h], O[t,h]>, stored next to LSE[t,h] log2(e) as one 8-byte pair so that the
+//                     main kernel fetches both row statistics with one gather
 //   k_bwd_main        one work unit = (kv head j, KV block i, up to kBwdUnit list entries).  The four wavefronts
 //                     of a workgroup share tiles of 128 gathered rows.  Wave w owns rows 32w..32w+31 for
 //                     S^T = K_i Q^T, dP^T = V_i dO^T, P = exp(S - LSE), dS = P (dP - delta) scale and
@@ -54,7 +55,8 @@ __device__ __forceinline__ void wave_sync_bwd() {  // orders a wavefront's own L
 }
 
 __global__ void __launch_bounds__(256)
-k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, float* __restrict__ delta) {
+k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, const float* __restrict__ LSE,
+            float2* __restrict__ stats) {
   const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   const int sub = threadIdx.x & 15;
   float acc = 0.f;
@@ -69,7 +71,7 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
   acc += __shfl_xor(acc, 4);
   acc += __shfl_xor(acc, 2);
   acc += __shfl_xor(acc, 1);
-  if (row < rows && sub == 0) delta[row] = acc;
+  if (row < rows && sub == 0) stats[row] = make_float2(LSE[row] * 1.4426950408889634f, acc);
 }
 
 // 512 threads = 8 wavefronts = two per SIMD, so one wave's LDS and memory waits are covered by the other's issue.
@@ -85,7 +87,7 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
 template <int NH>
 __global__ void __launch_bounds__(512)
 k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-           const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+           const bf16_t* __restrict__ dO, const float2* __restrict__ stats,
            const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
            const int32_t* __restrict__ qlist, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
@@ -187,8 +189,9 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     if (rc < rows_total) {
       const int ec = rc / P.g;
       const size_t grow = (size_t)ent[ec] * hq + hbase + (rc - ec * P.g);
-      lse2_n = LSE[grow] * 1.4426950408889634f;
-      dl_n = delta[grow];
+      const float2 st = stats[grow];  // (LSE in the log2 domain, delta)
+      lse2_n = st.x;
+      dl_n = st.y;
     } else {
       lse2_n = 0.f;
       dl_n = 0.f;
@@ -438,10 +441,11 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
   const int64_t rows = (int64_t)P.T * P.hq;
   const unsigned row_blocks = (unsigned)((rows + 15) / 16);
   { ProfScope ps(KID_BWD_DELTA, st);
-  hipLaunchKernelGGL(k_bwd_delta, dim3(row_blocks), dim3(256), 0, st, rows, (const bf16_t*)O, (const bf16_t*)dO, delta); }
+  hipLaunchKernelGGL(k_bwd_delta, dim3(row_blocks), dim3(256), 0, st, rows, (const bf16_t*)O, (const bf16_t*)dO, LSE,
+                     (float2*)delta); }
   { ProfScope ps(KID_BWD_MAIN, st);
   hipLaunchKernelGGL(main_kernel, dim3(L.bwd_units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
-                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, LSE, (const float*)delta, p.hdr, p.b_list,
+                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, (const float2*)delta, p.hdr, p.b_list,
                      p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.b_nu, (bf16_t*)dqpart, dkv_part, (bf16_t*)dK, (bf16_t*)dV); }
   { ProfScope ps(KID_BWD_DQ_REDUCE, st);
   hipLaunchKernelGGL(k_bwd_dq_reduce, dim3(row_blocks), dim3(256), 0, st, P, (const bf16_t*)dqpart, p.vmask,
