@@ -1,0 +1,56 @@
+"""Seeded random shapes (sequence mixes, head counts, top-k, block size, causal or not, adversarial rows) against the
+oracle, forward and backward; plus unit-boundary cases where a list has exactly as many entries as a work unit."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import nsa_sel_oracle as orc
+from gpu_util import Case, TOL_GRAD, TOL_O, assert_close, assert_lse_close, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(w, scale=0.0):
+    c = Case(w, scale=scale)
+    o, lse = c.forward()
+    dq, dk, dv = c.backward(o, lse)
+    Q, K, V, dO = c.host_f64()
+    sc = None if scale == 0.0 else scale
+    O_ref, LSE_ref = orc.forward(Q, K, V, w.idx, w.cu_seqlens, causal=w.causal, block=w.block, scale=sc)
+    rq, rk, rv = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, causal=w.causal, block=w.block, scale=sc)
+    assert_close("O", to_f64(o), O_ref, TOL_O)
+    assert_lse_close(to_f64(lse), LSE_ref)
+    assert_close("dQ", to_f64(dq), rq, TOL_GRAD)
+    assert_close("dK", to_f64(dk), rk, TOL_GRAD)
+    assert_close("dV", to_f64(dv), rv, TOL_GRAD)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shape(seed):
+    rng = np.random.default_rng(1000 + seed)
+    nseq = int(rng.integers(1, 5))
+    seqlens = [int(x) for x in rng.integers(1, 400, size=nseq)]
+    hkv = int(rng.integers(1, 4))
+    g = int(rng.integers(1, 9))
+    block = int(rng.choice([64, 128]))
+    topk = int(rng.integers(1, 9))
+    causal = bool(rng.integers(0, 4) > 0)
+    print("random case", seed, seqlens, hkv, g, block, topk, causal, flush=True)
+    w = wl.Workload(f"r{seed}", seqlens, hq=hkv * g, hkv=hkv, topk=topk, causal=causal, sink=bool(rng.integers(0, 2)),
+                    block=block, seed=seed)
+    wl.realise(w)
+    if rng.integers(0, 2):
+        w.idx = wl.draw_adversarial_indices(rng, seqlens, hkv, topk, block=block)
+    _check(w, scale=float(rng.choice([0.0, 0.11])))
+
+
+@pytest.mark.parametrize("n_tokens,g", [(1024, 1), (1025, 1), (2048, 2), (2049, 1), (4096 + 64, 1)])
+def test_list_length_at_unit_boundaries(n_tokens, g):
+    """Every token selects block 0 only: one list of exactly n_tokens entries (forward units hold 1024 entries,
+    backward units 2048), every other list empty."""
+    print("boundary case", n_tokens, g, flush=True)
+    w = wl.realise(wl.Workload("b", [n_tokens], hq=g, hkv=1, topk=2, seed=n_tokens))
+    w.idx[:] = -1
+    w.idx[:, :, 1] = 0
+    _check(w)
