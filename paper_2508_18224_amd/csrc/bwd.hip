@@ -5,14 +5,13 @@
 //
 //   k_bwd_delta       delta[t,h] = <dO[t,h], O[t,h]>, stored next to LSE[t,h] log2(e) as one 8-byte pair so that the
 //                     main kernel fetches both row statistics with one gather
-//   k_bwd_main        one work unit = (kv head j, KV block i, up to kBwdUnit list entries).  The four wavefronts
-//                     of a workgroup share tiles of 128 gathered rows.  Wave w owns rows 32w..32w+31 for
-//                     S^T = K_i Q^T, dP^T = V_i dO^T, P = exp(S - LSE), dS = P (dP - delta) scale and
-//                     dQ^T = K_i^T dS^T (its probabilities leave the MFMA already in B-operand layout), and it
-//                     owns channels 32w..32w+31 of the dK_i / dV_i accumulators, which stay in registers for
-//                     the whole unit: dV_i += P^T dO, dK_i += dS^T Q contract over the 128 rows of the tile
-//                     through LDS copies of P^T, dS^T, Q and dO.  Partial dQ rows go to the (token, head, slot)
-//                     workspace; the unit's dK_i, dV_i go to a per-unit fp32 buffer.
+//   k_bwd_main<NH>    one work unit = (kv head j, KV block i, up to kBwdUnit list entries); eight wavefronts share
+//                     tiles of 128 gathered rows and take three roles per tile (see the comment above the kernel):
+//                     S^T = K_i Q^T, dP^T = V_i dO^T, P = exp(S - LSE), dS = P (dP - delta) scale; then
+//                     dV_i += P^T dO and dK_i += dS^T Q (accumulators in registers for the whole unit) and
+//                     dQ^T = K_i^T dS^T.  All operands are row-major tiles in LDS; "lane = column" operands are
+//                     LDS transpose reads.  Partial dQ rows go to the compact buffer at the rows' list position;
+//                     the unit's dK_i, dV_i go out as bf16 (list fitted the unit) or to a per-unit fp32 buffer.
 //   k_bwd_dq_reduce   dQ[t,h] = sum over kept slots of the partial rows
 //   k_bwd_dkv_reduce  dK_i, dV_i = sum over the list's units in unit order (fixed order: bit-reproducible); a list
 //                     that fitted one unit was already written by that unit, a list with no entry gets zeros

@@ -1,19 +1,21 @@
 // Forward selected-block attention for gfx950 (paper Sec. 3.2, the KV-outer "token selection" step and the
 // reduction step; Eq. (2), c = sel).
 //
-// k_fwd_main: one work unit = (kv head j, KV block i, up to kFwdUnit entries of the block's query list).
+// k_fwd_main (B_K = 64): one work unit = (kv head j, KV block i, up to kFwdUnit entries of the block's query list).
 //   The block's K_i and V_i stay in registers for the whole unit (K as the A operand of S^T = K_i Q^T, V^T as
-//   the A operand of O^T = V_i^T P^T), so the inner loop touches no LDS: each wavefront walks tiles of 32
-//   query rows (row = (list entry, head of the group), flattened so any g packs densely), gathers the rows
-//   of Q straight into the B-operand layout, runs 16 + 16 MFMA 32x32x16 bf16, and does the softmax of the
-//   64 scores of a row inside the accumulator layout (a lane holds 32 keys of one query; one cross-lane
-//   exchange with lane ^ 32 completes max and sum).  Because S^T leaves each lane holding keys of ONE query,
-//   the probabilities are already in B-operand layout for the PV product; no transposition of P is needed.
+//   the A operand of O^T = V_i^T P^T), so the inner loop reads no K/V at all: each wavefront walks tiles of 32
+//   query rows (row = (list entry, head of the group), flattened so any g packs densely).  The rows of Q are
+//   gathered coalesced (16 lanes x 16 bytes per row) two tiles ahead and re-laid out into the B-operand layout
+//   through a wave-private LDS tile; 16 + 16 MFMA 32x32x16 bf16 per tile; the softmax of the 64 scores of a row
+//   runs inside the accumulator layout (a lane holds 32 keys of one query; one cross-lane exchange with
+//   lane ^ 32 completes max and sum).  Because S^T leaves each lane holding keys of ONE query, the probabilities
+//   are already in B-operand layout for the PV product; no transposition of P is needed.
 //   The result of a (token, head, block) triple is a partial output normalised by its own sum, plus the
 //   log-sum-exp of its 64 scores; both are stored at the entry's own position in the list order (the compact
-//   buffer the paper addresses through O_i), so a tile's 32 rows are one contiguous 8 KB write.
+//   buffer the paper addresses through O_i), so a tile's 32 rows are one contiguous 8 KB (non-temporal) write.
+// k_fwd_main128 (B_K = 128): see the comment above it.
 // k_fwd_merge: per (token, head) combines the kept slots: LSE = ln sum_s exp(lse_s), O = sum_s exp(lse_s-LSE) O_s.
-//   This replaces the paper's separate statistics pre-pass: per-slot (max, sum) make the merge exact.
+//   This replaces the paper's separate statistics pre-pass: per-slot log-sum-exps make the merge exact.
 #include "common.h"
 
 namespace nsa {

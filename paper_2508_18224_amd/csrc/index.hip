@@ -1,10 +1,9 @@
-// Index inversion for selected-block attention: from the selection table idx[token, kv head, slot] build, for
+// Index inversion for selected-block attention: from the selection table idx[token, kv head, column] build, for
 // every (kv head, KV block), the ascending list of query tokens that select it (the paper's index tensor I_i,
-// Sec. 3.2 "FSA token selection kernel") together with the slot each entry came from (which fixes its place
-// in the selection table) and, per kept (token, kv head, slot), the entry's position in its list, which is
-// where its partial result lives in the compact partial buffers (the role of the paper's O_i), plus the
-// work-unit tables of the attention
-// kernels.  Pipeline: per-(kv head, block, token chunk) histogram -> exclusive scan -> ordered scatter.
+// Sec. 3.2 "FSA token selection kernel") together with the column each entry came from, and, per kept
+// (token, kv head, column), the entry's position in its list, which is where its partial result lives in the
+// compact partial buffers (the role of the paper's O_i), plus the work-unit tables of the attention kernels.
+// Pipeline: per-(kv head, block, token chunk) histogram -> exclusive scan -> ordered scatter.
 // The scatter is deterministic: a chunk is walked by one wavefront in rounds of 64 tokens, and a token's rank
 // inside a round is a popcount over a 64-bit membership mask, so no ordering depends on atomics.
 #include "common.h"
