@@ -68,11 +68,11 @@ int nsa_sel_build_index(const nsa_sel_shape* shape, const int32_t* idx, const in
                         void* index_ws, size_t index_bytes, void* stream);
 
 /* Device pointers into a built index workspace (for inspection and tests): cnt int32 [hkv * b_cap],
- * off int32 [hkv * b_cap + 1] (exclusive prefix of cnt), qlist int32 [off[last]] token ids, qslot int32
- * [off[last]] columns, vmask uint32 [total_tokens * hkv] (bit m set: column m of the row was kept).
+ * off int32 [hkv * b_cap + 1] (exclusive prefix of cnt), qent int32 [off[last]][2] list entries as (token id,
+ * column of idx) pairs, vmask uint32 [total_tokens * hkv] (bit m set: column m of the row was kept).
  * *b_cap receives the list stride.  Any output pointer may be NULL. */
 int nsa_sel_index_view(const nsa_sel_shape* shape, const void* index_ws, const int32_t** cnt, const int32_t** off,
-                       const int32_t** qlist, const int32_t** qslot, const uint32_t** vmask, int32_t* b_cap);
+                       const int32_t** qent, const uint32_t** vmask, int32_t* b_cap);
 
 /* Forward (Eq. (2), c = sel): O and LSE from Q, K, V, idx.  With rebuild_index != 0 the index workspace is
  * (re)built from idx first; with 0 it must hold the result of an earlier build for the same idx/shape. */

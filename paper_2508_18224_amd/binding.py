@@ -35,7 +35,7 @@ def lib():
         vp, sz, i32p = C.c_void_p, C.c_size_t, C.c_void_p
         L.nsa_sel_workspace_bytes.argtypes = [C.POINTER(Shape), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
         L.nsa_sel_build_index.argtypes = [C.POINTER(Shape), i32p, i32p, vp, sz, vp]
-        L.nsa_sel_index_view.argtypes = [C.POINTER(Shape), vp] + [C.POINTER(vp)] * 5 + [C.POINTER(C.c_int32)]
+        L.nsa_sel_index_view.argtypes = [C.POINTER(Shape), vp] + [C.POINTER(vp)] * 4 + [C.POINTER(C.c_int32)]
         L.nsa_sel_fwd.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, sz, vp]
         L.nsa_sel_bwd.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, sz, vp]
         L.nsa_sel_profile_enable.argtypes = [C.c_int]
@@ -80,8 +80,8 @@ def build_index(shape: Shape, idx: torch.Tensor, cu: Optional[torch.Tensor], ind
 
 
 def index_view(shape: Shape, index_ws: torch.Tensor):
-    """Byte offsets (from the workspace base) of cnt, off, qlist, qslot, vmask, and the list stride b_cap."""
-    outs = [C.c_void_p() for _ in range(5)]
+    """Byte offsets (from the workspace base) of cnt, off, qent, vmask, and the list stride b_cap."""
+    outs = [C.c_void_p() for _ in range(4)]
     bcap = C.c_int32()
     _check(lib().nsa_sel_index_view(C.byref(shape), _ptr(index_ws), *[C.byref(o) for o in outs], C.byref(bcap)),
            "nsa_sel_index_view")
@@ -164,7 +164,7 @@ class SelAttention:
 
     def index_arrays(self):
         """Host copies of (cnt [hkv, b_cap], off, qlist, qslot, vmask [T, hkv]) for inspection."""
-        (o_cnt, o_off, o_ql, o_qs, o_vm), bcap = index_view(self.shape, self.index_ws)
+        (o_cnt, o_off, o_qe, o_vm), bcap = index_view(self.shape, self.index_ws)
         s = self.shape
         nl = s.hkv * bcap
         raw = self.index_ws
@@ -173,5 +173,6 @@ class SelAttention:
         cnt = ints(o_cnt, nl).reshape(s.hkv, bcap)
         off = ints(o_off, nl + 1)
         npairs = int(off[-1])
-        return cnt, off, ints(o_ql, npairs), ints(o_qs, npairs), ints(o_vm, s.total_tokens * s.hkv).reshape(
+        qent = ints(o_qe, 2 * npairs).reshape(npairs, 2)
+        return cnt, off, qent[:, 0].copy(), qent[:, 1].copy(), ints(o_vm, s.total_tokens * s.hkv).reshape(
             s.total_tokens, s.hkv).view("uint32"), bcap

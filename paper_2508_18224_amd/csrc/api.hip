@@ -50,8 +50,7 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.chunk_off = take(4 * (size_t)(L.n_counters + 1));
   L.cnt = take(4 * (size_t)L.n_lists);
   L.off = take(4 * (size_t)(L.n_lists + 1));
-  L.qlist = take(4 * (size_t)(L.p_max + 1));
-  L.qslot = take(4 * (size_t)(L.p_max + 1));
+  L.qent = take(8 * (size_t)(L.p_max + 1));
   L.vmask = take(4 * ((size_t)L.T * L.hkv + 1));
   L.slotpos = take(4 * (size_t)(L.p_max + 1));
   L.f_nu = take(4 * (size_t)(L.n_lists + 1));
@@ -124,7 +123,7 @@ int nsa_sel_build_index(const nsa_sel_shape* shape, const int32_t* idx, const in
 }
 
 int nsa_sel_index_view(const nsa_sel_shape* shape, const void* index_ws, const int32_t** cnt, const int32_t** off,
-                       const int32_t** qlist, const int32_t** qslot, const uint32_t** vmask, int32_t* b_cap) {
+                       const int32_t** qent, const uint32_t** vmask, int32_t* b_cap) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!index_ws) return NSA_SEL_EINVAL;
@@ -132,8 +131,7 @@ int nsa_sel_index_view(const nsa_sel_shape* shape, const void* index_ws, const i
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
   if (cnt) *cnt = p.cnt;
   if (off) *off = p.off;
-  if (qlist) *qlist = p.qlist;
-  if (qslot) *qslot = p.qslot;
+  if (qent) *qent = (const int32_t*)p.qent;
   if (vmask) *vmask = p.vmask;
   if (b_cap) *b_cap = L.b_cap;
   return NSA_SEL_OK;

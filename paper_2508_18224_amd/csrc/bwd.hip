@@ -89,7 +89,7 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
            const bf16_t* __restrict__ dO, const float2* __restrict__ stats,
            const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
-           const int32_t* __restrict__ qlist, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
+           const int2* __restrict__ qent, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
            float* __restrict__ dkv_part, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kLdsK);
@@ -134,7 +134,7 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   };
   load_kv(0);
   if (NH == 1) stage_kv();
-  for (int i = tid; i < ne; i += 512) ent[i] = qlist[e0 + i];
+  for (int i = tid; i < ne; i += 512) ent[i] = qent[e0 + i].x;
   f32x16 dkacc[NH], dvacc[NH];
 #pragma unroll
   for (int hf = 0; hf < NH; ++hf)
@@ -445,7 +445,7 @@ hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, con
   { ProfScope ps(KID_BWD_MAIN, st);
   hipLaunchKernelGGL(main_kernel, dim3(L.bwd_units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, (const float2*)delta, p.hdr, p.b_list,
-                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.b_nu, (bf16_t*)dqpart, dkv_part, (bf16_t*)dK, (bf16_t*)dV); }
+                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qent, p.b_nu, (bf16_t*)dqpart, dkv_part, (bf16_t*)dK, (bf16_t*)dV); }
   { ProfScope ps(KID_BWD_DQ_REDUCE, st);
   hipLaunchKernelGGL(k_bwd_dq_reduce, dim3(row_blocks), dim3(256), 0, st, P, (const bf16_t*)dqpart, p.vmask,
                      p.slotpos, (bf16_t*)dQ); }

@@ -26,7 +26,7 @@ struct IndexLayout {
   int64_t n_counters;   // n_lists * n_chunks
   int64_t p_max;        // T * hkv * topk
   int32_t fwd_units_max, bwd_units_max;
-  size_t hdr, blk_base, blk_tok0, blk_len, chunk_off, cnt, off, qlist, qslot, vmask, slotpos;
+  size_t hdr, blk_base, blk_tok0, blk_len, chunk_off, cnt, off, qent, vmask, slotpos;
   size_t f_nu, f_list, f_start, b_nu, b_list, b_start, scan_tmp;
   size_t total;
 };
@@ -42,10 +42,9 @@ struct IndexPtrs {
   int32_t* chunk_off;
   int32_t* cnt;
   int32_t* off;
-  int32_t* qlist;
-  int32_t* qslot;
+  int2* qent;        // list entries: (token, column of idx it came from)
   uint32_t* vmask;
-  int32_t* slotpos;  // [T, hkv, topk]: position in qlist of the entry a kept column produced
+  int32_t* slotpos;  // [T, hkv, topk]: position in qent of the entry a kept column produced
   int32_t *f_nu, *f_list, *f_start, *b_nu, *b_list, *b_start;
   int32_t* scan_tmp;
 };
@@ -60,8 +59,7 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
   r.chunk_off = (int32_t*)(p + L.chunk_off);
   r.cnt = (int32_t*)(p + L.cnt);
   r.off = (int32_t*)(p + L.off);
-  r.qlist = (int32_t*)(p + L.qlist);
-  r.qslot = (int32_t*)(p + L.qslot);
+  r.qent = (int2*)(p + L.qent);
   r.vmask = (uint32_t*)(p + L.vmask);
   r.slotpos = (int32_t*)(p + L.slotpos);
   r.f_nu = (int32_t*)(p + L.f_nu);

@@ -43,7 +43,7 @@ __global__ void __launch_bounds__(256)
 k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
            const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
-           const int32_t* __restrict__ qlist, const int32_t* __restrict__ qslot, bf16_t* __restrict__ opart,
+           const int2* __restrict__ qent, bf16_t* __restrict__ opart,
            float* __restrict__ lse_part) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kD * kVtStride];
   __shared__ __attribute__((aligned(16))) bf16_t tiles[4][32 * kTileStride];
@@ -78,7 +78,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
     for (int s = 0; s < 8; ++s) kf[mb][s] = key < blen ? *reinterpret_cast<const bf16x8*>(src + 16 * s) : zero8;
   }
-  for (int i = tid; i < ne; i += 256) ent[i] = make_int2(qlist[e0 + i], qslot[e0 + i]);
+  for (int i = tid; i < ne; i += 256) ent[i] = qent[e0 + i];
   __syncthreads();
   bf16x8 vf[4][4];
 #pragma unroll
@@ -239,7 +239,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
               const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list,
               const int32_t* __restrict__ u_start, const int32_t* __restrict__ off,
               const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
-              const int32_t* __restrict__ qlist, const int32_t* __restrict__ qslot, bf16_t* __restrict__ opart,
+              const int2* __restrict__ qent, bf16_t* __restrict__ opart,
               float* __restrict__ lse_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kF128K);
@@ -270,7 +270,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
           key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
     }
   }
-  for (int i = tid; i < ne; i += 64 * kWaves128) ent[i] = make_int2(qlist[e0 + i], qslot[e0 + i]);
+  for (int i = tid; i < ne; i += 64 * kWaves128) ent[i] = qent[e0 + i];
   __syncthreads();
 
   const int rows_total = ne * P.g;
@@ -473,10 +473,10 @@ hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, con
     ProfScope ps(KID_FWD_MAIN, st);
     hipLaunchKernelGGL(k_fwd_main128, dim3(L.fwd_units_max), dim3(64 * kWaves128), kF128Bytes, st, P, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len,
-                       p.qlist, p.qslot, (bf16_t*)opart, lse_part);
+                       p.qent, (bf16_t*)opart, lse_part);
   } else { ProfScope ps(KID_FWD_MAIN, st);
   hipLaunchKernelGGL(k_fwd_main, dim3(L.fwd_units_max), dim3(256), 0, st, P, (const bf16_t*)Q, (const bf16_t*)K,
-                     (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len, p.qlist, p.qslot,
+                     (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len, p.qent,
                      (bf16_t*)opart, lse_part); }
   const int64_t rows = (int64_t)P.T * P.hq;
   ProfScope ps(KID_FWD_MERGE, st);

@@ -64,9 +64,10 @@ __device__ __forceinline__ uint32_t kept_columns(const int32_t* row, int k, int 
   uint32_t vm = 0;
   for (int m = 0; m < k; ++m) {
     int x = row[m];
-    bool ok = x >= 0 && x < b_s && (!causal || x <= cur);
-    for (int mp = 0; mp < m && ok; ++mp) ok = row[mp] != x;
-    if (ok) vm |= 1u << m;
+    const bool ok = x >= 0 && x < b_s && (!causal || x <= cur);
+    bool dup = false;  // no early exit: the reads of the earlier columns are independent and overlap
+    for (int mp = 0; mp < m; ++mp) dup |= row[mp] == x;
+    if (ok && !dup) vm |= 1u << m;
   }
   return vm;
 }
@@ -87,7 +88,7 @@ __device__ __forceinline__ void chunk_window(const int32_t* cu, const int32_t* b
 __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                               const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
                                               int bk, int causal, int b_cap, int n_chunks,
-                                              int32_t* __restrict__ counters) {
+                                              int32_t* __restrict__ counters, uint32_t* __restrict__ vmask) {
   extern __shared__ int32_t lds[];
   int32_t* hist = lds;
   int32_t* rows = lds + b_cap;
@@ -106,7 +107,8 @@ __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, c
     for (int m = 0; m < k; ++m) row[m] = src[m];
     const int b_s = (c1 - c0 + bk - 1) / bk;
     const int cur = (t - c0) / bk;
-    uint32_t vm = kept_columns(row, k, b_s, cur, causal);
+    const uint32_t vm = kept_columns(row, k, b_s, cur, causal);
+    vmask[(size_t)t * hkv + j] = vm;
     const int base = blk_base[s] - gb_lo;
     for (int m = 0; m < k; ++m)
       if ((vm >> m) & 1u) atomicAdd(&hist[base + row[m]], 1);
@@ -183,18 +185,19 @@ static void scan_exclusive(int32_t* a, int64_t n, int32_t* tmp, hipStream_t st) 
 
 // ------------------------------------------------------------------------------------------------ scatter
 // grid (n_chunks, hkv), ONE wavefront per group.  chunk_off holds the scanned counters, i.e. for every
-// (kv head, block, chunk) the position in qlist where that chunk's tokens start.  Dynamic LDS: b_cap u64
-// masks + b_cap int cursors + 64*(k+1) ints.
+// (kv head, block, chunk) the position in qent where that chunk's tokens start.  Every kept column costs one
+// scattered 8-byte store (the list entry); the positions of a token's columns are collected in LDS and leave
+// as one contiguous row of slotpos.  Dynamic LDS: b_cap u64 masks + b_cap int cursors + 2 * 64*(k+1) ints.
 __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                                 const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
                                                 int bk, int causal, int b_cap, int n_chunks,
-                                                const int32_t* __restrict__ chunk_off, int32_t* __restrict__ qlist,
-                                                int32_t* __restrict__ qslot, uint32_t* __restrict__ vmask,
-                                                int32_t* __restrict__ slotpos) {
+                                                const int32_t* __restrict__ chunk_off, int2* __restrict__ qent,
+                                                const uint32_t* __restrict__ vmask, int32_t* __restrict__ slotpos) {
   extern __shared__ int32_t lds[];
   unsigned long long* mask = reinterpret_cast<unsigned long long*>(lds);
   int32_t* cursor = lds + 2 * b_cap;
   int32_t* rows = cursor + b_cap;
+  int32_t* prows = rows + 64 * (k + 1);
   const int chunk = blockIdx.x, j = blockIdx.y, lane = threadIdx.x;
   const int t0 = chunk * kChunkTokens, t1 = min(t0 + kChunkTokens, T);
   int gb_lo, gb_hi;
@@ -206,7 +209,9 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
   }
   __syncthreads();
   int32_t* row = rows + lane * (k + 1);
+  int32_t* prow = prows + lane * (k + 1);
   const unsigned long long below = (1ull << lane) - 1ull;
+  const bool vec4 = (k & 3) == 0 && ((reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(slotpos)) & 15) == 0;
   for (int r0 = t0; r0 < t1; r0 += 64) {
     const int t = r0 + lane;
     uint32_t vm = 0;
@@ -215,35 +220,72 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
       int s, c0, c1;
       seq_bounds(cu, nseq, T, t, s, c0, c1);
       const int32_t* src = idx + ((size_t)t * hkv + j) * k;
-      for (int m = 0; m < k; ++m) row[m] = src[m];
-      vm = kept_columns(row, k, (c1 - c0 + bk - 1) / bk, (t - c0) / bk, causal);
+      if (vec4) {
+        for (int m = 0; m < k; m += 4) {
+          const int4 x = *reinterpret_cast<const int4*>(src + m);
+          row[m] = x.x; row[m + 1] = x.y; row[m + 2] = x.z; row[m + 3] = x.w;
+        }
+      } else {
+        for (int m = 0; m < k; ++m) row[m] = src[m];
+      }
+      vm = vmask[(size_t)t * hkv + j];  // kept columns, decided by the histogram pass
       base = blk_base[s] - gb_lo;
-      vmask[(size_t)t * hkv + j] = vm;
     }
     // A: mark membership of this round's tokens in every block they keep
     for (int m = 0; m < k; ++m)
       if ((vm >> m) & 1u) atomicOr(&mask[base + row[m]], 1ull << lane);
     __syncthreads();
-    // B: rank among the lower tokens of the round gives the position; lists come out ascending
-    for (int m = 0; m < k; ++m)
-      if ((vm >> m) & 1u) {
-        const int w = base + row[m];
-        const int pos = cursor[w] + __popcll(mask[w] & below);
-        qlist[pos] = t;
-        qslot[pos] = m;
-        slotpos[((size_t)t * hkv + j) * k + m] = pos;
+    // B: rank among the lower tokens of the round gives the position; lists come out ascending.  Four columns
+    // per step so that their LDS reads are in flight together.
+    for (int m0 = 0; m0 < k; m0 += 4) {
+      int w[4], c[4];
+      unsigned long long mk[4];
+      bool on[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        on[u] = m0 + u < k && ((vm >> (m0 + u)) & 1u);
+        w[u] = on[u] ? base + row[m0 + u] : 0;
       }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        c[u] = cursor[w[u]];
+        mk[u] = mask[w[u]];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int pos = on[u] ? c[u] + __popcll(mk[u] & below) : -1;
+        if (on[u]) qent[pos] = make_int2(t, m0 + u);
+        if (m0 + u < k) prow[m0 + u] = pos;
+      }
+    }
+    if (t < t1) {
+      int32_t* dst = slotpos + ((size_t)t * hkv + j) * k;
+      if (vec4) {
+        for (int m = 0; m < k; m += 4)
+          *reinterpret_cast<int4*>(dst + m) = make_int4(prow[m], prow[m + 1], prow[m + 2], prow[m + 3]);
+      } else {
+        for (int m = 0; m < k; ++m) dst[m] = prow[m];
+      }
+    }
     __syncthreads();
     // C: the lowest member of each touched block advances its cursor and clears the mask
-    for (int m = 0; m < k; ++m)
-      if ((vm >> m) & 1u) {
-        const int w = base + row[m];
-        const unsigned long long mk = mask[w];
-        if (mk != 0ull && (mk & below) == 0ull) {
-          cursor[w] += __popcll(mk);
-          mask[w] = 0ull;
-        }
+    for (int m0 = 0; m0 < k; m0 += 4) {
+      int w[4];
+      unsigned long long mk[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool on = m0 + u < k && ((vm >> (m0 + u)) & 1u);
+        w[u] = on ? base + row[m0 + u] : -1;
       }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) mk[u] = w[u] >= 0 ? mask[w[u]] : 0ull;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (mk[u] != 0ull && (mk[u] & below) == 0ull) {
+          cursor[w[u]] += __popcll(mk[u]);
+          mask[w[u]] = 0ull;
+        }
+    }
     __syncthreads();
   }
 }
@@ -286,7 +328,7 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
                               hipStream_t st) {
   IndexPtrs p = index_ptrs(L, index_ws);
   const size_t lds_hist = (size_t)L.b_cap * 4 + 256 * (size_t)(L.topk + 1) * 4;
-  const size_t lds_scat = (size_t)L.b_cap * 12 + 64 * (size_t)(L.topk + 1) * 4;
+  const size_t lds_scat = (size_t)L.b_cap * 12 + 2 * 64 * (size_t)(L.topk + 1) * 4;
   if (lds_hist > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)k_hist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_hist);
     if (e != hipSuccess) return e;
@@ -305,13 +347,12 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
                      p.chunk_off, nc); }
   { ProfScope ps(KID_INDEX_HIST, st);
   hipLaunchKernelGGL(k_hist, dim3(L.n_chunks, L.hkv), dim3(256), lds_hist, st, idx, cu, p.blk_base, L.nseq, L.T, L.hkv,
-                     L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off); }
+                     L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.vmask); }
   { ProfScope ps(KID_INDEX_SCAN, st);
   scan_exclusive(p.chunk_off, nc, p.scan_tmp, st); }
   { ProfScope ps(KID_INDEX_SCATTER, st);
   hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
-                     L.hkv, L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qlist, p.qslot, p.vmask,
-                     p.slotpos); }
+                     L.hkv, L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qent, p.vmask, p.slotpos); }
   const int nl1 = L.n_lists + 1;
   { ProfScope ps(KID_INDEX_FINALIZE, st);
   hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.chunk_off, L.n_lists, L.n_chunks, p.cnt,
