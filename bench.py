@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the library's 1 GiB copy kernel once (for scaling rocprofv3 byte counters)")
+    ap.add_argument("--ws-cap-gb", type=float, default=0.0,
+                    help="cap each workspace at this many GB: the library then reuses it over groups of KV heads")
     ap.add_argument("--cpu-tokens", type=int, default=1280, help="query tokens of the CPU-oracle sample (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -85,7 +87,8 @@ def main():
     q, k, v, do = (dev(x) for x in (w.q, w.k, w.v, w.do))
     idx = torch.from_numpy(w.idx).cuda()
     cu = torch.from_numpy(w.cu_seqlens).cuda()
-    attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, block=w.block)
+    attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, block=w.block,
+                            ws_cap_bytes=int(args.ws_cap_gb * 1e9) if args.ws_cap_gb > 0 else None)
     o = torch.empty_like(q)
     lse = torch.empty(T, w.hq, dtype=torch.float32, device="cuda")
     grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
@@ -161,7 +164,9 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: N={T}, hq={w.hq}, hkv={w.hkv}, g={w.g}, topk={w.topk}, block={w.block}, "
                                f"d=128, causal, seed {w.seed}",
-                   "step": "index inversion + forward (main, merge) + backward (delta, main, dQ reduce, dK/dV reduce)"},
+                   "step": "index inversion + forward (main, merge) + backward (delta, main, dQ reduce, dK/dV reduce)",
+                   "workspace_GB": {"fwd": attn.fwd_ws.numel() / 1e9, "bwd": attn.bwd_ws.numel() / 1e9,
+                                    "index": attn.index_ws.numel() / 1e9}},
         "frac_of_bf16_mfma_peak": (f + b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "ms": {"index": idx_ms, "fwd": fwd_ms, "bwd": bwd_ms, "per_kernel": per_kernel},
         "roofline": roof,

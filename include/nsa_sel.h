@@ -20,6 +20,7 @@
  *   - cu_seqlens is int32 [nseq + 1] (device), cumulative sequence starts, cu_seqlens[nseq] == total_tokens;
  *     it may be NULL when nseq == 1.  Sequences need not be multiples of 64; the last block is ragged.
  *   - A row with no visible key gets O = 0, LSE = -inf and contributes no gradient.
+ *   - ws_bytes may lie anywhere between nsa_sel_workspace_bytes_min and nsa_sel_workspace_bytes (more is ignored).
  *   - Return value: 0 on success, a negative NSA_SEL_E* code otherwise.  Arguments are validated on the host
  *     before anything is launched; on error nothing has been enqueued (except NSA_SEL_EHIP, a launch failure).
  */
@@ -58,6 +59,13 @@ typedef struct {
  *   fwd_bytes:   per-(token, head, slot) partial outputs and log-sum-exps (the paper's O_buf, Sec. 3.2);
  *   bwd_bytes:   partial dQ, delta, and per-work-unit dK/dV partial sums. */
 int nsa_sel_workspace_bytes(const nsa_sel_shape* shape, size_t* fwd_bytes, size_t* bwd_bytes, size_t* index_bytes);
+
+/* Buffer reuse over head subsets (App. E, "implementation details and optimizations"): nsa_sel_fwd / nsa_sel_bwd
+ * also accept a ws smaller than the sizes above, down to the minima reported here (the partial results of ONE KV
+ * head with its g query heads; for the backward plus the per-row statistics of all heads).  The library then
+ * works through the KV heads in groups of as many heads as ws_bytes holds, one group after the other on the
+ * stream, reusing the buffers; results are bit-identical to the single-pass ones.  Either output may be NULL. */
+int nsa_sel_workspace_bytes_min(const nsa_sel_shape* shape, size_t* fwd_bytes, size_t* bwd_bytes);
 
 /* Index inversion (Sec. 3.2, "index tensors ... pre-computed from the NSA sparse selection tensor T"):
  * histogram -> exclusive scan -> ordered scatter.  For every list L = kv_head * b_cap + global_block

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
 _lib = None
 
-SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd",
+SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_workspace_bytes_min", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd",
            "nsa_sel_profile_enable", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_mfma_probe", "nsa_sel_strerror"]
 
 
@@ -34,6 +34,7 @@ def lib():
         L = C.CDLL(_LIB_PATH)
         vp, sz, i32p = C.c_void_p, C.c_size_t, C.c_void_p
         L.nsa_sel_workspace_bytes.argtypes = [C.POINTER(Shape), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+        L.nsa_sel_workspace_bytes_min.argtypes = [C.POINTER(Shape), C.POINTER(sz), C.POINTER(sz)]
         L.nsa_sel_build_index.argtypes = [C.POINTER(Shape), i32p, i32p, vp, sz, vp]
         L.nsa_sel_index_view.argtypes = [C.POINTER(Shape), vp] + [C.POINTER(vp)] * 4 + [C.POINTER(C.c_int32)]
         L.nsa_sel_fwd.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, sz, vp]
@@ -72,6 +73,13 @@ def workspace_bytes(shape: Shape):
     f, b, i = C.c_size_t(), C.c_size_t(), C.c_size_t()
     _check(lib().nsa_sel_workspace_bytes(C.byref(shape), C.byref(f), C.byref(b), C.byref(i)), "nsa_sel_workspace_bytes")
     return f.value, b.value, i.value
+
+
+def workspace_bytes_min(shape: Shape):
+    """Smallest (forward, backward) workspaces the library accepts: one KV head per pass."""
+    f, b = C.c_size_t(), C.c_size_t()
+    _check(lib().nsa_sel_workspace_bytes_min(C.byref(shape), C.byref(f), C.byref(b)), "nsa_sel_workspace_bytes_min")
+    return f.value, b.value
 
 
 def build_index(shape: Shape, idx: torch.Tensor, cu: Optional[torch.Tensor], index_ws: torch.Tensor):
@@ -133,9 +141,15 @@ class SelAttention:
     """Owns the workspaces for one shape and calls the library (buffers are torch uint8 tensors)."""
 
     def __init__(self, total_tokens, hq, hkv, topk, *, nseq=1, causal=True, scale=0.0, device="cuda:0", bwd=True,
-                 block=64):
+                 block=64, ws_cap_bytes=None):
+        """ws_cap_bytes caps each of the forward / backward workspaces (never below the library's minimum);
+        the library then works through the KV heads in as many passes as needed."""
         self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0)
         fb, bb, ib = workspace_bytes(self.shape)
+        if ws_cap_bytes is not None:
+            fmin, bmin = workspace_bytes_min(self.shape)
+            fb = min(fb, max(fmin, int(ws_cap_bytes)))
+            bb = min(bb, max(bmin, int(ws_cap_bytes)))
         self.device = torch.device(device)
         self.index_ws = torch.empty(ib, dtype=torch.uint8, device=self.device)
         self.fwd_ws = torch.empty(fb, dtype=torch.uint8, device=self.device)

@@ -17,7 +17,7 @@ static int check_shape(const nsa_sel_shape* s) {
   if (s->nseq > (1 << 20)) return NSA_SEL_EUNSUPPORTED;
   const int64_t b_cap = (int64_t)s->total_tokens / s->block + s->nseq;
   // LDS tables of the inversion (12 bytes per block) must fit in one CU's 160 KB
-  if (b_cap * 12 + 64 * (int64_t)(s->topk + 1) * 4 > 160 * 1024) return NSA_SEL_EUNSUPPORTED;
+  if (b_cap * 12 + 2 * 64 * (int64_t)(s->topk + 1) * 4 > 160 * 1024) return NSA_SEL_EUNSUPPORTED;
   const int64_t p_max = (int64_t)s->total_tokens * s->hkv * s->topk;
   if (p_max >= ((int64_t)1 << 31) - 4096) return NSA_SEL_EUNSUPPORTED;
   const int64_t n_chunks = ((int64_t)s->total_tokens + kChunkTokens - 1) / kChunkTokens;
@@ -75,23 +75,35 @@ static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
   P.causal = s->causal ? 1 : 0;
   P.b_cap = L.b_cap;
   P.bk = L.bk;
+  P.j0 = 0;
+  P.nj = s->hkv;
   P.scale = s->scale > 0.f ? s->scale : 0.08838834764831845f;  // 1/sqrt(128)
   return P;
 }
 
-static size_t partial_rows(const nsa_sel_shape* s) {  // one per (token, query head, selected block)
-  return (size_t)s->total_tokens * s->hq * s->topk;
+// Partial rows of nj KV heads: one per (token, query head of those KV heads, selected block).
+static size_t partial_rows(const nsa_sel_shape* s, int nj) {
+  return (size_t)s->total_tokens * nj * (s->hq / s->hkv) * s->topk;
 }
 
-static size_t fwd_ws_bytes(const nsa_sel_shape* s) {
-  const size_t rows = partial_rows(s);
+// Workspaces that hold the partial results of nj KV heads at once (nj = hkv: everything in one pass).
+static size_t fwd_ws_bytes(const nsa_sel_shape* s, int nj) {
+  const size_t rows = partial_rows(s, nj);
   return align256(rows * kD * 2) + align256(rows * 4);
 }
 
-static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L) {
-  const size_t rows = partial_rows(s);
+static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L, int nj) {
+  const size_t rows = partial_rows(s, nj);
   return align256(rows * kD * 2) + align256((size_t)s->total_tokens * s->hq * 8) +
-         align256((size_t)L.bwd_units_max * 2 * L.bk * kD * 4);
+         align256((size_t)bwd_units_bound(nj, L.b_cap, L.T, L.topk) * 2 * L.bk * kD * 4);
+}
+
+// Largest number of KV heads per pass that `bytes` can hold; 0 when not even one fits.
+template <class F>
+static int heads_that_fit(int hkv, size_t bytes, F need) {
+  int nj = hkv;
+  while (nj > 0 && need(nj) > bytes) --nj;
+  return nj;
 }
 }  // namespace nsa
 
@@ -103,9 +115,18 @@ int nsa_sel_workspace_bytes(const nsa_sel_shape* shape, size_t* fwd_bytes, size_
   int rc = check_shape(shape);
   if (rc) return rc;
   IndexLayout L = make_layout(shape);
-  if (fwd_bytes) *fwd_bytes = fwd_ws_bytes(shape);
-  if (bwd_bytes) *bwd_bytes = bwd_ws_bytes(shape, L);
+  if (fwd_bytes) *fwd_bytes = fwd_ws_bytes(shape, shape->hkv);
+  if (bwd_bytes) *bwd_bytes = bwd_ws_bytes(shape, L, shape->hkv);
   if (index_bytes) *index_bytes = L.total;
+  return NSA_SEL_OK;
+}
+
+int nsa_sel_workspace_bytes_min(const nsa_sel_shape* shape, size_t* fwd_bytes, size_t* bwd_bytes) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  IndexLayout L = make_layout(shape);
+  if (fwd_bytes) *fwd_bytes = fwd_ws_bytes(shape, 1);
+  if (bwd_bytes) *bwd_bytes = bwd_ws_bytes(shape, L, 1);
   return NSA_SEL_OK;
 }
 
@@ -146,15 +167,16 @@ int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   if (rebuild_index && !idx) return NSA_SEL_EINVAL;
   if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
   IndexLayout L = make_layout(shape);
-  if (index_bytes < L.total || ws_bytes < fwd_ws_bytes(shape)) return NSA_SEL_EWORKSPACE;
+  const int hpp = heads_that_fit(shape->hkv, ws_bytes, [&](int nj) { return fwd_ws_bytes(shape, nj); });
+  if (index_bytes < L.total || hpp < 1) return NSA_SEL_EWORKSPACE;
   if (shape->total_tokens == 0) return NSA_SEL_OK;
   hipStream_t st = (hipStream_t)stream;
   if (rebuild_index && launch_build_index(L, idx, cu_seqlens, index_ws, st) != hipSuccess) return NSA_SEL_EHIP;
   Problem P = make_problem(shape, L);
-  const size_t rows = partial_rows(shape);
+  const size_t rows = partial_rows(shape, hpp);
   void* opart = ws;
   float* lse_part = (float*)((char*)ws + align256(rows * kD * 2));
-  return launch_fwd(P, L, Q, K, V, index_ws, opart, lse_part, O, LSE, st) == hipSuccess ? NSA_SEL_OK : NSA_SEL_EHIP;
+  return launch_fwd(P, L, hpp, Q, K, V, index_ws, opart, lse_part, O, LSE, st) == hipSuccess ? NSA_SEL_OK : NSA_SEL_EHIP;
 }
 
 int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
@@ -165,15 +187,16 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   if (!Q || !K || !V || !O || !LSE || !dO || !index_ws || !dQ || !dK || !dV || !ws) return NSA_SEL_EINVAL;
   if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
   IndexLayout L = make_layout(shape);
-  if (index_bytes < L.total || ws_bytes < bwd_ws_bytes(shape, L)) return NSA_SEL_EWORKSPACE;
+  const int hpp = heads_that_fit(shape->hkv, ws_bytes, [&](int nj) { return bwd_ws_bytes(shape, L, nj); });
+  if (index_bytes < L.total || hpp < 1) return NSA_SEL_EWORKSPACE;
   if (shape->total_tokens == 0) return NSA_SEL_OK;
   Problem P = make_problem(shape, L);
-  const size_t rows = partial_rows(shape);
+  const size_t rows = partial_rows(shape, hpp);
   char* w = (char*)ws;
   void* dqpart = w;
   float* delta = (float*)(w + align256(rows * kD * 2));
   float* dkv_part = (float*)((char*)delta + align256((size_t)shape->total_tokens * shape->hq * 8));
-  return launch_bwd(P, L, Q, K, V, O, LSE, dO, index_ws, dqpart, delta, dkv_part, dQ, dK, dV, (hipStream_t)stream) ==
+  return launch_bwd(P, L, hpp, Q, K, V, O, LSE, dO, index_ws, dqpart, delta, dkv_part, dQ, dK, dV, (hipStream_t)stream) ==
                  hipSuccess
              ? NSA_SEL_OK
              : NSA_SEL_EHIP;
@@ -184,7 +207,7 @@ const char* nsa_sel_strerror(int code) {
     case NSA_SEL_OK: return "ok";
     case NSA_SEL_EINVAL: return "invalid argument (null pointer, head counts, nseq)";
     case NSA_SEL_EUNSUPPORTED: return "unsupported shape (d must be 128, block 64 or 128, topk 1..32, size limits)";
-    case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes)";
+    case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes / nsa_sel_workspace_bytes_min)";
     case NSA_SEL_EHIP: return "HIP runtime error at launch";
     default: return "unknown nsa_sel error code";
   }

@@ -87,7 +87,7 @@ template <int NH>
 __global__ void __launch_bounds__(512)
 k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
            const bf16_t* __restrict__ dO, const float2* __restrict__ stats,
-           const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
+           const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
            const int2* __restrict__ qent, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
            float* __restrict__ dkv_part, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
@@ -100,12 +100,15 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   bf16_t* dSt = reinterpret_cast<bf16_t*>(smem + kLdsDSt);
   int32_t* ent = reinterpret_cast<int32_t*>(smem + kLdsEnt);
 
-  const int u = blockIdx.x;
-  if (u >= hdr[HDR_BUNITS]) return;
+  // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
+  const int ubase = nu_scan[P.j0 * P.b_cap];
+  const int u = ubase + blockIdx.x;
+  if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
   const int L = u_list[u];
   const int j = L / P.b_cap;
   const int gb = L - j * P.b_cap;
   const int e0 = u_start[u];
+  const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
   const int ne = min(kBwdUnit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -324,7 +327,7 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         *reinterpret_cast<uint2*>(&Qmine[col * kRowStride + 64 * half + 32 * db + 8 * a + 4 * qh]) = w;
       }
     wave_sync_bwd();
-    const size_t prow0 = (size_t)e0 * P.g + (size_t)(tile0 + 32 * rb);
+    const size_t prow0 = (size_t)(e0 - pos0) * P.g + (size_t)(tile0 + 32 * rb);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = 8 * i + srow;
@@ -351,7 +354,7 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     return;
   }
   // unit partial: [u][0 = dK, 1 = dV][key][d] fp32, summed by k_bwd_dkv_reduce in unit order
-  float* outk = dkv_part + (size_t)u * 2 * (NH * kBlock) * kD + 32 * dsl + col;
+  float* outk = dkv_part + (size_t)(u - ubase) * 2 * (NH * kBlock) * kD + 32 * dsl + col;
   float* outv = outk + (NH * kBlock) * kD;
 #pragma unroll
   for (int hf = 0; hf < NH; ++hf)
@@ -365,13 +368,17 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 
 __global__ void __launch_bounds__(256)
 k_bwd_dq_reduce(Problem P, const bf16_t* __restrict__ dqpart, const uint32_t* __restrict__ vmask,
-                const int32_t* __restrict__ slotpos, bf16_t* __restrict__ dQ) {
-  const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+                const int32_t* __restrict__ slotpos, const int32_t* __restrict__ off, bf16_t* __restrict__ dQ) {
+  // rows of the pass: (token, head of the KV heads [j0, j0 + nj))
+  const int hp = P.nj * P.g;
+  const int64_t prow = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   const int sub = threadIdx.x & 15;
-  if (row >= (int64_t)P.T * P.hq) return;
-  const int t = (int)(row / P.hq);
-  const int h = (int)(row - (int64_t)t * P.hq);
+  if (prow >= (int64_t)P.T * hp) return;
+  const int t = (int)(prow / hp);
+  const int h = P.j0 * P.g + (int)(prow - (int64_t)t * hp);
+  const int64_t row = (int64_t)t * P.hq + h;
   const int j = h / P.g, hh = h - j * P.g;
+  const int pos0 = off[P.j0 * P.b_cap];
   const uint32_t vm = vmask[(size_t)t * P.hkv + j];
   const int32_t* sp = slotpos + ((size_t)t * P.hkv + j) * P.topk;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -381,7 +388,7 @@ k_bwd_dq_reduce(Problem P, const bf16_t* __restrict__ dqpart, const uint32_t* __
     for (int i = 0; i < 16; ++i) {
       const int m = m0 + i;
       const bool on = m < P.topk && ((vm >> m) & 1u);
-      x[i] = on ? *reinterpret_cast<const uint4*>(dqpart + ((size_t)sp[on ? m : 0] * P.g + hh) * kD + 8 * sub)
+      x[i] = on ? *reinterpret_cast<const uint4*>(dqpart + ((size_t)(sp[on ? m : 0] - pos0) * P.g + hh) * kD + 8 * sub)
                 : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
@@ -405,7 +412,8 @@ __global__ void __launch_bounds__(256)
 k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* __restrict__ blk_tok0,
                  const int32_t* __restrict__ blk_len, const float* __restrict__ dkv_part, bf16_t* __restrict__ dK,
                  bf16_t* __restrict__ dV) {
-  const int L = blockIdx.x, which = blockIdx.y;
+  const int L = P.j0 * P.b_cap + blockIdx.x, which = blockIdx.y;  // lists of the pass's KV heads
+  const int ubase = nu_scan[P.j0 * P.b_cap];
   const int j = L / P.b_cap, gb = L - j * P.b_cap;
   const int blen = blk_len[gb];
   if (blen == 0) return;
@@ -418,7 +426,7 @@ k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* 
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int u = u0; u < u1; ++u) {
       const float4 x =
-          *reinterpret_cast<const float4*>(dkv_part + ((size_t)u * 2 + which) * P.bk * kD + key * kD + d4);
+          *reinterpret_cast<const float4*>(dkv_part + ((size_t)(u - ubase) * 2 + which) * P.bk * kD + key * kD + d4);
       acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
     }
     uint2 w;
@@ -428,30 +436,40 @@ k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* 
   }
 }
 
-hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
-                      const void* O, const float* LSE, const void* dO, const void* index_ws, void* dqpart,
-                      float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st) {
+hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
+                      const void* V, const void* O, const float* LSE, const void* dO, const void* index_ws,
+                      void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
-  auto* main_kernel = P.bk == 128 ? k_bwd_main<2> : k_bwd_main<1>;
+  auto* main_kernel = P0.bk == 128 ? k_bwd_main<2> : k_bwd_main<1>;
   {
     hipError_t e = hipFuncSetAttribute((const void*)main_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBwdBytes);
     if (e != hipSuccess) return e;
   }
-  const int64_t rows = (int64_t)P.T * P.hq;
-  const unsigned row_blocks = (unsigned)((rows + 15) / 16);
-  { ProfScope ps(KID_BWD_DELTA, st);
-  hipLaunchKernelGGL(k_bwd_delta, dim3(row_blocks), dim3(256), 0, st, rows, (const bf16_t*)O, (const bf16_t*)dO, LSE,
-                     (float2*)delta); }
-  { ProfScope ps(KID_BWD_MAIN, st);
-  hipLaunchKernelGGL(main_kernel, dim3(L.bwd_units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
-                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, (const float2*)delta, p.hdr, p.b_list,
-                     p.b_start, p.off, p.blk_tok0, p.blk_len, p.qent, p.b_nu, (bf16_t*)dqpart, dkv_part, (bf16_t*)dK, (bf16_t*)dV); }
-  { ProfScope ps(KID_BWD_DQ_REDUCE, st);
-  hipLaunchKernelGGL(k_bwd_dq_reduce, dim3(row_blocks), dim3(256), 0, st, P, (const bf16_t*)dqpart, p.vmask,
-                     p.slotpos, (bf16_t*)dQ); }
-  ProfScope ps(KID_BWD_DKV_REDUCE, st);
-  hipLaunchKernelGGL(k_bwd_dkv_reduce, dim3(L.n_lists, 2), dim3(256), 0, st, P, p.b_nu, p.blk_tok0, p.blk_len,
-                     (const float*)dkv_part, (bf16_t*)dK, (bf16_t*)dV);
+  {
+    const int64_t rows = (int64_t)P0.T * P0.hq;
+    ProfScope ps(KID_BWD_DELTA, st);
+    hipLaunchKernelGGL(k_bwd_delta, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, rows, (const bf16_t*)O,
+                       (const bf16_t*)dO, LSE, (float2*)delta);
+  }
+  // KV heads are processed heads_per_pass at a time, every pass reusing the partial-dQ and unit-partial buffers
+  for (int j0 = 0; j0 < P0.hkv; j0 += heads_per_pass) {
+    Problem P = P0;
+    P.j0 = j0;
+    P.nj = min(heads_per_pass, P0.hkv - j0);
+    const unsigned units_max = (unsigned)bwd_units_bound(P.nj, P.b_cap, P.T, P.topk);
+    const int64_t rows = (int64_t)P.T * P.nj * P.g;
+    { ProfScope ps(KID_BWD_MAIN, st);
+    hipLaunchKernelGGL(main_kernel, dim3(units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, (const float2*)delta, p.b_list,
+                       p.b_start, p.off, p.blk_tok0, p.blk_len, p.qent, p.b_nu, (bf16_t*)dqpart, dkv_part,
+                       (bf16_t*)dK, (bf16_t*)dV); }
+    { ProfScope ps(KID_BWD_DQ_REDUCE, st);
+    hipLaunchKernelGGL(k_bwd_dq_reduce, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P,
+                       (const bf16_t*)dqpart, p.vmask, p.slotpos, p.off, (bf16_t*)dQ); }
+    ProfScope ps(KID_BWD_DKV_REDUCE, st);
+    hipLaunchKernelGGL(k_bwd_dkv_reduce, dim3(P.nj * P.b_cap, 2), dim3(256), 0, st, P, p.b_nu, p.blk_tok0, p.blk_len,
+                       (const float*)dkv_part, (bf16_t*)dK, (bf16_t*)dV);
+  }
   return hipGetLastError();
 }
 

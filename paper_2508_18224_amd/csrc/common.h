@@ -75,8 +75,18 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
 // Problem description handed to the attention kernels.
 struct Problem {
   int32_t T, nseq, hq, hkv, g, topk, causal, b_cap, bk;
+  int32_t j0, nj;  // KV heads [j0, j0 + nj) handled by this launch (all of them unless the workspace is capped)
   float scale;
 };
+
+// Upper bounds of the work units of nj KV heads (one per non-empty list plus one per full unit of entries);
+// the real counts are only known on the device.
+inline int64_t fwd_units_bound(int nj, int b_cap, int T, int topk) {
+  return (int64_t)nj * b_cap + (int64_t)nj * T * topk / kFwdUnit + 1;
+}
+inline int64_t bwd_units_bound(int nj, int b_cap, int T, int topk) {
+  return (int64_t)nj * b_cap + (int64_t)nj * T * topk / kBwdUnit + 1;
+}
 
 // ---- optional per-kernel timing (off unless nsa_sel_profile_enable was called) ---------------------------
 enum KernelId {
@@ -95,11 +105,13 @@ struct ProfScope {
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) -------------------------------------
 hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
                               hipStream_t st);
-hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
-                      const void* index_ws, void* opart, float* lse_part, void* O, float* LSE, hipStream_t st);
-hipError_t launch_bwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
-                      const void* O, const float* LSE, const void* dO, const void* index_ws, void* dqpart,
-                      float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st);
+// heads_per_pass: KV heads whose partial results the workspace can hold at once (1 .. hkv)
+hipError_t launch_fwd(const Problem& P, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
+                      const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
+                      hipStream_t st);
+hipError_t launch_bwd(const Problem& P, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
+                      const void* V, const void* O, const float* LSE, const void* dO, const void* index_ws,
+                      void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st);
 
 // ---- device helpers ------------------------------------------------------------------------------------
 #if defined(__HIPCC__)

@@ -41,19 +41,21 @@ __device__ __forceinline__ void wave_sync() {
 
 __global__ void __launch_bounds__(256)
 k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-           const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
+           const int32_t* __restrict__ nu_scan, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
            const int2* __restrict__ qent, bf16_t* __restrict__ opart,
            float* __restrict__ lse_part) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kD * kVtStride];
   __shared__ __attribute__((aligned(16))) bf16_t tiles[4][32 * kTileStride];
   __shared__ int2 ent[kFwdUnit];  // (token, slot) of the unit's list entries
-  const int u = blockIdx.x;
-  if (u >= hdr[HDR_FUNITS]) return;
+  // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
+  const int u = nu_scan[P.j0 * P.b_cap] + blockIdx.x;
+  if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
   const int L = u_list[u];
   const int j = L / P.b_cap;
   const int gb = L - j * P.b_cap;
   const int e0 = u_start[u];
+  const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
   const int ne = min(kFwdUnit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
@@ -190,7 +192,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       }
     wave_sync();
     // partial rows live at the list position of their entry: a tile's 32 rows are one contiguous 8 KB run
-    const size_t prow0 = (size_t)e0 * P.g + (size_t)tile * 32;
+    const size_t prow0 = (size_t)(e0 - pos0) * P.g + (size_t)tile * 32;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = 4 * i + crow;
@@ -236,7 +238,7 @@ __device__ __forceinline__ bf16x4 lds_read_tr_f(const bf16_t* p) {
 
 __global__ void __launch_bounds__(64 * kWaves128)
 k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-              const int32_t* __restrict__ hdr, const int32_t* __restrict__ u_list,
+              const int32_t* __restrict__ nu_scan, const int32_t* __restrict__ u_list,
               const int32_t* __restrict__ u_start, const int32_t* __restrict__ off,
               const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
               const int2* __restrict__ qent, bf16_t* __restrict__ opart,
@@ -245,12 +247,14 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kF128K);
   bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kF128V);
   int2* ent = reinterpret_cast<int2*>(smem + kF128Ent);
-  const int u = blockIdx.x;
-  if (u >= hdr[HDR_FUNITS]) return;
+  // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
+  const int u = nu_scan[P.j0 * P.b_cap] + blockIdx.x;
+  if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
   const int L = u_list[u];
   const int j = L / P.b_cap;
   const int gb = L - j * P.b_cap;
   const int e0 = u_start[u];
+  const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
   const int ne = min(kFwdUnit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -382,7 +386,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
         *reinterpret_cast<uint2*>(&tile_lds[col * kTileStride + 32 * db + 8 * a + 4 * qh]) = w;
       }
     wave_sync();
-    const size_t prow0 = (size_t)e0 * P.g + (size_t)tile * 32;
+    const size_t prow0 = (size_t)(e0 - pos0) * P.g + (size_t)tile * 32;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = 4 * i + crow;
@@ -400,14 +404,19 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
 // 16 independent 256-byte gathers in flight; batches are chained by the usual running-max rescale.
 __global__ void __launch_bounds__(256)
 k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict__ lse_part,
-            const uint32_t* __restrict__ vmask, const int32_t* __restrict__ slotpos, bf16_t* __restrict__ O,
+            const uint32_t* __restrict__ vmask, const int32_t* __restrict__ slotpos,
+            const int32_t* __restrict__ off, bf16_t* __restrict__ O,
             float* __restrict__ LSE) {
-  const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  // rows of the pass: (token, head of the KV heads [j0, j0 + nj))
+  const int hp = P.nj * P.g;
+  const int64_t prow = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   const int sub = threadIdx.x & 15;
-  if (row >= (int64_t)P.T * P.hq) return;
-  const int t = (int)(row / P.hq);
-  const int h = (int)(row - (int64_t)t * P.hq);
+  if (prow >= (int64_t)P.T * hp) return;
+  const int t = (int)(prow / hp);
+  const int h = P.j0 * P.g + (int)(prow - (int64_t)t * hp);
+  const int64_t row = (int64_t)t * P.hq + h;
   const int j = h / P.g, hh = h - j * P.g;
+  const int pos0 = off[P.j0 * P.b_cap];
   const uint32_t vm = vmask[(size_t)t * P.hkv + j];
   bf16_t* orow = O + row * kD + 8 * sub;
   if (vm == 0u) {
@@ -426,7 +435,7 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
     for (int i = 0; i < 16; ++i) {
       const int m = m0 + i;
       const bool on = m < P.topk && ((vm >> m) & 1u);
-      pr[i] = on ? (size_t)sp[m] * P.g + hh : (size_t)0;
+      pr[i] = on ? (size_t)(sp[m] - pos0) * P.g + hh : (size_t)0;
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -464,24 +473,38 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
   if (sub == 0) LSE[row] = M + __logf(Ls);
 }
 
-hipError_t launch_fwd(const Problem& P, const IndexLayout& L, const void* Q, const void* K, const void* V,
-                      const void* index_ws, void* opart, float* lse_part, void* O, float* LSE, hipStream_t st) {
+hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
+                      const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
+                      hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
-  if (P.bk == 128) {
+  if (P0.bk == 128) {
     hipError_t e = hipFuncSetAttribute((const void*)k_fwd_main128, hipFuncAttributeMaxDynamicSharedMemorySize, kF128Bytes);
     if (e != hipSuccess) return e;
-    ProfScope ps(KID_FWD_MAIN, st);
-    hipLaunchKernelGGL(k_fwd_main128, dim3(L.fwd_units_max), dim3(64 * kWaves128), kF128Bytes, st, P, (const bf16_t*)Q,
-                       (const bf16_t*)K, (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len,
-                       p.qent, (bf16_t*)opart, lse_part);
-  } else { ProfScope ps(KID_FWD_MAIN, st);
-  hipLaunchKernelGGL(k_fwd_main, dim3(L.fwd_units_max), dim3(256), 0, st, P, (const bf16_t*)Q, (const bf16_t*)K,
-                     (const bf16_t*)V, p.hdr, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len, p.qent,
-                     (bf16_t*)opart, lse_part); }
-  const int64_t rows = (int64_t)P.T * P.hq;
-  ProfScope ps(KID_FWD_MERGE, st);
-  hipLaunchKernelGGL(k_fwd_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P, (const bf16_t*)opart,
-                     (const float*)lse_part, p.vmask, p.slotpos, (bf16_t*)O, LSE);
+  }
+  // KV heads are processed heads_per_pass at a time; every pass reuses the same partial buffers (the lists of
+  // one KV head are contiguous in list-position order, so a pass owns a contiguous range of positions).
+  for (int j0 = 0; j0 < P0.hkv; j0 += heads_per_pass) {
+    Problem P = P0;
+    P.j0 = j0;
+    P.nj = min(heads_per_pass, P0.hkv - j0);
+    // upper bound of the work units of the pass (the real count is only known on the device)
+    const unsigned units_max = (unsigned)fwd_units_bound(P.nj, P.b_cap, P.T, P.topk);
+    if (P.bk == 128) {
+      ProfScope ps(KID_FWD_MAIN, st);
+      hipLaunchKernelGGL(k_fwd_main128, dim3(units_max), dim3(64 * kWaves128), kF128Bytes, st, P, (const bf16_t*)Q,
+                         (const bf16_t*)K, (const bf16_t*)V, p.f_nu, p.f_list, p.f_start, p.off, p.blk_tok0,
+                         p.blk_len, p.qent, (bf16_t*)opart, lse_part);
+    } else {
+      ProfScope ps(KID_FWD_MAIN, st);
+      hipLaunchKernelGGL(k_fwd_main, dim3(units_max), dim3(256), 0, st, P, (const bf16_t*)Q, (const bf16_t*)K,
+                         (const bf16_t*)V, p.f_nu, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len, p.qent,
+                         (bf16_t*)opart, lse_part);
+    }
+    const int64_t rows = (int64_t)P.T * P.nj * P.g;
+    ProfScope ps(KID_FWD_MERGE, st);
+    hipLaunchKernelGGL(k_fwd_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P, (const bf16_t*)opart,
+                       (const float*)lse_part, p.vmask, p.slotpos, p.off, (bf16_t*)O, LSE);
+  }
   return hipGetLastError();
 }
 

@@ -29,6 +29,8 @@ def test_shape_validation_happens_on_the_host():
     f, b, i = nsa.workspace_bytes(ok)
     assert f >= 4096 * 8 * 16 * 128 * 2 and b > f and i > 0
     assert nsa.workspace_bytes(nsa.Shape(4096, 1, 8, 2, 128, 128, 8, 1, 0.0, 0))[0] * 2 == f   # half the slots
+    fmin, bmin = nsa.workspace_bytes_min(ok)                 # one of the two KV heads per pass
+    assert fmin * 2 == f and fmin >= 4096 * 4 * 16 * 128 * 2 and fmin < bmin < b
     bad = [
         (nsa.Shape(4096, 1, 8, 3, 128, 64, 16, 1, 0.0, 0), -1),     # hq % hkv
         (nsa.Shape(4096, 1, 18, 2, 128, 64, 16, 1, 0.0, 0), -1),    # g = 9

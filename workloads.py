@@ -207,6 +207,8 @@ def small(name: str) -> Workload:
         return Workload(name, [2500], hq=4, hkv=1, topk=32, sink=True, seed=16)
     if name == "g3_k1":
         return Workload(name, [777], hq=3, hkv=1, topk=1, seed=17)
+    if name == "g2_hkv5":       # several KV heads, a sink list long enough to split into work units
+        return Workload(name, [2300, 700], hq=10, hkv=5, topk=8, sink=True, seed=20)
     if name == "b128_g4":       # the paper's second setting (B_K, T) = (128, 8)
         return Workload(name, [2100], hq=8, hkv=2, topk=8, sink=True, block=128, seed=18)
     if name == "b128_varlen":
@@ -214,7 +216,7 @@ def small(name: str) -> Workload:
     raise KeyError(name)
 
 
-SMALL_NAMES = ["g4", "g7", "g1_varlen", "g8", "g2_noncausal", "g4_k32", "g3_k1", "b128_g4", "b128_varlen"]
+SMALL_NAMES = ["g4", "g7", "g1_varlen", "g8", "g2_noncausal", "g4_k32", "g3_k1", "g2_hkv5", "b128_g4", "b128_varlen"]
 
 
 def draw_adversarial_indices(rng: np.random.Generator, seqlens: Sequence[int], hkv: int, topk: int,
