@@ -126,13 +126,17 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    nsa.profile_enable(args.steps * 24)
+    nsa.profile_enable(args.steps * (24 + 8 * w.hkv))   # room for every launch, also with a capped workspace
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()      # on the launch stream, no synchronisation: per-step spread only
         step()
+    marks[args.steps].record()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = nsa.profile_collect()
     nsa.profile_enable(0)
 
@@ -168,7 +172,8 @@ def main():
                    "workspace_GB": {"fwd": attn.fwd_ws.numel() / 1e9, "bwd": attn.bwd_ws.numel() / 1e9,
                                     "index": attn.index_ws.numel() / 1e9}},
         "frac_of_bf16_mfma_peak": (f + b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "ms": {"index": idx_ms, "fwd": fwd_ms, "bwd": bwd_ms, "per_kernel": per_kernel},
+        "ms": {"index": idx_ms, "fwd": fwd_ms, "bwd": bwd_ms, "per_kernel": per_kernel,
+               "step_median": per_step[len(per_step) // 2], "step_min": per_step[0]},
         "roofline": roof,
         "measured_peaks": {"mfma_loop_TFLOPs": mfma_measured, "stream_copy_GBps": copy_measured,
                            "frac_of_measured_mfma": (f + b) / (ms * 1e-3) / 1e12 / mfma_measured},

@@ -72,14 +72,16 @@ __device__ __forceinline__ uint32_t kept_columns(const int32_t* row, int k, int 
   return vm;
 }
 
-// Window of global blocks a token chunk can touch: all blocks of the sequences it overlaps.
+// Window of global blocks a token chunk can touch: the blocks of the sequences it overlaps, and under the
+// causal rule none past the block of the chunk's last token.
 __device__ __forceinline__ void chunk_window(const int32_t* cu, const int32_t* blk_base, int nseq, int T, int t0,
-                                             int t1, int& gb_lo, int& gb_hi) {
-  int s0, s1, a, b;
+                                             int t1, int bk, int causal, int& gb_lo, int& gb_hi) {
+  int s0, s1, a, b, c0;
   seq_bounds(cu, nseq, T, t0, s0, a, b);
-  seq_bounds(cu, nseq, T, t1 - 1, s1, a, b);
+  seq_bounds(cu, nseq, T, t1 - 1, s1, c0, b);
   gb_lo = blk_base[s0];
   gb_hi = blk_base[s1 + 1];
+  if (causal) gb_hi = min(gb_hi, blk_base[s1] + (t1 - 1 - c0) / bk + 1);
 }
 
 // ------------------------------------------------------------------------------------------------ histogram
@@ -95,7 +97,7 @@ __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, c
   const int chunk = blockIdx.x, j = blockIdx.y;
   const int t0 = chunk * kChunkTokens, t1 = min(t0 + kChunkTokens, T);
   int gb_lo, gb_hi;
-  chunk_window(cu, blk_base, nseq, T, t0, t1, gb_lo, gb_hi);
+  chunk_window(cu, blk_base, nseq, T, t0, t1, bk, causal, gb_lo, gb_hi);
   const int win = gb_hi - gb_lo;
   for (int i = threadIdx.x; i < win; i += blockDim.x) hist[i] = 0;
   __syncthreads();
@@ -201,7 +203,7 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
   const int chunk = blockIdx.x, j = blockIdx.y, lane = threadIdx.x;
   const int t0 = chunk * kChunkTokens, t1 = min(t0 + kChunkTokens, T);
   int gb_lo, gb_hi;
-  chunk_window(cu, blk_base, nseq, T, t0, t1, gb_lo, gb_hi);
+  chunk_window(cu, blk_base, nseq, T, t0, t1, bk, causal, gb_lo, gb_hi);
   const int win = gb_hi - gb_lo;
   for (int i = lane; i < win; i += 64) {
     mask[i] = 0ull;

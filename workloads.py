@@ -12,6 +12,8 @@ generation order (forced, local, uniform) and padded with -1.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import List, Optional, Sequence
 
@@ -147,13 +149,29 @@ def realise(w: Workload, *, tensors: bool = True) -> Workload:
     w.idx = draw_block_indices(rng, w.seqlens, w.hkv, w.topk, sink=w.sink, recent=w.recent,
                                local_picks=w.local_picks, local_window=w.local_window, block=w.block)
     if tensors:
-        def draw(heads):
-            return f32_to_bf16_bits(rng.standard_normal((T, heads, w.d), dtype=np.float32))
-        w.q = draw(w.hq)
-        w.k = draw(w.hkv)
-        w.v = draw(w.hkv)
-        w.do = draw(w.hq)
+        w.q = _draw_bf16(w.seed, 0, T, w.hq, w.d)
+        w.k = _draw_bf16(w.seed, 1, T, w.hkv, w.d)
+        w.v = _draw_bf16(w.seed, 2, T, w.hkv, w.d)
+        w.do = _draw_bf16(w.seed, 3, T, w.hq, w.d)
     return w
+
+
+_SLAB_TOKENS = 2048
+
+
+def _draw_bf16(seed: int, tensor: int, T: int, heads: int, d: int) -> np.ndarray:
+    """Standard-normal values rounded to bf16, [T, heads, d] as bit patterns.  Every slab of 2048 tokens has
+    its own generator seeded by (seed, tensor, slab), so the result does not depend on how many threads draw."""
+    out = np.empty((T, heads, d), dtype=np.uint16)
+
+    def work(t0: int):
+        t1 = min(t0 + _SLAB_TOKENS, T)
+        r = np.random.default_rng([seed, tensor, t0 // _SLAB_TOKENS])
+        out[t0:t1] = f32_to_bf16_bits(r.standard_normal((t1 - t0, heads, d), dtype=np.float32))
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        list(pool.map(work, range(0, T, _SLAB_TOKENS)))
+    return out
 
 
 # ----------------------------------------------------------------------------- named workloads
@@ -179,11 +197,13 @@ def named(name: str) -> Workload:
         return Workload(name, [131072], hq=64, hkv=8, topk=16, sink=True, recent=2, seed=1005)
     if name == "headline_b128":   # the headline shape at the paper's second setting (B_K, T) = (128, 8)
         return Workload(name, [65536], hq=32, hkv=8, topk=8, sink=True, block=128, seed=1006)
-    if name.startswith("grid_"):  # the paper's kernel grid (Sec. 4.1): grid_g<g>_b<B_K>_n<N in K>, 32 query heads
+    if name.startswith("grid_"):
+        # the paper's kernel grid (Sec. 4.1): grid_g<g>_b<B_K>_n<N in K>[_h<query heads>], 32 query heads unless
+        # given (the 128K / 256K tables of App. F use 64)
         parts = dict((p[0], int(p[1:])) for p in name.split("_")[1:])
-        g, block, n = parts["g"], parts["b"], parts["n"] * 1024
-        return Workload(name, [n], hq=32, hkv=32 // g, topk=1024 // block, sink=True, block=block,
-                        seed=2000 + 100 * g + block + parts["n"])
+        g, block, n, hq = parts["g"], parts["b"], parts["n"] * 1024, parts.get("h", 32)
+        return Workload(name, [n], hq=hq, hkv=hq // g, topk=1024 // block, sink=True, block=block,
+                        seed=2000 + 100 * g + block + parts["n"] + (hq if hq != 32 else 0))
     raise KeyError(name)
 
 
