@@ -8,7 +8,8 @@
  * products are dense MFMA tiles with no padding of small query tiles.
  *
  * Conventions
- *   - All tensor pointers are DEVICE pointers; `shape` and the size_t outputs are HOST pointers.
+ *   - All tensor pointers are DEVICE pointers; `shape` and the size_t outputs are HOST pointers.  Q, K, V, O, dO,
+ *     dQ, dK, dV and the workspaces must be 16-byte aligned (NSA_SEL_EINVAL otherwise).
  *   - The library never allocates, frees or synchronises: every buffer, including workspaces, belongs to
  *     the caller, and all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream).
  *   - Layouts are token-major and contiguous: Q, O, dO, dQ are bf16 [total_tokens, hq, d]; K, V, dK, dV are
@@ -35,9 +36,9 @@ extern "C" {
 #endif
 
 #define NSA_SEL_OK            0
-#define NSA_SEL_EINVAL       -1   /* null pointer, g outside [1,8], hq % hkv != 0, nseq < 1, negative sizes    */
+#define NSA_SEL_EINVAL       -1   /* null/misaligned pointer, g not in [1,8], hq % hkv != 0, nseq < 1, negative size */
 #define NSA_SEL_EUNSUPPORTED -2   /* d != 128, block not 64 or 128, topk outside [1,32], too many tokens      */
-#define NSA_SEL_EWORKSPACE   -3   /* a workspace is smaller than nsa_sel_workspace_bytes reports              */
+#define NSA_SEL_EWORKSPACE   -3   /* index workspace too small, or ws below nsa_sel_workspace_bytes_min       */
 #define NSA_SEL_EHIP         -4   /* the HIP runtime refused a launch or attribute                            */
 
 typedef struct {

@@ -6,6 +6,9 @@ int64_t index_scan_tmp_ints(int64_t n_counters);
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Tensors are moved with 16-byte accesses and the workspaces are carved at 256-byte offsets.
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
 static int check_shape(const nsa_sel_shape* s) {
   if (!s) return NSA_SEL_EINVAL;
   if (s->total_tokens < 0 || s->nseq < 1 || s->hq < 1 || s->hkv < 1) return NSA_SEL_EINVAL;
@@ -134,7 +137,7 @@ int nsa_sel_build_index(const nsa_sel_shape* shape, const int32_t* idx, const in
                         size_t index_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
-  if (!idx || !index_ws) return NSA_SEL_EINVAL;
+  if (!idx || !index_ws || !aligned16(index_ws)) return NSA_SEL_EINVAL;
   if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
   IndexLayout L = make_layout(shape);
   if (index_bytes < L.total) return NSA_SEL_EWORKSPACE;
@@ -164,6 +167,8 @@ int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!Q || !K || !V || !index_ws || !O || !LSE || !ws) return NSA_SEL_EINVAL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(ws) || !aligned16(index_ws))
+    return NSA_SEL_EINVAL;
   if (rebuild_index && !idx) return NSA_SEL_EINVAL;
   if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
   IndexLayout L = make_layout(shape);
@@ -185,6 +190,9 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!Q || !K || !V || !O || !LSE || !dO || !index_ws || !dQ || !dK || !dV || !ws) return NSA_SEL_EINVAL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(dQ) ||
+      !aligned16(dK) || !aligned16(dV) || !aligned16(ws) || !aligned16(index_ws))
+    return NSA_SEL_EINVAL;
   if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
   IndexLayout L = make_layout(shape);
   const int hpp = heads_that_fit(shape->hkv, ws_bytes, [&](int nj) { return bwd_ws_bytes(shape, L, nj); });
@@ -205,7 +213,7 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
 const char* nsa_sel_strerror(int code) {
   switch (code) {
     case NSA_SEL_OK: return "ok";
-    case NSA_SEL_EINVAL: return "invalid argument (null pointer, head counts, nseq)";
+    case NSA_SEL_EINVAL: return "invalid argument (null or misaligned pointer, head counts, nseq)";
     case NSA_SEL_EUNSUPPORTED: return "unsupported shape (d must be 128, block 64 or 128, topk 1..32, size limits)";
     case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes / nsa_sel_workspace_bytes_min)";
     case NSA_SEL_EHIP: return "HIP runtime error at launch";

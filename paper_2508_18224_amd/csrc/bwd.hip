@@ -442,7 +442,8 @@ hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
   auto* main_kernel = P0.bk == 128 ? k_bwd_main<2> : k_bwd_main<1>;
   {
-    hipError_t e = hipFuncSetAttribute((const void*)main_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBwdBytes);
+    static std::atomic<uint64_t> ready[2];
+    hipError_t e = allow_dynamic_lds((const void*)main_kernel, kLdsBwdBytes, ready[P0.bk == 128]);
     if (e != hipSuccess) return e;
   }
   {

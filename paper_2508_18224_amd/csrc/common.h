@@ -5,6 +5,8 @@
 #include <stdint.h>
 #include <stddef.h>
 
+#include <atomic>
+
 #include "../../include/nsa_sel.h"
 
 namespace nsa {
@@ -101,6 +103,19 @@ struct ProfScope {
   ProfScope(int kid, hipStream_t stream);
   ~ProfScope();
 };
+
+// Raises a kernel's dynamic-LDS limit to `bytes`, once per device (`done` holds one bit per device id), so that
+// later launches - also those recorded into a HIP graph - make no attribute call at all.
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) -------------------------------------
 hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,

@@ -478,7 +478,8 @@ hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
                       hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
   if (P0.bk == 128) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_fwd_main128, hipFuncAttributeMaxDynamicSharedMemorySize, kF128Bytes);
+    static std::atomic<uint64_t> ready;
+    hipError_t e = allow_dynamic_lds((const void*)k_fwd_main128, kF128Bytes, ready);
     if (e != hipSuccess) return e;
   }
   // KV heads are processed heads_per_pass at a time; every pass reuses the same partial buffers (the lists of

@@ -331,13 +331,10 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
   IndexPtrs p = index_ptrs(L, index_ws);
   const size_t lds_hist = (size_t)L.b_cap * 4 + 256 * (size_t)(L.topk + 1) * 4;
   const size_t lds_scat = (size_t)L.b_cap * 12 + 2 * 64 * (size_t)(L.topk + 1) * 4;
-  if (lds_hist > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_hist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_hist);
-    if (e != hipSuccess) return e;
-  }
-  if (lds_scat > 64 * 1024) {
-    hipError_t e =
-        hipFuncSetAttribute((const void*)k_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_scat);
+  if (lds_hist > 64 * 1024 || lds_scat > 64 * 1024) {  // long sequences: block tables beyond the default 64 KB
+    static std::atomic<uint64_t> ready_hist, ready_scat;
+    hipError_t e = allow_dynamic_lds((const void*)k_hist, 160 * 1024, ready_hist);
+    if (e == hipSuccess) e = allow_dynamic_lds((const void*)k_scatter, 160 * 1024, ready_scat);
     if (e != hipSuccess) return e;
   }
   { ProfScope ps(KID_INDEX_PREP, st);

@@ -47,6 +47,10 @@ def test_shape_validation_happens_on_the_host():
     # null pointers are rejected before anything is launched (no GPU is touched)
     assert L.nsa_sel_build_index(ctypes.byref(ok), None, None, None, 0, None) == -1
     assert L.nsa_sel_fwd(ctypes.byref(ok), None, None, None, None, None, 1, None, 0, None, None, None, 0, None) == -1
+    # a misaligned tensor pointer is an argument error, found before any size check or launch
+    vp = ctypes.c_void_p
+    assert L.nsa_sel_fwd(ctypes.byref(ok), vp(4096 + 2), vp(4096), vp(4096), None, None, 0, vp(4096), 1 << 40, vp(4096),
+                         vp(4096), vp(4096), 1 << 40, None) == -1
     assert b"workspace" in L.nsa_sel_strerror(-3)
 
 
