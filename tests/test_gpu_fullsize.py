@@ -24,15 +24,16 @@ def _visible_counts(w):
     tok = np.arange(T)
     seq = np.searchsorted(cu, tok, side="right") - 1
     p = tok - cu[seq]
-    cur = p // 64
+    B = w.block
+    cur = p // B
     length = cu[seq + 1] - cu[seq]
-    nblk = -(-length // 64)
+    nblk = -(-length // B)
     ok = (idx >= 0) & (idx < nblk[:, None, None]) & (idx <= cur[:, None, None])
     k = idx.shape[2]
     for m in range(1, k):                                    # first occurrence only
         ok[:, :, m] &= ~((idx[:, :, :m] == idx[:, :, m:m + 1]) & ok[:, :, :m]).any(axis=2)
-    full = (ok & (idx < cur[:, None, None])).sum(axis=2) * 64
-    diag = (ok & (idx == cur[:, None, None])).any(axis=2) * (p % 64 + 1)[:, None]
+    full = (ok & (idx < cur[:, None, None])).sum(axis=2) * B
+    diag = (ok & (idx == cur[:, None, None])).any(axis=2) * (p % B + 1)[:, None]
     return full + diag
 
 
@@ -47,16 +48,16 @@ def _run_case(name, n_tokens, blocks):
     Q, K, V, dO = (BitsF64(x) for x in (w.q, w.k, w.v, w.do))
     rng = np.random.default_rng(99)
     tokens = sorted({0, 63, 64, T - 1, *[int(x) for x in rng.integers(0, T, n_tokens)]})
-    O_ref, LSE_ref = orc.forward(Q, K, V, w.idx, w.cu_seqlens, tokens=tokens)
-    dQ_ref, _, _ = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, tokens=tokens)
+    O_ref, LSE_ref = orc.forward(Q, K, V, w.idx, w.cu_seqlens, block=w.block, tokens=tokens)
+    dQ_ref, _, _ = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, block=w.block, tokens=tokens)
     sel = torch.tensor(tokens, device="cuda")
     assert_close("O", to_f64(o[sel]), O_ref[tokens], TOL_O)
     assert np.abs(to_f64(lse[sel]) - LSE_ref[tokens]).max() <= TOL_LSE
     assert_close("dQ", to_f64(dq[sel]), dQ_ref[tokens], TOL_GRAD)
     print("  sampled rows ok", flush=True)
-    ref = orc.backward_kv_blocks(Q, K, V, dO, w.idx, w.cu_seqlens, blocks)
+    ref = orc.backward_kv_blocks(Q, K, V, dO, w.idx, w.cu_seqlens, blocks, block=w.block)
     for (j, s, x), (dKb, dVb) in zip(blocks, ref):
-        lo = int(w.cu_seqlens[s]) + x * 64
+        lo = int(w.cu_seqlens[s]) + x * w.block
         hi = lo + dKb.shape[0]
         assert_close(f"dK block {(j, s, x)}", to_f64(dk[lo:hi, j]), dKb, TOL_GRAD)
         assert_close(f"dV block {(j, s, x)}", to_f64(dv[lo:hi, j]), dVb, TOL_GRAD)
@@ -77,6 +78,14 @@ def _run_case(name, n_tokens, blocks):
 
 def test_headline_64k_g4():
     _run_case("headline", 12, [(0, 0, 0), (3, 0, 517), (7, 0, 1023)])
+
+
+def test_llama8b_32k_g4():
+    _run_case("llama8b_32k", 8, [(2, 0, 100), (5, 0, 511)])
+
+
+def test_headline_128_token_blocks():
+    _run_case("headline_b128", 8, [(1, 0, 300), (6, 0, 511)])
 
 
 def test_qwen_g7_64k():
