@@ -2,10 +2,13 @@
 // reduction step; Eq. (2), c = sel).
 //
 // k_fwd_main (B_K = 64): one work unit = (kv head j, KV block i, up to kFwdUnit entries of the block's query list).
-//   The block's K_i and V_i stay in registers for the whole unit (K as the A operand of S^T = K_i Q^T, V^T as
-//   the A operand of O^T = V_i^T P^T), so the inner loop reads no K/V at all: each wavefront walks tiles of 32
-//   query rows (row = (list entry, head of the group), flattened so any g packs densely).  The rows of Q are
-//   gathered coalesced (16 lanes x 16 bytes per row) two tiles ahead and re-laid out into the B-operand layout
+//   The block's K_i stays in registers for the whole unit (the A operand of S^T = K_i Q^T) and V_i^T sits in LDS,
+//   transposed and key-permuted once per unit (the A operand of O^T = V_i^T P^T), so the inner loop reads no K/V
+//   from memory: each wavefront walks tiles of 32 query rows (row = (list entry, head of the group), flattened so
+//   any g packs densely).  The kernel is held to 256 registers per wavefront so that TWO workgroups share a CU:
+//   one's unit prologue, gather waits and softmax overlap the other's MFMA and stores (with V_i^T in registers too
+//   only one workgroup fitted and the kernel ran 30 % slower).  The rows of Q are gathered coalesced (16 lanes x 16
+//   bytes per row) one tile ahead and re-laid out into the B-operand layout
 //   through a wave-private LDS tile; 16 + 16 MFMA 32x32x16 bf16 per tile; the softmax of the 64 scores of a row
 //   runs inside the accumulator layout (a lane holds 32 keys of one query; one cross-lane exchange with
 //   lane ^ 32 completes max and sum).  Because S^T leaves each lane holding keys of ONE query, the probabilities
@@ -39,7 +42,7 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)  // two workgroups per CU: 256 registers per wavefront
 k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
            const int32_t* __restrict__ nu_scan, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
@@ -82,12 +85,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   }
   for (int i = tid; i < ne; i += 256) ent[i] = qent[e0 + i];
   __syncthreads();
-  bf16x8 vf[4][4];
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int sp = 0; sp < 4; ++sp)
-      vf[db][sp] = *reinterpret_cast<const bf16x8*>(&Vt[(32 * db + col) * kVtStride + 16 * sp + 8 * qh]);
+  const bf16_t* vbase = &Vt[col * kVtStride + 8 * qh];  // this lane's V^T fragments: + 32 db rows, + 16 sp keys
 
   const int rows_total = ne * P.g;
   const int n_tiles = (rows_total + 31) >> 5;
@@ -120,7 +118,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
     for (int s = 0; s < 8; ++s)
       qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kTileStride + 16 * s + 8 * qh]);
-    if (tile + 8 < n_tiles) issue_q(tile + 8, qc);  // two of this wave's tiles ahead: rows fly during compute
+    if (tile + 4 < n_tiles) issue_q(tile + 4, qc);  // this wave's next tile: its rows fly during the compute
 
     f32x16 sacc[2];
 #pragma unroll
@@ -176,8 +174,10 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
     for (int sp = 0; sp < 4; ++sp)
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][sp], pf[sp], oacc[db], 0, 0, 0);
+      for (int db = 0; db < 4; ++db) {
+        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vbase + 32 * db * kVtStride + 16 * sp);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], oacc[db], 0, 0, 0);
+      }
 
     // normalised partial rows -> wave tile in LDS -> coalesced 256-byte row stores
     const float inv = valid ? 1.f / l : 0.f;
@@ -204,13 +204,9 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     wave_sync();
   };
 
-  uint4 qa[8], qb[8];
+  uint4 qa[8];
   issue_q(wave, qa);
-  if (wave + 4 < n_tiles) issue_q(wave + 4, qb);
-  for (int tile = wave; tile < n_tiles; tile += 8) {
-    do_tile(tile, qa);
-    if (tile + 4 < n_tiles) do_tile(tile + 4, qb);
-  }
+  for (int tile = wave; tile < n_tiles; tile += 4) do_tile(tile, qa);
 }
 
 // ---- B_K = 128 -----------------------------------------------------------------------------------------------
