@@ -366,6 +366,293 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     }
 }
 
+// ---- B_K = 64: two workgroups per CU -------------------------------------------------------------------------
+// Same mathematics and the same three roles as k_bwd_main above, re-cut so that TWO workgroups share a CU: four
+// wavefronts (256 registers each) and half of the LDS per workgroup.  The two workgroups run out of phase, so one's
+// barriers, gather waits, unit prologue and LDS-bound phases are covered by the other's MFMA work (with one
+// eight-wave workgroup per CU all waves sat in the same phase and LDS, MFMA and VALU time simply added up).
+// Per 64-row tile (w = wave index, rb = w / 2, hf = w % 2):
+//   rows/keys   S^T, dP^T, P, dS for rows 32 rb.. and keys 32 hf..; K_i fragments from LDS, V_i fragments of the
+//               wave's 32 keys held in registers for the whole unit (V_i is used by this role only)
+//   keys/chans  dV_i, dK_i accumulators for keys 32 rb.. and channels 64 hf.. (two 32-channel blocks share every
+//               P^T / dS^T operand read)
+//   rows/chans  dQ^T for rows 32 rb.. and channels 64 hf..; the same wave stages / prefetches that part of the Q and
+//               dO tiles and stores that part of dQ
+// The list's token ids are kept in LDS 1024 entries at a time.
+constexpr int kB2Rows = 64;    // rows per tile
+constexpr int kPStride = 72;   // bf16 per row of the P^T / dS^T tiles: 64 rows + 8 pad (144-byte pitch)
+constexpr int kEntSeg = 1024;  // list entries whose token ids are resident in LDS
+constexpr int kB2K = 0;
+constexpr int kB2Q = kB2K + kBlock * kRowStride * 2;
+constexpr int kB2DO = kB2Q + kB2Rows * kRowStride * 2;
+constexpr int kB2Pt = kB2DO + kB2Rows * kRowStride * 2;
+constexpr int kB2DSt = kB2Pt + kBlock * kPStride * 2;
+constexpr int kB2Ent = kB2DSt + kBlock * kPStride * 2;
+constexpr int kB2Bytes = kB2Ent + kEntSeg * 4;  // 80896
+static_assert(2 * kB2Bytes <= 160 * 1024, "two workgroups of the 64-key backward must fit one CU's LDS");
+static_assert((kEntSeg * 1) % 64 == 0, "segments hold whole tiles for every g");
+
+__global__ void __launch_bounds__(256, 2)
+k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+             const bf16_t* __restrict__ dO, const float2* __restrict__ stats, const int32_t* __restrict__ u_list,
+             const int32_t* __restrict__ u_start, const int32_t* __restrict__ off,
+             const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
+             const int2* __restrict__ qent, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
+             float* __restrict__ dkv_part, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kB2K);
+  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + kB2Q);
+  bf16_t* dOs = reinterpret_cast<bf16_t*>(smem + kB2DO);
+  bf16_t* Pt = reinterpret_cast<bf16_t*>(smem + kB2Pt);
+  bf16_t* dSt = reinterpret_cast<bf16_t*>(smem + kB2DSt);
+  int32_t* ent = reinterpret_cast<int32_t*>(smem + kB2Ent);
+
+  const int ubase = nu_scan[P.j0 * P.b_cap];
+  const int u = ubase + blockIdx.x;
+  if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
+  const int L = u_list[u];
+  const int j = L / P.b_cap;
+  const int gb = L - j * P.b_cap;
+  const int e0 = u_start[u];
+  const int pos0 = off[P.j0 * P.b_cap];
+  const int ne = min(kBwdUnit, off[L + 1] - e0);
+  const int tok0 = blk_tok0[gb], blen = blk_len[gb];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int col = lane & 31, qh = lane >> 5;  // not const: made opaque at the top of the tile loop
+  const int rb = wave >> 1, hf = wave & 1;
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+  {  // K_i -> LDS, row-major; rows past the end of a ragged block are zero
+    const int key = tid >> 2, d0 = (tid & 3) * 32;
+    const bf16_t* src = K + ((size_t)(tok0 + key) * P.hkv + j) * kD + d0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<bf16x8*>(&Ks[key * kRowStride + d0 + 8 * i]) =
+          key < blen ? *reinterpret_cast<const bf16x8*>(src + 8 * i) : zero8;
+  }
+  bf16x8 vf[8];  // V_i fragments of keys 32 hf.. (A operand of dP^T = V_i dO^T)
+  {
+    const int key = 32 * hf + col;
+    const bf16_t* src = V + ((size_t)(tok0 + key) * P.hkv + j) * kD + 8 * qh;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) vf[s] = key < blen ? *reinterpret_cast<const bf16x8*>(src + 16 * s) : zero8;
+  }
+  f32x16 dkacc[2], dvacc[2];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      dkacc[cb][v] = 0.f;
+      dvacc[cb][v] = 0.f;
+    }
+
+  const float c2 = P.scale * 1.4426950408889634f;
+  const size_t hq = P.hq;
+  const int hbase = j * P.g;
+  const int grp = lane >> 4, sl = lane & 15;
+  // this lane's share of a transposing read of four rows x 16 columns (see lds_read_tr), for the two row pitches
+  int tr_lane = ((sl >> 2) + 8 * (grp >> 1)) * kRowStride + 16 * (grp & 1) + 4 * (sl & 3);
+  int tr_lane_p = ((sl >> 2) + 8 * (grp >> 1)) * kPStride + 16 * (grp & 1) + 4 * (sl & 3);
+  // staging layout: 8 lanes x 16 B cover the 64 channels of a row half, 8 rows per access
+  int srow = lane >> 3, schunk = 64 * hf + (lane & 7) * 8;
+  bf16_t* Qmine = Qs + (32 * rb) * kRowStride;
+  bf16_t* dOmine = dOs + (32 * rb) * kRowStride;
+  const int q4 = 8 / P.g, r4 = 8 - q4 * P.g;  // row -> (entry, head) stepping by 8 rows without dividing
+
+  uint4 qc[4], dc[4];
+  float lse2_n, dl_n;
+  int seg0 = 0;  // first list entry whose token id is in `ent`
+  int rows_end = 0;
+  auto issue_rows = [&](int tile0) {
+    int r = tile0 + 32 * rb + srow;
+    int e = r / P.g, hh = r - e * P.g;
+    e -= seg0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (r < rows_end) {
+        const size_t o = ((size_t)ent[e] * hq + hbase + hh) * kD + schunk;
+        qc[i] = *reinterpret_cast<const uint4*>(Q + o);
+        dc[i] = *reinterpret_cast<const uint4*>(dO + o);
+      } else {
+        qc[i] = make_uint4(0, 0, 0, 0);
+        dc[i] = make_uint4(0, 0, 0, 0);
+      }
+      r += 8;
+      e += q4;
+      hh += r4;
+      if (hh >= P.g) {
+        hh -= P.g;
+        e += 1;
+      }
+    }
+    const int rc = tile0 + 32 * rb + col;
+    if (rc < rows_end) {
+      const int ec = rc / P.g;
+      const float2 st = stats[(size_t)ent[ec - seg0] * hq + hbase + (rc - ec * P.g)];  // (LSE in log2 domain, delta)
+      lse2_n = st.x;
+      dl_n = st.y;
+    } else {
+      lse2_n = 0.f;
+      dl_n = 0.f;
+    }
+  };
+
+  for (seg0 = 0; seg0 < ne; seg0 += kEntSeg) {
+    const int seg_n = min(kEntSeg, ne - seg0);
+    __syncthreads();  // the previous segment's ids (and, first time, nothing) are no longer read
+    for (int i = tid; i < seg_n; i += 256) ent[i] = qent[e0 + seg0 + i].x;
+    __syncthreads();  // ids (and K_i on the first pass) visible
+    rows_end = (seg0 + seg_n) * P.g;
+    issue_rows(seg0 * P.g);
+
+    for (int tile0 = seg0 * P.g; tile0 < rows_end; tile0 += kB2Rows) {
+      // keep the lane-derived LDS addresses from being precomputed and held across the loop (register budget)
+      asm volatile("" : "+v"(col), "+v"(qh), "+v"(tr_lane), "+v"(tr_lane_p), "+v"(srow), "+v"(schunk));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        *reinterpret_cast<uint4*>(&Qmine[(8 * i + srow) * kRowStride + schunk]) = qc[i];
+        *reinterpret_cast<uint4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
+      }
+      const float lse2 = lse2_n, dl = dl_n;
+      const bool more = tile0 + kB2Rows < rows_end;
+      if (more) issue_rows(tile0 + kB2Rows);  // the next tile's rows fly while this one computes
+      const int r = tile0 + 32 * rb + col;
+      const bool valid = r < rows_end;
+      const int t = valid ? ent[r / P.g - seg0] : -1;
+      int lim = P.causal ? min(blen, t - tok0 + 1) : blen;  // keys [0, lim) of the block are visible to this row
+      if (!valid) lim = 0;
+      __syncthreads();  // Q / dO tile staged by all waves
+
+      {  // role rows/keys
+        f32x16 sacc, dpacc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          sacc[v] = 0.f;
+          dpacc[v] = 0.f;
+        }
+        const bf16_t* qrow = Qmine + col * kRowStride + 8 * qh;
+        const bf16_t* drow = dOmine + col * kRowStride + 8 * qh;
+        const bf16_t* krow = Ks + (32 * hf + col) * kRowStride + 8 * qh;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
+          const bf16x8 dof = *reinterpret_cast<const bf16x8*>(drow + 16 * s);
+          const bf16x8 kfa = *reinterpret_cast<const bf16x8*>(krow + 16 * s);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa, qf, sacc, 0, 0, 0);
+          dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], dof, dpacc, 0, 0, 0);
+        }
+        bf16_t* pdst = Pt + 32 * rb + col;
+        bf16_t* sdst = dSt + 32 * rb + col;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = 32 * hf + 8 * (v >> 2) + 4 * qh + (v & 3);
+          const float p = key < lim ? __builtin_amdgcn_exp2f(sacc[v] * c2 - lse2) : 0.f;
+          const float ds = p * (dpacc[v] - dl) * P.scale;
+          pdst[key * kPStride] = (bf16_t)p;
+          sdst[key * kPStride] = (bf16_t)ds;
+        }
+      }
+      __syncthreads();  // P^T, dS^T complete
+      {  // role keys/chans: dV_i += P^T dO, dK_i += dS^T Q for keys 32 rb.., channels 64 hf + 32 cb..
+        int tr_row = tr_lane + 64 * hf;
+        asm volatile("" : "+v"(tr_row));
+        const bf16_t* parow = Pt + (32 * rb + col) * kPStride + 8 * qh;
+        const bf16_t* sarow = dSt + (32 * rb + col) * kPStride + 8 * qh;
+#pragma unroll
+        for (int qs = 0; qs < 4; ++qs) {
+          const bf16x8 pa = *reinterpret_cast<const bf16x8*>(parow + 16 * qs);
+          const bf16x8 sa = *reinterpret_cast<const bf16x8*>(sarow + 16 * qs);
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) {
+            const bf16x4 d0 = lds_read_tr(&dOs[16 * qs * kRowStride + tr_row + 32 * cb]);
+            const bf16x4 d1 = lds_read_tr(&dOs[(16 * qs + 4) * kRowStride + tr_row + 32 * cb]);
+            const bf16x4 q0 = lds_read_tr(&Qs[16 * qs * kRowStride + tr_row + 32 * cb]);
+            const bf16x4 q1 = lds_read_tr(&Qs[(16 * qs + 4) * kRowStride + tr_row + 32 * cb]);
+            const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
+            dvacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc[cb], 0, 0, 0);
+            dkacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qb, dkacc[cb], 0, 0, 0);
+          }
+        }
+      }
+      f32x16 dqacc[2];
+      {  // role rows/chans: dQ^T[64 hf.., 32 rb..] = K_i^T dS^T over the 64 keys
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
+        int tr_key = tr_lane + 64 * hf;
+        int tr_ds = tr_lane_p + 32 * rb;
+        asm volatile("" : "+v"(tr_key), "+v"(tr_ds));
+#pragma unroll
+        for (int sp = 0; sp < 4; ++sp) {
+          const bf16x4 b0 = lds_read_tr(&dSt[16 * sp * kPStride + tr_ds]);
+          const bf16x4 b1 = lds_read_tr(&dSt[(16 * sp + 4) * kPStride + tr_ds]);
+          const bf16x8 dsb = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+          for (int db = 0; db < 2; ++db) {
+            const bf16x4 a0 = lds_read_tr(&Ks[16 * sp * kRowStride + tr_key + 32 * db]);
+            const bf16x4 a1 = lds_read_tr(&Ks[(16 * sp + 4) * kRowStride + tr_key + 32 * db]);
+            const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+            dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsb, dqacc[db], 0, 0, 0);
+          }
+        }
+      }
+      __syncthreads();  // every wave is done reading the Q / dO / P^T / dS^T tiles
+      // dQ rows (32 rows x 64 channels) -> the part of the Q tile this wave staged -> 128-byte row segments
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          uint2 w;
+          w.x = pack_bf16x2(dqacc[db][4 * a + 0], dqacc[db][4 * a + 1]);
+          w.y = pack_bf16x2(dqacc[db][4 * a + 2], dqacc[db][4 * a + 3]);
+          *reinterpret_cast<uint2*>(&Qmine[col * kRowStride + 64 * hf + 32 * db + 8 * a + 4 * qh]) = w;
+        }
+      wave_sync_bwd();
+      const size_t prow0 = (size_t)(e0 - pos0) * P.g + (size_t)(tile0 + 32 * rb);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = 8 * i + srow;
+        if (tile0 + 32 * rb + row < rows_end)
+          store_streaming(dqpart + (prow0 + row) * kD + schunk,
+                          *reinterpret_cast<const uint4*>(&Qmine[row * kRowStride + schunk]));
+      }
+      wave_sync_bwd();
+    }
+  }
+
+  if (nu_scan[L + 1] - nu_scan[L] == 1) {
+    // the whole list fitted this unit: dK_i, dV_i are final, write them as bf16 (keys of a ragged tail excluded)
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      bf16_t* outk = dK + ((size_t)tok0 * P.hkv + j) * kD + 64 * hf + 32 * cb + col;
+      bf16_t* outv = dV + ((size_t)tok0 * P.hkv + j) * kD + 64 * hf + 32 * cb + col;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = 32 * rb + 8 * (v >> 2) + 4 * qh + (v & 3);
+        if (key < blen) {
+          outk[(size_t)key * P.hkv * kD] = (bf16_t)dkacc[cb][v];
+          outv[(size_t)key * P.hkv * kD] = (bf16_t)dvacc[cb][v];
+        }
+      }
+    }
+    return;
+  }
+  // unit partial: [u][0 = dK, 1 = dV][key][d] fp32, summed by k_bwd_dkv_reduce in unit order
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    float* outk = dkv_part + (size_t)(u - ubase) * 2 * kBlock * kD + 64 * hf + 32 * cb + col;
+    float* outv = outk + kBlock * kD;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = 32 * rb + 8 * (v >> 2) + 4 * qh + (v & 3);
+      outk[key * kD] = dkacc[cb][v];
+      outv[key * kD] = dvacc[cb][v];
+    }
+  }
+}
+
 __global__ void __launch_bounds__(256)
 k_bwd_dq_reduce(Problem P, const bf16_t* __restrict__ dqpart, const uint32_t* __restrict__ vmask,
                 const int32_t* __restrict__ slotpos, const int32_t* __restrict__ off, bf16_t* __restrict__ dQ) {
@@ -440,10 +727,14 @@ hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
                       const void* V, const void* O, const float* LSE, const void* dO, const void* index_ws,
                       void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
-  auto* main_kernel = P0.bk == 128 ? k_bwd_main<2> : k_bwd_main<1>;
+  // 64-token blocks: four-wave kernel, two workgroups per CU; 128-token blocks: eight-wave kernel, two key halves
+  const bool b128 = P0.bk == 128;
+  auto* main_kernel = b128 ? k_bwd_main<2> : k_bwd_main64;
+  const int main_threads = b128 ? 512 : 256;
+  const int main_lds = b128 ? kLdsBwdBytes : kB2Bytes;
   {
     static std::atomic<uint64_t> ready[2];
-    hipError_t e = allow_dynamic_lds((const void*)main_kernel, kLdsBwdBytes, ready[P0.bk == 128]);
+    hipError_t e = allow_dynamic_lds((const void*)main_kernel, main_lds, ready[b128]);
     if (e != hipSuccess) return e;
   }
   {
@@ -460,7 +751,7 @@ hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
     const unsigned units_max = (unsigned)bwd_units_bound(P.nj, P.b_cap, P.T, P.topk);
     const int64_t rows = (int64_t)P.T * P.nj * P.g;
     { ProfScope ps(KID_BWD_MAIN, st);
-    hipLaunchKernelGGL(main_kernel, dim3(units_max), dim3(512), kLdsBwdBytes, st, P, (const bf16_t*)Q,
+    hipLaunchKernelGGL(main_kernel, dim3(units_max), dim3(main_threads), main_lds, st, P, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, (const float2*)delta, p.b_list,
                        p.b_start, p.off, p.blk_tok0, p.blk_len, p.qent, p.b_nu, (bf16_t*)dqpart, dkv_part,
                        (bf16_t*)dK, (bf16_t*)dV); }
