@@ -78,6 +78,7 @@ static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
   P.causal = s->causal ? 1 : 0;
   P.b_cap = L.b_cap;
   P.bk = L.bk;
+  P.g_magic = (uint32_t)(((uint64_t)1 << 32) / (uint64_t)P.g + 1);  // wraps to 1 for g = 1, where it is unused
   P.j0 = 0;
   P.nj = s->hkv;
   P.scale = s->scale > 0.f ? s->scale : 0.08838834764831845f;  // 1/sqrt(128)

@@ -162,42 +162,25 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   int srow = lane >> 3, schunk = 64 * half + (lane & 7) * 8;
   bf16_t* Qmine = Qs + (32 * rb) * kRowStride;
   bf16_t* dOmine = dOs + (32 * rb) * kRowStride;
-  const int q4 = 8 / P.g, r4 = 8 - q4 * P.g;  // row -> (entry, head) stepping by 8 rows without dividing
 
-  uint4 qc[4], dc[4];
+  u32x4 qc[4], dc[4];
   float lse2_n, dl_n;
   auto issue_rows = [&](int tile0) {
-    int r = tile0 + 32 * rb + srow;
-    int e = r / P.g, hh = r - e * P.g;
+    // rows past the end of the list re-read its last row: their P and dS are forced to zero (lim = 0) and their
+    // dQ is never stored, so no branch and no zero fill is needed
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (r < rows_total) {
-        const size_t o = ((size_t)ent[e] * hq + hbase + hh) * kD + schunk;
-        qc[i] = *reinterpret_cast<const uint4*>(Q + o);
-        dc[i] = *reinterpret_cast<const uint4*>(dO + o);
-      } else {
-        qc[i] = make_uint4(0, 0, 0, 0);
-        dc[i] = make_uint4(0, 0, 0, 0);
-      }
-      r += 8;
-      e += q4;
-      hh += r4;
-      if (hh >= P.g) {
-        hh -= P.g;
-        e += 1;
-      }
+      const int r = min(tile0 + 32 * rb + 8 * i + srow, rows_total - 1);
+      const int e = div_g(r, P.g, P.g_magic);
+      const size_t o = ((size_t)ent[e] * hq + hbase + (r - e * P.g)) * kD + schunk;
+      qc[i] = *reinterpret_cast<const u32x4*>(Q + o);
+      dc[i] = *reinterpret_cast<const u32x4*>(dO + o);
     }
-    const int rc = tile0 + 32 * rb + col;
-    if (rc < rows_total) {
-      const int ec = rc / P.g;
-      const size_t grow = (size_t)ent[ec] * hq + hbase + (rc - ec * P.g);
-      const float2 st = stats[grow];  // (LSE in the log2 domain, delta)
-      lse2_n = st.x;
-      dl_n = st.y;
-    } else {
-      lse2_n = 0.f;
-      dl_n = 0.f;
-    }
+    const int rc = min(tile0 + 32 * rb + col, rows_total - 1);
+    const int ec = div_g(rc, P.g, P.g_magic);
+    const float2 st = stats[(size_t)ent[ec] * hq + hbase + (rc - ec * P.g)];  // (LSE in the log2 domain, delta)
+    lse2_n = st.x;
+    dl_n = st.y;
   };
   issue_rows(0);
 
@@ -209,15 +192,15 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     // stage this wave's part of the tile; then let the next tile's rows fly while this one computes
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<uint4*>(&Qmine[(8 * i + srow) * kRowStride + schunk]) = qc[i];
-      *reinterpret_cast<uint4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
+      *reinterpret_cast<u32x4*>(&Qmine[(8 * i + srow) * kRowStride + schunk]) = qc[i];
+      *reinterpret_cast<u32x4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
     }
     const float lse2 = lse2_n, dl = dl_n;
     const bool more = tile0 + kTileRows < rows_total;
     if (NH == 1 && more) issue_rows(tile0 + kTileRows);
     const int r = tile0 + 32 * rb + col;
     const bool valid = r < rows_total;
-    const int t = valid ? ent[r / P.g] : -1;
+    const int t = valid ? ent[div_g(r, P.g, P.g_magic)] : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;  // keys [0, lim) of the block are visible to this row
     if (!valid) lim = 0;
     f32x16 dqacc[2];
@@ -457,44 +440,27 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
   int srow = lane >> 3, schunk = 64 * hf + (lane & 7) * 8;
   bf16_t* Qmine = Qs + (32 * rb) * kRowStride;
   bf16_t* dOmine = dOs + (32 * rb) * kRowStride;
-  const int q4 = 8 / P.g, r4 = 8 - q4 * P.g;  // row -> (entry, head) stepping by 8 rows without dividing
 
-  uint4 qc[4], dc[4];
+  u32x4 qc[4], dc[4];
   float lse2_n, dl_n;
   int seg0 = 0;  // first list entry whose token id is in `ent`
   int rows_end = 0;
   auto issue_rows = [&](int tile0) {
-    int r = tile0 + 32 * rb + srow;
-    int e = r / P.g, hh = r - e * P.g;
-    e -= seg0;
+    // rows past the end of the list re-read its last row: their P and dS are forced to zero (lim = 0) and their
+    // dQ is never stored, so no branch and no zero fill is needed
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (r < rows_end) {
-        const size_t o = ((size_t)ent[e] * hq + hbase + hh) * kD + schunk;
-        qc[i] = *reinterpret_cast<const uint4*>(Q + o);
-        dc[i] = *reinterpret_cast<const uint4*>(dO + o);
-      } else {
-        qc[i] = make_uint4(0, 0, 0, 0);
-        dc[i] = make_uint4(0, 0, 0, 0);
-      }
-      r += 8;
-      e += q4;
-      hh += r4;
-      if (hh >= P.g) {
-        hh -= P.g;
-        e += 1;
-      }
+      const int r = min(tile0 + 32 * rb + 8 * i + srow, rows_end - 1);
+      const int e = div_g(r, P.g, P.g_magic);
+      const size_t o = ((size_t)ent[e - seg0] * hq + hbase + (r - e * P.g)) * kD + schunk;
+      qc[i] = *reinterpret_cast<const u32x4*>(Q + o);
+      dc[i] = *reinterpret_cast<const u32x4*>(dO + o);
     }
-    const int rc = tile0 + 32 * rb + col;
-    if (rc < rows_end) {
-      const int ec = rc / P.g;
-      const float2 st = stats[(size_t)ent[ec - seg0] * hq + hbase + (rc - ec * P.g)];  // (LSE in log2 domain, delta)
-      lse2_n = st.x;
-      dl_n = st.y;
-    } else {
-      lse2_n = 0.f;
-      dl_n = 0.f;
-    }
+    const int rc = min(tile0 + 32 * rb + col, rows_end - 1);
+    const int ec = div_g(rc, P.g, P.g_magic);
+    const float2 st = stats[(size_t)ent[ec - seg0] * hq + hbase + (rc - ec * P.g)];  // (LSE in log2 domain, delta)
+    lse2_n = st.x;
+    dl_n = st.y;
   };
 
   for (seg0 = 0; seg0 < ne; seg0 += kEntSeg) {
@@ -510,15 +476,15 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
       asm volatile("" : "+v"(col), "+v"(qh), "+v"(tr_lane), "+v"(tr_lane_p), "+v"(srow), "+v"(schunk));
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<uint4*>(&Qmine[(8 * i + srow) * kRowStride + schunk]) = qc[i];
-        *reinterpret_cast<uint4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
+        *reinterpret_cast<u32x4*>(&Qmine[(8 * i + srow) * kRowStride + schunk]) = qc[i];
+        *reinterpret_cast<u32x4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
       }
       const float lse2 = lse2_n, dl = dl_n;
       const bool more = tile0 + kB2Rows < rows_end;
       if (more) issue_rows(tile0 + kB2Rows);  // the next tile's rows fly while this one computes
       const int r = tile0 + 32 * rb + col;
       const bool valid = r < rows_end;
-      const int t = valid ? ent[r / P.g - seg0] : -1;
+      const int t = valid ? ent[div_g(r, P.g, P.g_magic) - seg0] : -1;
       int lim = P.causal ? min(blen, t - tok0 + 1) : blen;  // keys [0, lim) of the block are visible to this row
       if (!valid) lim = 0;
       __syncthreads();  // Q / dO tile staged by all waves

@@ -77,6 +77,7 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
 // Problem description handed to the attention kernels.
 struct Problem {
   int32_t T, nseq, hq, hkv, g, topk, causal, b_cap, bk;
+  uint32_t g_magic;  // floor(2^32 / g) + 1: row / g as one multiply-high (see div_g); unused when g == 1
   int32_t j0, nj;  // KV heads [j0, j0 + nj) handled by this launch (all of them unless the workspace is capped)
   float scale;
 };
@@ -135,6 +136,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // 16 bytes in flight as a plain vector (rows being gathered)
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
@@ -144,13 +146,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
+// r / g for 0 <= r < 2^20 and g in [1, 8] without an integer division: the error of the rounded-up reciprocal,
+// r (magic - 2^32 / g) < r, stays far below 2^32 / g, so the high word of the product is the exact quotient.
+__device__ __forceinline__ int div_g(int r, int g, uint32_t g_magic) {
+  return g == 1 ? r : (int)(((uint64_t)(uint32_t)r * g_magic) >> 32);
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 
 // 16-byte store with the non-temporal hint: partial rows are written once and read once much later, so they
 // should not displace the gathered Q / dO rows from the caches.
 __device__ __forceinline__ void store_streaming(bf16_t* dst, uint4 v) {
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   u32x4 x = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(x, reinterpret_cast<u32x4*>(dst));
 }

@@ -96,23 +96,20 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int hbase = j * P.g;
 
   // gather the 32 rows of Q of a tile in coalesced form (a row = 16 lanes x 16 bytes, 4 rows per access)
-  auto issue_q = [&](int tile, uint4 (&qc)[8]) {
+  auto issue_q = [&](int tile, u32x4 (&qc)[8]) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int r = tile * 32 + 4 * i + crow;
-      if (r < rows_total) {
-        const int e = r / P.g;
-        qc[i] = *reinterpret_cast<const uint4*>(Q + ((size_t)ent[e].x * hq + hbase + (r - e * P.g)) * kD + cchunk);
-      } else {
-        qc[i] = make_uint4(0, 0, 0, 0);
-      }
+      // rows past the end of the list re-read the last row: they are masked out below and never stored
+      const int r = min(tile * 32 + 4 * i + crow, rows_total - 1);
+      const int e = div_g(r, P.g, P.g_magic);
+      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)ent[e].x * hq + hbase + (r - e * P.g)) * kD + cchunk);
     }
   };
 
-  auto do_tile = [&](int tile, uint4 (&qc)[8]) {
+  auto do_tile = [&](int tile, u32x4 (&qc)[8]) {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<uint4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
+      *reinterpret_cast<u32x4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
     wave_sync();
     bf16x8 qf[8];
 #pragma unroll
@@ -134,7 +131,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     // keys [0, lim) of the block are visible to this row
     const int r = tile * 32 + col;
     const bool valid = r < rows_total;
-    const int t = valid ? ent[r / P.g].x : -1;
+    const int t = valid ? ent[div_g(r, P.g, P.g_magic)].x : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
     float m = -INFINITY;
@@ -204,7 +201,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     wave_sync();
   };
 
-  uint4 qa[8];
+  u32x4 qa[8];
   issue_q(wave, qa);
   for (int tile = wave; tile < n_tiles; tile += 4) do_tile(tile, qa);
 }
@@ -284,17 +281,14 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   const int grp = lane >> 4, sl = lane & 15;
   int tr_v = ((sl >> 2) + 4 * (grp >> 1)) * kPitch128 + 16 * (grp & 1) + 4 * (sl & 3);
 
-  uint4 qc[8];
+  u32x4 qc[8];
   auto issue_q = [&](int tile) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int r = tile * 32 + 4 * i + crow;
-      if (r < rows_total) {
-        const int e = r / P.g;
-        qc[i] = *reinterpret_cast<const uint4*>(Q + ((size_t)ent[e].x * hq + hbase + (r - e * P.g)) * kD + cchunk);
-      } else {
-        qc[i] = make_uint4(0, 0, 0, 0);
-      }
+      // rows past the end of the list re-read the last row: they are masked out below and never stored
+      const int r = min(tile * 32 + 4 * i + crow, rows_total - 1);
+      const int e = div_g(r, P.g, P.g_magic);
+      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)ent[e].x * hq + hbase + (r - e * P.g)) * kD + cchunk);
     }
   };
   issue_q(wave);
@@ -304,7 +298,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
     asm volatile("" : "+v"(col), "+v"(qh), "+v"(crow), "+v"(cchunk), "+v"(tr_v));
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<uint4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
+      *reinterpret_cast<u32x4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
     wave_sync();
     bf16x8 qf[8];
 #pragma unroll
@@ -327,7 +321,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
 
     const int r = tile * 32 + col;
     const bool valid = r < rows_total;
-    const int t = valid ? ent[r / P.g].x : -1;
+    const int t = valid ? ent[div_g(r, P.g, P.g_magic)].x : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
     float m = -INFINITY;
