@@ -241,11 +241,12 @@ k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         }
         bf16_t* pdst = Pt + 32 * rb + col;
         bf16_t* sdst = dSt + 32 * rb + col;
+        const float dls = dl * P.scale;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = 32 * half + 8 * (v >> 2) + 4 * qh + (v & 3);
-          const float p = 64 * hf + key < lim ? __builtin_amdgcn_exp2f(sacc[v] * c2 - lse2) : 0.f;
-          const float ds = p * (dpacc[v] - dl) * P.scale;
+          const float p = 64 * hf + key < lim ? __builtin_amdgcn_exp2f(fmaf(sacc[v], c2, -lse2)) : 0.f;
+          const float ds = p * fmaf(dpacc[v], P.scale, -dls);  // P (dP - delta) scale
           pdst[key * kRowStride] = (bf16_t)p;
           sdst[key * kRowStride] = (bf16_t)ds;
         }
@@ -509,11 +510,12 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
         }
         bf16_t* pdst = Pt + 32 * rb + col;
         bf16_t* sdst = dSt + 32 * rb + col;
+        const float dls = dl * P.scale;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = 32 * hf + 8 * (v >> 2) + 4 * qh + (v & 3);
-          const float p = key < lim ? __builtin_amdgcn_exp2f(sacc[v] * c2 - lse2) : 0.f;
-          const float ds = p * (dpacc[v] - dl) * P.scale;
+          const float p = key < lim ? __builtin_amdgcn_exp2f(fmaf(sacc[v], c2, -lse2)) : 0.f;
+          const float ds = p * fmaf(dpacc[v], P.scale, -dls);  // P (dP - delta) scale
           pdst[key * kPStride] = (bf16_t)p;
           sdst[key * kPStride] = (bf16_t)ds;
         }

@@ -134,24 +134,34 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     const int t = valid ? ent[div_g(r, P.g, P.g_magic)].x : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
+    // Only tiles with a row in the block itself (causal diagonal) or a ragged block end need the key mask; the
+    // test is wave-uniform.  The maximum is taken over the raw scores (the scale is positive) and the scale is
+    // folded into the exponent: p = 2^(s c2 - m c2).
     float m = -INFINITY;
+    if (__builtin_amdgcn_ballot_w64(lim < kBlock) == 0) {
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+      for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
-        const float x = key < lim ? sacc[mb][v] * c2 : -INFINITY;
-        sacc[mb][v] = x;
-        m = fmaxf(m, x);
-      }
+        for (int v = 0; v < 16; ++v) m = fmaxf(m, sacc[mb][v]);
+    } else {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
+          const float x = key < lim ? sacc[mb][v] : -INFINITY;
+          sacc[mb][v] = x;
+          m = fmaxf(m, x);
+        }
+    }
     m = fmaxf(m, __shfl_xor(m, 32));
-    const float msafe = (m == -INFINITY) ? 0.f : m;
+    const float mc = (m == -INFINITY) ? 0.f : m * c2;  // row maximum in the log2 domain
     float l = 0.f;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(sacc[mb][v] - msafe);
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][v], c2, -mc));
         sacc[mb][v] = p;
         l += p;
       }
@@ -197,7 +207,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         store_streaming(opart + (prow0 + row) * kD + cchunk,
                         *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]));
     }
-    if (valid && qh == 0) lse_part[prow0 + col] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    if (valid && qh == 0) lse_part[prow0 + col] = (mc + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
     wave_sync();
   };
 
@@ -324,25 +334,34 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
     const int t = valid ? ent[div_g(r, P.g, P.g_magic)].x : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
+    // key mask only where a row lies in the block itself or the block is ragged (wave-uniform test); maximum over
+    // the raw scores, scale folded into the exponent
     float m = -INFINITY;
+    if (__builtin_amdgcn_ballot_w64(lim < 2 * kBlock) == 0) {
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+      for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
-        const float x = key < lim ? sacc[mb][v] * c2 : -INFINITY;
-        sacc[mb][v] = x;
-        m = fmaxf(m, x);
-      }
+        for (int v = 0; v < 16; ++v) m = fmaxf(m, sacc[mb][v]);
+    } else {
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
+          const float x = key < lim ? sacc[mb][v] : -INFINITY;
+          sacc[mb][v] = x;
+          m = fmaxf(m, x);
+        }
+    }
     m = fmaxf(m, __shfl_xor(m, 32));
-    const float msafe = (m == -INFINITY) ? 0.f : m;
+    const float mc = (m == -INFINITY) ? 0.f : m * c2;  // row maximum in the log2 domain
     float l = 0.f;
     bf16x8 pf[8];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(sacc[mb][v] - msafe);
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][v], c2, -mc));
         l += p;
         pf[2 * mb + (v >> 3)][v & 7] = (bf16_t)p;
       }
@@ -384,7 +403,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
         store_streaming(opart + (prow0 + row) * kD + cchunk,
                         *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]));
     }
-    if (valid && qh == 0) lse_part[prow0 + col] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    if (valid && qh == 0) lse_part[prow0 + col] = (mc + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
     wave_sync();
   }
 }
