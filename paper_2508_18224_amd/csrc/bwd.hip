@@ -5,13 +5,16 @@
 //
 //   k_bwd_delta       delta[t,h] = <dO[t,h], O[t,h]>, stored next to LSE[t,h] log2(e) as one 8-byte pair so that the
 //                     main kernel fetches both row statistics with one gather
-//   k_bwd_main<NH>    one work unit = (kv head j, KV block i, up to kBwdUnit list entries); eight wavefronts share
-//                     tiles of 128 gathered rows and take three roles per tile (see the comment above the kernel):
-//                     S^T = K_i Q^T, dP^T = V_i dO^T, P = exp(S - LSE), dS = P (dP - delta) scale; then
+//   k_bwd_main64      B_K = 64.  One work unit = (kv head j, KV block i, up to kBwdUnit list entries); four wavefronts
+//                     and half of a CU's LDS, so two workgroups share a CU and cover each other's barriers and waits.
+//                     The waves share tiles of 64 gathered rows and take three roles per tile (see the comment above
+//                     the kernel): S^T = K_i Q^T, dP^T = V_i dO^T, P = exp(S - LSE), dS = P (dP - delta) scale; then
 //                     dV_i += P^T dO and dK_i += dS^T Q (accumulators in registers for the whole unit) and
-//                     dQ^T = K_i^T dS^T.  All operands are row-major tiles in LDS; "lane = column" operands are
-//                     LDS transpose reads.  Partial dQ rows go to the compact buffer at the rows' list position;
-//                     the unit's dK_i, dV_i go out as bf16 (list fitted the unit) or to a per-unit fp32 buffer.
+//                     dQ^T = K_i^T dS^T.  Operands are row-major tiles in LDS; "lane = column" operands are LDS
+//                     transpose reads.  Partial dQ rows go to the compact buffer at the rows' list position; the
+//                     unit's dK_i, dV_i go out as bf16 (list fitted the unit) or to a per-unit fp32 buffer.
+//   k_bwd_main<2>     B_K = 128.  The same roles with eight wavefronts and all of the LDS (the fp32 dK/dV accumulators
+//                     of a 128-key block need eight waves' registers); tiles of 128 rows, two 64-key halves per tile.
 //   k_bwd_dq_reduce   dQ[t,h] = sum over kept slots of the partial rows
 //   k_bwd_dkv_reduce  dK_i, dV_i = sum over the list's units in unit order (fixed order: bit-reproducible); a list
 //                     that fitted one unit was already written by that unit, a list with no entry gets zeros
@@ -83,6 +86,7 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
 // one half at a time (re-staged from registers that were loaded one half ahead; the block stays L2-resident), the
 // Q and dO tiles are gathered once per tile, dQ^T accumulates over both halves, and each half has its own dK/dV
 // accumulators.
+// Only NH = 2 is launched (64-key blocks use k_bwd_main64 below); NH = 1 stays a valid instantiation of this cut.
 template <int NH>
 __global__ void __launch_bounds__(512)
 k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
