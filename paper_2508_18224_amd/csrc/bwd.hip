@@ -5,16 +5,15 @@
 //
 //   k_bwd_delta       delta[t,h] = <dO[t,h], O[t,h]>, stored next to LSE[t,h] log2(e) as one 8-byte pair so that the
 //                     main kernel fetches both row statistics with one gather
-//   k_bwd_main64      B_K = 64.  One work unit = (kv head j, KV block i, up to kBwdUnit list entries); four wavefronts
-//                     and half of a CU's LDS, so two workgroups share a CU and cover each other's barriers and waits.
-//                     The waves share tiles of 64 gathered rows and take three roles per tile (see the comment above
-//                     the kernel): S^T = K_i Q^T, dP^T = V_i dO^T, P = exp(S - LSE), dS = P (dP - delta) scale; then
+//   k_bwd_tiled<NKB>  one work unit = (kv head j, KV block i, up to kBwdUnit list entries); NKB = B_K / 32.  With
+//                     B_K = 64: four wavefronts and half of a CU's LDS, so two workgroups share a CU and cover each
+//                     other's barriers and waits; with B_K = 128: eight wavefronts, one workgroup per CU.  The waves
+//                     share tiles of 64 gathered rows and take three roles per tile (see the comment above the
+//                     kernel): S^T = K_i Q^T, dP^T = V_i dO^T, P = exp(S - LSE), dS = P (dP - delta) scale; then
 //                     dV_i += P^T dO and dK_i += dS^T Q (accumulators in registers for the whole unit) and
 //                     dQ^T = K_i^T dS^T.  Operands are row-major tiles in LDS; "lane = column" operands are LDS
 //                     transpose reads.  Partial dQ rows go to the compact buffer at the rows' list position; the
 //                     unit's dK_i, dV_i go out as bf16 (list fitted the unit) or to a per-unit fp32 buffer.
-//   k_bwd_main<2>     B_K = 128.  The same roles with eight wavefronts and all of the LDS (the fp32 dK/dV accumulators
-//                     of a 128-key block need eight waves' registers); tiles of 128 rows, two 64-key halves per tile.
 //   k_bwd_dq_reduce   dQ[t,h] = sum over kept slots of the partial rows
 //   k_bwd_dkv_reduce  dK_i, dV_i = sum over the list's units in unit order (fixed order: bit-reproducible); a list
 //                     that fitted one unit was already written by that unit, a list with no entry gets zeros
@@ -22,22 +21,11 @@
 
 namespace nsa {
 
-// bf16 per row of the K / V / Q / dO / P^T / dS^T tiles in LDS: 128 + 24 pad.  A 304-byte row pitch puts the rows
+// bf16 per row of the K / Q / dO tiles in LDS: 128 + 24 pad.  A 304-byte row pitch puts the rows
 // of both access shapes used here (16-byte operand reads down a column of rows, and the 4-row x 32-byte footprint
 // of a transposing read) on disjoint banks; with 128 + 8 the transposing reads conflicted two-way (measured:
 // 45 % of LDS cycles were bank conflicts, 8 % kernel time).
 constexpr int kRowStride = 152;
-constexpr int kTileRows = 128;
-
-constexpr int kLdsK = 0;
-constexpr int kLdsV = kLdsK + kBlock * kRowStride * 2;
-constexpr int kLdsQ = kLdsV + kBlock * kRowStride * 2;
-constexpr int kLdsDO = kLdsQ + kTileRows * kRowStride * 2;
-constexpr int kLdsPt = kLdsDO + kTileRows * kRowStride * 2;
-constexpr int kLdsDSt = kLdsPt + kBlock * kRowStride * 2;
-constexpr int kLdsEnt = kLdsDSt + kBlock * kRowStride * 2;
-constexpr int kLdsBwdBytes = kLdsEnt + kBwdUnit * 4;  // 163840: all of the CU's 160 KB
-static_assert(kLdsBwdBytes <= 160 * 1024, "backward tile set must fit the CU's LDS");
 
 // ds_read_b64_tr_b16: every lane passes the address of 8 bytes (four 16-bit elements); within each group of
 // 16 lanes, lane i receives element (i % 4) of the 8 bytes addressed by lanes 4e + i / 4, for e = 0..3.  With
@@ -76,324 +64,63 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
   if (row < rows && sub == 0) stats[row] = make_float2(LSE[row] * 1.4426950408889634f, acc);
 }
 
-// 512 threads = 8 wavefronts = two per SIMD, so one wave's LDS and memory waits are covered by the other's issue.
-// Per 128-row tile the waves take three roles in turn (w = wave index):
-//   rows/keys   (rb = w / 2, mb = w % 2): S^T, dP^T, P, dS for rows 32 rb.. and keys 32 mb..; writes P^T, dS^T
-//   keys/chans  (mb = w / 4, ds = w % 4): dV_i, dK_i accumulators for keys 32 mb.. and channels 32 ds..
-//   rows/chans  (rb = w / 2, dh = w % 2): dQ^T for rows 32 rb.. and channels 64 dh..; also stages / prefetches
-//                                         exactly that part of the Q and dO tiles and stores that part of dQ
-// NH = B_K / 64.  With B_K = 128 the block is worked through as two 64-key halves per tile: the K/V tiles in LDS hold
-// one half at a time (re-staged from registers that were loaded one half ahead; the block stays L2-resident), the
-// Q and dO tiles are gathered once per tile, dQ^T accumulates over both halves, and each half has its own dK/dV
-// accumulators.
-// Only NH = 2 is launched (64-key blocks use k_bwd_main64 below); NH = 1 stays a valid instantiation of this cut.
-template <int NH>
-__global__ void __launch_bounds__(512)
-k_bwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-           const bf16_t* __restrict__ dO, const float2* __restrict__ stats,
-           const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
-           const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
-           const int2* __restrict__ qent, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
-           float* __restrict__ dkv_part, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kLdsK);
-  bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kLdsV);
-  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + kLdsQ);
-  bf16_t* dOs = reinterpret_cast<bf16_t*>(smem + kLdsDO);
-  bf16_t* Pt = reinterpret_cast<bf16_t*>(smem + kLdsPt);
-  bf16_t* dSt = reinterpret_cast<bf16_t*>(smem + kLdsDSt);
-  int32_t* ent = reinterpret_cast<int32_t*>(smem + kLdsEnt);
-
-  // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
-  const int ubase = nu_scan[P.j0 * P.b_cap];
-  const int u = ubase + blockIdx.x;
-  if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
-  const int L = u_list[u];
-  const int j = L / P.b_cap;
-  const int gb = L - j * P.b_cap;
-  const int e0 = u_start[u];
-  const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
-  const int ne = min(kBwdUnit, off[L + 1] - e0);
-  const int tok0 = blk_tok0[gb], blen = blk_len[gb];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int col = lane & 31, qh = lane >> 5;  // not const: see the top of the tile loop
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-
-  // K/V staging: thread -> (key of the half, 16 channels); rows past the end of a ragged block are zero
-  const int skey = tid >> 3, sd0 = (tid & 7) * 16;
-  bf16x8 kreg[2], vreg[2];
-  auto load_kv = [&](int hf) {
-    int key = 64 * hf + skey;
-    asm volatile("" : "+v"(key));  // recompute the addresses at each use instead of keeping them in registers
-    const size_t o = ((size_t)(tok0 + key) * P.hkv + j) * kD + sd0;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      kreg[i] = key < blen ? *reinterpret_cast<const bf16x8*>(K + o + 8 * i) : zero8;
-      vreg[i] = key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
-    }
-  };
-  auto stage_kv = [&]() {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      *reinterpret_cast<bf16x8*>(&Ks[skey * kRowStride + sd0 + 8 * i]) = kreg[i];
-      *reinterpret_cast<bf16x8*>(&Vs[skey * kRowStride + sd0 + 8 * i]) = vreg[i];
-    }
-  };
-  load_kv(0);
-  if (NH == 1) stage_kv();
-  for (int i = tid; i < ne; i += 512) ent[i] = qent[e0 + i].x;
-  f32x16 dkacc[NH], dvacc[NH];
-#pragma unroll
-  for (int hf = 0; hf < NH; ++hf)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      dkacc[hf][v] = 0.f;
-      dvacc[hf][v] = 0.f;
-    }
-  __syncthreads();
-
-  const int rows_total = ne * P.g;
-  const float c2 = P.scale * 1.4426950408889634f;
-  const size_t hq = P.hq;
-  const int hbase = j * P.g;
-  const int rb = wave >> 1, half = wave & 1;   // roles rows/keys (half = mb) and rows/chans (half = dh)
-  const int mb2 = wave >> 2, dsl = wave & 3;   // role keys/chans
-  // this lane's share of a transposing LDS read of four rows x 16 columns: its group's 16 columns start at
-  // 16 (grp & 1) of a 32-column slice, the group's lanes belong to MFMA lane half grp / 2
-  const int grp = lane >> 4, sl = lane & 15;
-  int tr_lane = (sl >> 2) * kRowStride + 16 * (grp & 1) + 4 * (sl & 3);
-  // staging layout of the rows/chans role: 8 lanes x 16 B cover the 64 channels of a row half, 8 rows per access
-  int srow = lane >> 3, schunk = 64 * half + (lane & 7) * 8;
-  bf16_t* Qmine = Qs + (32 * rb) * kRowStride;
-  bf16_t* dOmine = dOs + (32 * rb) * kRowStride;
-
-  u32x4 qc[4], dc[4];
-  float lse2_n, dl_n;
-  auto issue_rows = [&](int tile0) {
-    // rows past the end of the list re-read its last row: their P and dS are forced to zero (lim = 0) and their
-    // dQ is never stored, so no branch and no zero fill is needed
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = min(tile0 + 32 * rb + 8 * i + srow, rows_total - 1);
-      const int e = div_g(r, P.g, P.g_magic);
-      const size_t o = ((size_t)ent[e] * hq + hbase + (r - e * P.g)) * kD + schunk;
-      qc[i] = *reinterpret_cast<const u32x4*>(Q + o);
-      dc[i] = *reinterpret_cast<const u32x4*>(dO + o);
-    }
-    const int rc = min(tile0 + 32 * rb + col, rows_total - 1);
-    const int ec = div_g(rc, P.g, P.g_magic);
-    const float2 st = stats[(size_t)ent[ec] * hq + hbase + (rc - ec * P.g)];  // (LSE in the log2 domain, delta)
-    lse2_n = st.x;
-    dl_n = st.y;
-  };
-  issue_rows(0);
-
-  for (int tile0 = 0; tile0 < rows_total; tile0 += kTileRows) {
-    // Register budget of the two-half variant: the lane-dependent index pieces are made opaque here so that the
-    // ~100 LDS addresses derived from them are recomputed where they are used instead of being kept in registers
-    // across the whole loop (the one-half variant has the room and keeps them).
-    if (NH == 2) asm volatile("" : "+v"(col), "+v"(qh), "+v"(tr_lane), "+v"(srow), "+v"(schunk));
-    // stage this wave's part of the tile; then let the next tile's rows fly while this one computes
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<u32x4*>(&Qmine[(8 * i + srow) * kRowStride + schunk]) = qc[i];
-      *reinterpret_cast<u32x4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
-    }
-    const float lse2 = lse2_n, dl = dl_n;
-    const bool more = tile0 + kTileRows < rows_total;
-    if (NH == 1 && more) issue_rows(tile0 + kTileRows);
-    const int r = tile0 + 32 * rb + col;
-    const bool valid = r < rows_total;
-    const int t = valid ? ent[div_g(r, P.g, P.g_magic)] : -1;
-    int lim = P.causal ? min(blen, t - tok0 + 1) : blen;  // keys [0, lim) of the block are visible to this row
-    if (!valid) lim = 0;
-    f32x16 dqacc[2];
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
-
-#pragma unroll
-    for (int hf = 0; hf < NH; ++hf) {
-      if (NH == 2) stage_kv();  // this half's K/V (loaded ahead into registers) -> LDS
-      __syncthreads();
-      // register budget (two waves per SIMD): the first half carries the second half's K/V in flight, the second
-      // half carries the next tile's Q / dO rows; the first half's K/V is re-fetched (L2) behind the dQ store
-      if (NH == 2 && hf == 0) load_kv(1);
-      if (NH == 2 && hf == 1 && more) issue_rows(tile0 + kTileRows);
-
-      {  // role rows/keys: S^T = K_i Q^T, dP^T = V_i dO^T, P, dS for rows 32 rb.., keys 64 hf + 32 half..
-        f32x16 sacc, dpacc;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          sacc[v] = 0.f;
-          dpacc[v] = 0.f;
-        }
-        const bf16_t* qrow = Qmine + col * kRowStride + 8 * qh;
-        const bf16_t* drow = dOmine + col * kRowStride + 8 * qh;
-        const bf16_t* krow = Ks + (32 * half + col) * kRowStride + 8 * qh;
-        const bf16_t* vrow = Vs + (32 * half + col) * kRowStride + 8 * qh;
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
-          const bf16x8 dof = *reinterpret_cast<const bf16x8*>(drow + 16 * s);
-          const bf16x8 kfa = *reinterpret_cast<const bf16x8*>(krow + 16 * s);
-          const bf16x8 vfa = *reinterpret_cast<const bf16x8*>(vrow + 16 * s);
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa, qf, sacc, 0, 0, 0);
-          dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa, dof, dpacc, 0, 0, 0);
-          if (NH == 2 && (s & 1)) __builtin_amdgcn_sched_barrier(0);  // bound the operands in flight (register budget)
-        }
-        bf16_t* pdst = Pt + 32 * rb + col;
-        bf16_t* sdst = dSt + 32 * rb + col;
-        const float dls = dl * P.scale;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = 32 * half + 8 * (v >> 2) + 4 * qh + (v & 3);
-          const float p = 64 * hf + key < lim ? __builtin_amdgcn_exp2f(fmaf(sacc[v], c2, -lse2)) : 0.f;
-          const float ds = p * fmaf(dpacc[v], P.scale, -dls);  // P (dP - delta) scale
-          pdst[key * kRowStride] = (bf16_t)p;
-          sdst[key * kRowStride] = (bf16_t)ds;
-        }
-      }
-      __syncthreads();
-      {  // role keys/chans: dV_i += P^T dO, dK_i += dS^T Q over the tile's 128 rows.  A operands (lane = key,
-         // elements = 8 rows) are plain reads of P^T / dS^T; B operands (lane = channel, elements = 8 rows) are
-         // transposing reads of the row-major dO / Q tiles.
-        // (the transposing read takes no immediate offset; keeping its addresses opaque per phase stops the compiler
-        // from precomputing all of them outside the tile loop, which cost ~56 registers)
-        int tr_row = tr_lane + 8 * (grp >> 1) * kRowStride + 32 * dsl;
-        asm volatile("" : "+v"(tr_row));
-        const bf16_t* parow = Pt + (32 * mb2 + col) * kRowStride + 8 * qh;
-        const bf16_t* sarow = dSt + (32 * mb2 + col) * kRowStride + 8 * qh;
-#pragma unroll
-        for (int qs = 0; qs < 8; ++qs) {
-          const bf16x4 d0 = lds_read_tr(&dOs[16 * qs * kRowStride + tr_row]);
-          const bf16x4 d1 = lds_read_tr(&dOs[(16 * qs + 4) * kRowStride + tr_row]);
-          const bf16x4 q0 = lds_read_tr(&Qs[16 * qs * kRowStride + tr_row]);
-          const bf16x4 q1 = lds_read_tr(&Qs[(16 * qs + 4) * kRowStride + tr_row]);
-          const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
-          const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
-          const bf16x8 pa = *reinterpret_cast<const bf16x8*>(parow + 16 * qs);
-          const bf16x8 sa = *reinterpret_cast<const bf16x8*>(sarow + 16 * qs);
-          dvacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc[hf], 0, 0, 0);
-          dkacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qb, dkacc[hf], 0, 0, 0);
-          if (NH == 2 && (qs & 1)) __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-      {  // role rows/chans: dQ^T[64 half.. , 32 rb..] += K_i^T dS^T, contraction over this half's 64 keys in natural
-         // order.  A = K^T (lane = channel, elements = 8 keys) and B = dS^T (lane = row, elements = 8 keys) both
-         // come from row-major tiles (K [key][chan], dS^T [key][row]) by transposing reads.
-        int tr_key = tr_lane + 8 * (grp >> 1) * kRowStride;
-        asm volatile("" : "+v"(tr_key));
-#pragma unroll
-        for (int sp = 0; sp < 4; ++sp) {
-          const bf16x4 b0 = lds_read_tr(&dSt[16 * sp * kRowStride + tr_key + 32 * rb]);
-          const bf16x4 b1 = lds_read_tr(&dSt[(16 * sp + 4) * kRowStride + tr_key + 32 * rb]);
-          const bf16x8 dsb = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-          for (int db = 0; db < 2; ++db) {
-            const bf16x4 a0 = lds_read_tr(&Ks[16 * sp * kRowStride + tr_key + 64 * half + 32 * db]);
-            const bf16x4 a1 = lds_read_tr(&Ks[(16 * sp + 4) * kRowStride + tr_key + 64 * half + 32 * db]);
-            const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-            dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsb, dqacc[db], 0, 0, 0);
-          }
-          if (NH == 2) __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-      __syncthreads();
-    }
-    if (NH == 2 && more) load_kv(0);
-    // dQ rows (this wave's 32 rows x 64 channels) -> the part of the Q tile this wave staged -> 128-byte row
-    // segments at the rows' list position
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        uint2 w;
-        w.x = pack_bf16x2(dqacc[db][4 * a + 0], dqacc[db][4 * a + 1]);
-        w.y = pack_bf16x2(dqacc[db][4 * a + 2], dqacc[db][4 * a + 3]);
-        *reinterpret_cast<uint2*>(&Qmine[col * kRowStride + 64 * half + 32 * db + 8 * a + 4 * qh]) = w;
-      }
-    wave_sync_bwd();
-    const size_t prow0 = (size_t)(e0 - pos0) * P.g + (size_t)(tile0 + 32 * rb);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = 8 * i + srow;
-      if (tile0 + 32 * rb + row < rows_total)
-        store_streaming(dqpart + (prow0 + row) * kD + schunk,
-                        *reinterpret_cast<const uint4*>(&Qmine[row * kRowStride + schunk]));
-    }
-    wave_sync_bwd();
-  }
-  if (nu_scan[L + 1] - nu_scan[L] == 1) {
-    // the whole list fitted this unit: dK_i, dV_i are final, write them as bf16 (keys of a ragged tail excluded)
-    bf16_t* outk = dK + ((size_t)tok0 * P.hkv + j) * kD + 32 * dsl + col;
-    bf16_t* outv = dV + ((size_t)tok0 * P.hkv + j) * kD + 32 * dsl + col;
-#pragma unroll
-    for (int hf = 0; hf < NH; ++hf)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = 64 * hf + 32 * mb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
-        if (key < blen) {
-          outk[(size_t)key * P.hkv * kD] = (bf16_t)dkacc[hf][v];
-          outv[(size_t)key * P.hkv * kD] = (bf16_t)dvacc[hf][v];
-        }
-      }
-    return;
-  }
-  // unit partial: [u][0 = dK, 1 = dV][key][d] fp32, summed by k_bwd_dkv_reduce in unit order
-  float* outk = dkv_part + (size_t)(u - ubase) * 2 * (NH * kBlock) * kD + 32 * dsl + col;
-  float* outv = outk + (NH * kBlock) * kD;
-#pragma unroll
-  for (int hf = 0; hf < NH; ++hf)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int key = 64 * hf + 32 * mb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
-      outk[key * kD] = dkacc[hf][v];
-      outv[key * kD] = dvacc[hf][v];
-    }
-}
-
-// ---- B_K = 64: two workgroups per CU -------------------------------------------------------------------------
-// Same mathematics and the same three roles as k_bwd_main above, re-cut so that TWO workgroups share a CU: four
-// wavefronts (256 registers each) and half of the LDS per workgroup.  The two workgroups run out of phase, so one's
-// barriers, gather waits, unit prologue and LDS-bound phases are covered by the other's MFMA work (with one
-// eight-wave workgroup per CU all waves sat in the same phase and LDS, MFMA and VALU time simply added up).
-// Per 64-row tile (w = wave index, rb = w / 2, hf = w % 2):
-//   rows/keys   S^T, dP^T, P, dS for rows 32 rb.. and keys 32 hf..; K_i fragments from LDS, V_i fragments of the
-//               wave's 32 keys held in registers for the whole unit (V_i is used by this role only)
-//   keys/chans  dV_i, dK_i accumulators for keys 32 rb.. and channels 64 hf.. (two 32-channel blocks share every
-//               P^T / dS^T operand read)
-//   rows/chans  dQ^T for rows 32 rb.. and channels 64 hf..; the same wave stages / prefetches that part of the Q and
-//               dO tiles and stores that part of dQ
-// The list's token ids are kept in LDS 1024 entries at a time.
-constexpr int kB2Rows = 64;    // rows per tile
-constexpr int kPStride = 72;   // bf16 per row of the P^T / dS^T tiles: 64 rows + 8 pad (144-byte pitch)
+// ---- the tiled backward main kernel ----------------------------------------------------------------------------
+// NKB = B_K / 32 key blocks, 2 NKB wavefronts per workgroup, tiles of 64 gathered rows.
+// With B_K = 64 (NKB = 2) a workgroup is four wavefronts (256 registers each) and half of a CU's LDS, so TWO
+// workgroups share a CU and run out of phase: one's barriers, gather waits, unit prologue and LDS-bound phases are
+// covered by the other's MFMA work (with one eight-wave workgroup per CU all waves sat in the same phase, and LDS,
+// MFMA and VALU time simply added up).  With B_K = 128 (NKB = 4) the fp32 dK/dV accumulators of the block need eight
+// waves' registers and there is one workgroup per CU.
+// Per tile, wave w takes three roles in turn:
+//   rows/keys   (rb = w / NKB, kb = w % NKB): S^T, dP^T, P, dS for rows 32 rb.. and keys 32 kb..; K_i fragments from
+//               LDS, V_i fragments of the wave's 32 keys held in registers for the whole unit (only this role uses V_i)
+//   keys/chans  (kb2 = w / 2, hf = w % 2): dV_i, dK_i accumulators for keys 32 kb2.. and channels 64 hf.. (two
+//               32-channel blocks share every P^T / dS^T operand read)
+//   rows/chans  (rb = w / NKB, part = w % NKB): dQ^T for rows 32 rb.. and the 128 / NKB channels of `part`; the same
+//               wave stages / prefetches that part of the Q and dO tiles and stores that part of dQ
+// K_i, Q, dO (304-byte pitch) and P^T, dS^T (144-byte pitch) are row-major tiles in LDS; "lane = column" operands
+// are LDS transpose reads.  The list's token ids are kept in LDS 1024 entries at a time.
+constexpr int kTile = 64;      // rows per tile
+constexpr int kPStride = 72;   // bf16 per row of the P^T / dS^T tiles: 64 rows + 8 pad
 constexpr int kEntSeg = 1024;  // list entries whose token ids are resident in LDS
-constexpr int kB2K = 0;
-constexpr int kB2Q = kB2K + kBlock * kRowStride * 2;
-constexpr int kB2DO = kB2Q + kB2Rows * kRowStride * 2;
-constexpr int kB2Pt = kB2DO + kB2Rows * kRowStride * 2;
-constexpr int kB2DSt = kB2Pt + kBlock * kPStride * 2;
-constexpr int kB2Ent = kB2DSt + kBlock * kPStride * 2;
-constexpr int kB2Bytes = kB2Ent + kEntSeg * 4;  // 80896
-static_assert(2 * kB2Bytes <= 160 * 1024, "two workgroups of the 64-key backward must fit one CU's LDS");
-static_assert((kEntSeg * 1) % 64 == 0, "segments hold whole tiles for every g");
 
-__global__ void __launch_bounds__(256, 2)
-k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-             const bf16_t* __restrict__ dO, const float2* __restrict__ stats, const int32_t* __restrict__ u_list,
-             const int32_t* __restrict__ u_start, const int32_t* __restrict__ off,
-             const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
-             const int2* __restrict__ qent, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
-             float* __restrict__ dkv_part, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
+template <int NKB>
+struct BwdLds {
+  static constexpr int kKeys = 32 * NKB;
+  static constexpr int K = 0;
+  static constexpr int Q = K + kKeys * kRowStride * 2;
+  static constexpr int DO = Q + kTile * kRowStride * 2;
+  static constexpr int Pt = DO + kTile * kRowStride * 2;
+  static constexpr int DSt = Pt + kKeys * kPStride * 2;
+  static constexpr int Ent = DSt + kKeys * kPStride * 2;
+  static constexpr int Bytes = Ent + kEntSeg * 4;  // 80896 (NKB = 2), 118784 (NKB = 4)
+};
+static_assert(2 * BwdLds<2>::Bytes <= 160 * 1024, "two workgroups of the 64-key backward must fit one CU's LDS");
+static_assert(BwdLds<4>::Bytes <= 160 * 1024, "the 128-key backward must fit one CU's LDS");
+
+template <int NKB>
+__global__ void __launch_bounds__(128 * NKB, NKB == 2 ? 2 : 1)
+k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+            const bf16_t* __restrict__ dO, const float2* __restrict__ stats, const int32_t* __restrict__ u_list,
+            const int32_t* __restrict__ u_start, const int32_t* __restrict__ off,
+            const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
+            const int2* __restrict__ qent, const int32_t* __restrict__ nu_scan, bf16_t* __restrict__ dqpart,
+            float* __restrict__ dkv_part, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
+  using Lds = BwdLds<NKB>;
+  constexpr int kKeys = 32 * NKB;      // B_K
+  constexpr int kThreads = 128 * NKB;
+  constexpr int kCW = 128 / NKB;       // channels of the rows/chans part of a wave: 64 or 32
+  constexpr int kNDB = kCW / 32;       // its 32-channel accumulator blocks: 2 or 1
+  constexpr int kLPR = kCW / 8;        // lanes (16 bytes each) that cover the part's channels of one row: 8 or 4
+  constexpr int kRPP = 64 / kLPR;      // rows staged per access: 8 or 16
+  constexpr int kNP = 32 / kRPP;       // accesses per tile and tensor: 4 or 2
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kB2K);
-  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + kB2Q);
-  bf16_t* dOs = reinterpret_cast<bf16_t*>(smem + kB2DO);
-  bf16_t* Pt = reinterpret_cast<bf16_t*>(smem + kB2Pt);
-  bf16_t* dSt = reinterpret_cast<bf16_t*>(smem + kB2DSt);
-  int32_t* ent = reinterpret_cast<int32_t*>(smem + kB2Ent);
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + Lds::K);
+  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + Lds::Q);
+  bf16_t* dOs = reinterpret_cast<bf16_t*>(smem + Lds::DO);
+  bf16_t* Pt = reinterpret_cast<bf16_t*>(smem + Lds::Pt);
+  bf16_t* dSt = reinterpret_cast<bf16_t*>(smem + Lds::DSt);
+  int32_t* ent = reinterpret_cast<int32_t*>(smem + Lds::Ent);
 
   const int ubase = nu_scan[P.j0 * P.b_cap];
   const int u = ubase + blockIdx.x;
@@ -407,7 +134,8 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int col = lane & 31, qh = lane >> 5;  // not const: made opaque at the top of the tile loop
-  const int rb = wave >> 1, hf = wave & 1;
+  const int rb = wave / NKB, kb = wave % NKB;   // rows/keys role; rows/chans role uses (rb, part = kb)
+  const int kb2 = wave >> 1, hf = wave & 1;     // keys/chans role
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
   {  // K_i -> LDS, row-major; rows past the end of a ragged block are zero
@@ -418,9 +146,9 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
       *reinterpret_cast<bf16x8*>(&Ks[key * kRowStride + d0 + 8 * i]) =
           key < blen ? *reinterpret_cast<const bf16x8*>(src + 8 * i) : zero8;
   }
-  bf16x8 vf[8];  // V_i fragments of keys 32 hf.. (A operand of dP^T = V_i dO^T)
+  bf16x8 vf[8];  // V_i fragments of keys 32 kb.. (A operand of dP^T = V_i dO^T)
   {
-    const int key = 32 * hf + col;
+    const int key = 32 * kb + col;
     const bf16_t* src = V + ((size_t)(tok0 + key) * P.hkv + j) * kD + 8 * qh;
 #pragma unroll
     for (int s = 0; s < 8; ++s) vf[s] = key < blen ? *reinterpret_cast<const bf16x8*>(src + 16 * s) : zero8;
@@ -441,12 +169,12 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
   // this lane's share of a transposing read of four rows x 16 columns (see lds_read_tr), for the two row pitches
   int tr_lane = ((sl >> 2) + 8 * (grp >> 1)) * kRowStride + 16 * (grp & 1) + 4 * (sl & 3);
   int tr_lane_p = ((sl >> 2) + 8 * (grp >> 1)) * kPStride + 16 * (grp & 1) + 4 * (sl & 3);
-  // staging layout: 8 lanes x 16 B cover the 64 channels of a row half, 8 rows per access
-  int srow = lane >> 3, schunk = 64 * hf + (lane & 7) * 8;
+  // staging layout of this wave's part: kLPR lanes x 16 B cover its channels of a row, kRPP rows per access
+  int srow = lane / kLPR, schunk = kCW * kb + (lane % kLPR) * 8;
   bf16_t* Qmine = Qs + (32 * rb) * kRowStride;
   bf16_t* dOmine = dOs + (32 * rb) * kRowStride;
 
-  u32x4 qc[4], dc[4];
+  u32x4 qc[kNP], dc[kNP];
   float lse2_n, dl_n;
   int seg0 = 0;  // first list entry whose token id is in `ent`
   int rows_end = 0;
@@ -454,8 +182,8 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
     // rows past the end of the list re-read its last row: their P and dS are forced to zero (lim = 0) and their
     // dQ is never stored, so no branch and no zero fill is needed
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = min(tile0 + 32 * rb + 8 * i + srow, rows_end - 1);
+    for (int i = 0; i < kNP; ++i) {
+      const int r = min(tile0 + 32 * rb + kRPP * i + srow, rows_end - 1);
       const int e = div_g(r, P.g, P.g_magic);
       const size_t o = ((size_t)ent[e - seg0] * hq + hbase + (r - e * P.g)) * kD + schunk;
       qc[i] = *reinterpret_cast<const u32x4*>(Q + o);
@@ -470,23 +198,23 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
 
   for (seg0 = 0; seg0 < ne; seg0 += kEntSeg) {
     const int seg_n = min(kEntSeg, ne - seg0);
-    __syncthreads();  // the previous segment's ids (and, first time, nothing) are no longer read
-    for (int i = tid; i < seg_n; i += 256) ent[i] = qent[e0 + seg0 + i].x;
+    __syncthreads();  // the previous segment's ids are no longer read
+    for (int i = tid; i < seg_n; i += kThreads) ent[i] = qent[e0 + seg0 + i].x;
     __syncthreads();  // ids (and K_i on the first pass) visible
     rows_end = (seg0 + seg_n) * P.g;
     issue_rows(seg0 * P.g);
 
-    for (int tile0 = seg0 * P.g; tile0 < rows_end; tile0 += kB2Rows) {
+    for (int tile0 = seg0 * P.g; tile0 < rows_end; tile0 += kTile) {
       // keep the lane-derived LDS addresses from being precomputed and held across the loop (register budget)
       asm volatile("" : "+v"(col), "+v"(qh), "+v"(tr_lane), "+v"(tr_lane_p), "+v"(srow), "+v"(schunk));
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<u32x4*>(&Qmine[(8 * i + srow) * kRowStride + schunk]) = qc[i];
-        *reinterpret_cast<u32x4*>(&dOmine[(8 * i + srow) * kRowStride + schunk]) = dc[i];
+      for (int i = 0; i < kNP; ++i) {
+        *reinterpret_cast<u32x4*>(&Qmine[(kRPP * i + srow) * kRowStride + schunk]) = qc[i];
+        *reinterpret_cast<u32x4*>(&dOmine[(kRPP * i + srow) * kRowStride + schunk]) = dc[i];
       }
       const float lse2 = lse2_n, dl = dl_n;
-      const bool more = tile0 + kB2Rows < rows_end;
-      if (more) issue_rows(tile0 + kB2Rows);  // the next tile's rows fly while this one computes
+      const bool more = tile0 + kTile < rows_end;
+      if (more) issue_rows(tile0 + kTile);  // the next tile's rows fly while this one computes
       const int r = tile0 + 32 * rb + col;
       const bool valid = r < rows_end;
       const int t = valid ? ent[div_g(r, P.g, P.g_magic) - seg0] : -1;
@@ -503,7 +231,7 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
         }
         const bf16_t* qrow = Qmine + col * kRowStride + 8 * qh;
         const bf16_t* drow = dOmine + col * kRowStride + 8 * qh;
-        const bf16_t* krow = Ks + (32 * hf + col) * kRowStride + 8 * qh;
+        const bf16_t* krow = Ks + (32 * kb + col) * kRowStride + 8 * qh;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
           const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
@@ -517,7 +245,7 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
         const float dls = dl * P.scale;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int key = 32 * hf + 8 * (v >> 2) + 4 * qh + (v & 3);
+          const int key = 32 * kb + 8 * (v >> 2) + 4 * qh + (v & 3);
           const float p = key < lim ? __builtin_amdgcn_exp2f(fmaf(sacc[v], c2, -lse2)) : 0.f;
           const float ds = p * fmaf(dpacc[v], P.scale, -dls);  // P (dP - delta) scale
           pdst[key * kPStride] = (bf16_t)p;
@@ -525,11 +253,11 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
         }
       }
       __syncthreads();  // P^T, dS^T complete
-      {  // role keys/chans: dV_i += P^T dO, dK_i += dS^T Q for keys 32 rb.., channels 64 hf + 32 cb..
+      {  // role keys/chans: dV_i += P^T dO, dK_i += dS^T Q for keys 32 kb2.., channels 64 hf + 32 cb..
         int tr_row = tr_lane + 64 * hf;
         asm volatile("" : "+v"(tr_row));
-        const bf16_t* parow = Pt + (32 * rb + col) * kPStride + 8 * qh;
-        const bf16_t* sarow = dSt + (32 * rb + col) * kPStride + 8 * qh;
+        const bf16_t* parow = Pt + (32 * kb2 + col) * kPStride + 8 * qh;
+        const bf16_t* sarow = dSt + (32 * kb2 + col) * kPStride + 8 * qh;
 #pragma unroll
         for (int qs = 0; qs < 4; ++qs) {
           const bf16x8 pa = *reinterpret_cast<const bf16x8*>(parow + 16 * qs);
@@ -547,22 +275,22 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
           }
         }
       }
-      f32x16 dqacc[2];
-      {  // role rows/chans: dQ^T[64 hf.., 32 rb..] = K_i^T dS^T over the 64 keys
+      f32x16 dqacc[kNDB];
+      {  // role rows/chans: dQ^T[kCW kb.., 32 rb..] = K_i^T dS^T over the block's keys
 #pragma unroll
-        for (int db = 0; db < 2; ++db)
+        for (int db = 0; db < kNDB; ++db)
 #pragma unroll
           for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
-        int tr_key = tr_lane + 64 * hf;
+        int tr_key = tr_lane + kCW * kb;
         int tr_ds = tr_lane_p + 32 * rb;
         asm volatile("" : "+v"(tr_key), "+v"(tr_ds));
 #pragma unroll
-        for (int sp = 0; sp < 4; ++sp) {
+        for (int sp = 0; sp < kKeys / 16; ++sp) {
           const bf16x4 b0 = lds_read_tr(&dSt[16 * sp * kPStride + tr_ds]);
           const bf16x4 b1 = lds_read_tr(&dSt[(16 * sp + 4) * kPStride + tr_ds]);
           const bf16x8 dsb = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-          for (int db = 0; db < 2; ++db) {
+          for (int db = 0; db < kNDB; ++db) {
             const bf16x4 a0 = lds_read_tr(&Ks[16 * sp * kRowStride + tr_key + 32 * db]);
             const bf16x4 a1 = lds_read_tr(&Ks[(16 * sp + 4) * kRowStride + tr_key + 32 * db]);
             const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -571,21 +299,21 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
         }
       }
       __syncthreads();  // every wave is done reading the Q / dO / P^T / dS^T tiles
-      // dQ rows (32 rows x 64 channels) -> the part of the Q tile this wave staged -> 128-byte row segments
+      // dQ rows (32 rows x kCW channels) -> the part of the Q tile this wave staged -> contiguous row segments
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < kNDB; ++db)
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
           uint2 w;
           w.x = pack_bf16x2(dqacc[db][4 * a + 0], dqacc[db][4 * a + 1]);
           w.y = pack_bf16x2(dqacc[db][4 * a + 2], dqacc[db][4 * a + 3]);
-          *reinterpret_cast<uint2*>(&Qmine[col * kRowStride + 64 * hf + 32 * db + 8 * a + 4 * qh]) = w;
+          *reinterpret_cast<uint2*>(&Qmine[col * kRowStride + kCW * kb + 32 * db + 8 * a + 4 * qh]) = w;
         }
       wave_sync_bwd();
       const size_t prow0 = (size_t)(e0 - pos0) * P.g + (size_t)(tile0 + 32 * rb);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = 8 * i + srow;
+      for (int i = 0; i < kNP; ++i) {
+        const int row = kRPP * i + srow;
         if (tile0 + 32 * rb + row < rows_end)
           store_streaming(dqpart + (prow0 + row) * kD + schunk,
                           *reinterpret_cast<const uint4*>(&Qmine[row * kRowStride + schunk]));
@@ -602,7 +330,7 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
       bf16_t* outv = dV + ((size_t)tok0 * P.hkv + j) * kD + 64 * hf + 32 * cb + col;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int key = 32 * rb + 8 * (v >> 2) + 4 * qh + (v & 3);
+        const int key = 32 * kb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
         if (key < blen) {
           outk[(size_t)key * P.hkv * kD] = (bf16_t)dkacc[cb][v];
           outv[(size_t)key * P.hkv * kD] = (bf16_t)dvacc[cb][v];
@@ -614,11 +342,11 @@ k_bwd_main64(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__
   // unit partial: [u][0 = dK, 1 = dV][key][d] fp32, summed by k_bwd_dkv_reduce in unit order
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb) {
-    float* outk = dkv_part + (size_t)(u - ubase) * 2 * kBlock * kD + 64 * hf + 32 * cb + col;
-    float* outv = outk + kBlock * kD;
+    float* outk = dkv_part + (size_t)(u - ubase) * 2 * kKeys * kD + 64 * hf + 32 * cb + col;
+    float* outv = outk + kKeys * kD;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int key = 32 * rb + 8 * (v >> 2) + 4 * qh + (v & 3);
+      const int key = 32 * kb2 + 8 * (v >> 2) + 4 * qh + (v & 3);
       outk[key * kD] = dkacc[cb][v];
       outv[key * kD] = dvacc[cb][v];
     }
@@ -699,11 +427,11 @@ hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
                       const void* V, const void* O, const float* LSE, const void* dO, const void* index_ws,
                       void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
-  // 64-token blocks: four-wave kernel, two workgroups per CU; 128-token blocks: eight-wave kernel, two key halves
+  // 64-token blocks: four waves, two workgroups per CU; 128-token blocks: eight waves, one workgroup per CU
   const bool b128 = P0.bk == 128;
-  auto* main_kernel = b128 ? k_bwd_main<2> : k_bwd_main64;
+  auto* main_kernel = b128 ? k_bwd_tiled<4> : k_bwd_tiled<2>;
   const int main_threads = b128 ? 512 : 256;
-  const int main_lds = b128 ? kLdsBwdBytes : kB2Bytes;
+  const int main_lds = b128 ? BwdLds<4>::Bytes : BwdLds<2>::Bytes;
   {
     static std::atomic<uint64_t> ready[2];
     hipError_t e = allow_dynamic_lds((const void*)main_kernel, main_lds, ready[b128]);
