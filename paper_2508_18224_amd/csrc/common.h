@@ -14,7 +14,7 @@ namespace nsa {
 constexpr int kBlock = 64;         // keys per MFMA key tile (B_K = 64 is one tile, B_K = 128 two)
 constexpr int kD = 128;            // head dimension
 constexpr int kChunkTokens = 512;  // token chunk of the inversion histogram / scatter
-constexpr int kFwdUnit = 1024;      // list entries per forward work unit
+constexpr int kFwdUnit = 2048;     // list entries per forward work unit
 constexpr int kBwdUnit = 2048;     // list entries per backward work unit
 constexpr int kMaxTopk = 32;
 

@@ -50,7 +50,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
            float* __restrict__ lse_part) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kD * kVtStride];
   __shared__ __attribute__((aligned(16))) bf16_t tiles[4][32 * kTileStride];
-  __shared__ int2 ent[kFwdUnit];  // (token, slot) of the unit's list entries
+  __shared__ int32_t ent[kFwdUnit];  // tokens of the unit's list entries
   // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
   const int u = nu_scan[P.j0 * P.b_cap] + blockIdx.x;
   if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
@@ -83,7 +83,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
     for (int s = 0; s < 8; ++s) kf[mb][s] = key < blen ? *reinterpret_cast<const bf16x8*>(src + 16 * s) : zero8;
   }
-  for (int i = tid; i < ne; i += 256) ent[i] = qent[e0 + i];
+  for (int i = tid; i < ne; i += 256) ent[i] = qent[e0 + i].x;
   __syncthreads();
   const bf16_t* vbase = &Vt[col * kVtStride + 8 * qh];  // this lane's V^T fragments: + 32 db rows, + 16 sp keys
 
@@ -102,7 +102,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       // rows past the end of the list re-read the last row: they are masked out below and never stored
       const int r = min(tile * 32 + 4 * i + crow, rows_total - 1);
       const int e = div_g(r, P.g, P.g_magic);
-      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)ent[e].x * hq + hbase + (r - e * P.g)) * kD + cchunk);
+      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)ent[e] * hq + hbase + (r - e * P.g)) * kD + cchunk);
     }
   };
 
@@ -131,7 +131,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     // keys [0, lim) of the block are visible to this row
     const int r = tile * 32 + col;
     const bool valid = r < rows_total;
-    const int t = valid ? ent[div_g(r, P.g, P.g_magic)].x : -1;
+    const int t = valid ? ent[div_g(r, P.g, P.g_magic)] : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
     // Only tiles with a row in the block itself (causal diagonal) or a ragged block end need the key mask; the
@@ -227,7 +227,7 @@ constexpr int kF128K = 0;
 constexpr int kF128V = kF128K + 128 * kPitch128 * 2;
 constexpr int kF128Tiles = kF128V + 128 * kPitch128 * 2;
 constexpr int kF128Ent = kF128Tiles + kWaves128 * 32 * kTileStride * 2;
-constexpr int kF128Bytes = kF128Ent + kFwdUnit * 8;  // 155648
+constexpr int kF128Bytes = kF128Ent + kFwdUnit * 4;
 static_assert(kF128Bytes <= 160 * 1024, "forward 128-key tile set must fit the CU's LDS");
 
 // ds_read_b64_tr_b16: every lane passes the address of 8 bytes (four 16-bit elements); within each group of 16
@@ -249,7 +249,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kF128K);
   bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kF128V);
-  int2* ent = reinterpret_cast<int2*>(smem + kF128Ent);
+  int32_t* ent = reinterpret_cast<int32_t*>(smem + kF128Ent);
   // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
   const int u = nu_scan[P.j0 * P.b_cap] + blockIdx.x;
   if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
@@ -277,7 +277,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
           key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
     }
   }
-  for (int i = tid; i < ne; i += 64 * kWaves128) ent[i] = qent[e0 + i];
+  for (int i = tid; i < ne; i += 64 * kWaves128) ent[i] = qent[e0 + i].x;
   __syncthreads();
 
   const int rows_total = ne * P.g;
@@ -298,7 +298,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
       // rows past the end of the list re-read the last row: they are masked out below and never stored
       const int r = min(tile * 32 + 4 * i + crow, rows_total - 1);
       const int e = div_g(r, P.g, P.g_magic);
-      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)ent[e].x * hq + hbase + (r - e * P.g)) * kD + cchunk);
+      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)ent[e] * hq + hbase + (r - e * P.g)) * kD + cchunk);
     }
   };
   issue_q(wave);
@@ -331,7 +331,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
 
     const int r = tile * 32 + col;
     const bool valid = r < rows_total;
-    const int t = valid ? ent[div_g(r, P.g, P.g_magic)].x : -1;
+    const int t = valid ? ent[div_g(r, P.g, P.g_magic)] : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
     // key mask only where a row lies in the block itself or the block is ragged (wave-uniform test); maximum over

@@ -45,10 +45,10 @@ def test_random_shape(seed):
     _check(w, scale=float(rng.choice([0.0, 0.11])))
 
 
-@pytest.mark.parametrize("n_tokens,g", [(1024, 1), (1025, 1), (2048, 2), (2049, 1), (4096 + 64, 1)])
+@pytest.mark.parametrize("n_tokens,g", [(1024, 1), (1025, 1), (2048, 2), (2049, 1), (4096, 3), (4096 + 64, 1)])
 def test_list_length_at_unit_boundaries(n_tokens, g):
-    """Every token selects block 0 only: one list of exactly n_tokens entries (forward units hold 1024 entries,
-    backward units 2048), every other list empty."""
+    """Every token selects block 0 only: one list of exactly n_tokens entries, every other list empty (work units hold
+    2048 entries, the backward keeps token ids in LDS 1024 entries at a time)."""
     print("boundary case", n_tokens, g, flush=True)
     w = wl.realise(wl.Workload("b", [n_tokens], hq=g, hkv=1, topk=2, seed=n_tokens))
     w.idx[:] = -1
