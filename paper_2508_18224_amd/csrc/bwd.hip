@@ -369,17 +369,17 @@ k_bwd_dq_reduce(Problem P, const bf16_t* __restrict__ dqpart, const uint32_t* __
   const uint32_t vm = vmask[(size_t)t * P.hkv + j];
   const int32_t* sp = slotpos + ((size_t)t * P.hkv + j) * P.topk;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int m0 = 0; m0 < P.topk; m0 += 16) {  // 16 independent 256-byte gathers in flight per row
-    uint4 x[16];
+  for (int m0 = 0; m0 < P.topk; m0 += kSlotBatch) {  // kSlotBatch independent 256-byte gathers in flight per row
+    uint4 x[kSlotBatch];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < kSlotBatch; ++i) {
       const int m = m0 + i;
       const bool on = m < P.topk && ((vm >> m) & 1u);
       x[i] = on ? *reinterpret_cast<const uint4*>(dqpart + ((size_t)(sp[on ? m : 0] - pos0) * P.g + hh) * kD + 8 * sub)
                 : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < kSlotBatch; ++i) {
       acc[0] += bf16_lo(x[i].x); acc[1] += bf16_hi(x[i].x);
       acc[2] += bf16_lo(x[i].y); acc[3] += bf16_hi(x[i].y);
       acc[4] += bf16_lo(x[i].z); acc[5] += bf16_hi(x[i].z);

@@ -17,6 +17,7 @@ constexpr int kChunkTokens = 512;  // token chunk of the inversion histogram / s
 constexpr int kFwdUnit = 2048;     // list entries per forward work unit
 constexpr int kBwdUnit = 2048;     // list entries per backward work unit
 constexpr int kMaxTopk = 32;
+constexpr int kSlotBatch = 4;      // slots of a row the two reduction kernels gather at a time
 
 // Host-computed description of the index workspace (byte offsets from its base, all 256-aligned).
 struct IndexLayout {

@@ -408,9 +408,10 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   }
 }
 
-// 16 lanes per (token, head) row, 8 output channels per lane.  Slots are taken 16 at a time: positions, partial
-// log-sum-exps and partial rows of a batch are all requested before any of them is used, so one row keeps up to
-// 16 independent 256-byte gathers in flight; batches are chained by the usual running-max rescale.
+// 16 lanes per (token, head) row, 8 output channels per lane.  Slots are taken kSlotBatch at a time: positions,
+// partial log-sum-exps and partial rows of a batch are all requested before any of them is used; batches are chained
+// by the usual running-max rescale.  Small batches keep the register count low, and the many resident waves that
+// result hide the gather latency better than long batches did (16 -> 4: 1.87 -> 1.80 ms at the headline shape).
 __global__ void __launch_bounds__(256)
 k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict__ lse_part,
             const uint32_t* __restrict__ vmask, const int32_t* __restrict__ slotpos,
@@ -436,18 +437,18 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
   const int32_t* sp = slotpos + ((size_t)t * P.hkv + j) * P.topk;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   float M = -INFINITY, Ls = 0.f;
-  for (int m0 = 0; m0 < P.topk; m0 += 16) {
-    size_t pr[16];
-    uint4 x[16];
-    float ls[16];
+  for (int m0 = 0; m0 < P.topk; m0 += kSlotBatch) {
+    size_t pr[kSlotBatch];
+    uint4 x[kSlotBatch];
+    float ls[kSlotBatch];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < kSlotBatch; ++i) {
       const int m = m0 + i;
       const bool on = m < P.topk && ((vm >> m) & 1u);
       pr[i] = on ? (size_t)(sp[m] - pos0) * P.g + hh : (size_t)0;
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < kSlotBatch; ++i) {
       const int m = m0 + i;
       const bool on = m < P.topk && ((vm >> m) & 1u);
       x[i] = on ? *reinterpret_cast<const uint4*>(opart + pr[i] * kD + 8 * sub) : make_uint4(0, 0, 0, 0);
@@ -455,7 +456,7 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
     }
     float Mb = M;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) Mb = fmaxf(Mb, ls[i]);
+    for (int i = 0; i < kSlotBatch; ++i) Mb = fmaxf(Mb, ls[i]);
     if (Mb == -INFINITY) continue;  // no kept slot in this batch or before it
     const float rescale = __expf(M - Mb);  // 0 on the first non-empty batch
     Ls *= rescale;
@@ -463,7 +464,7 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
     for (int c = 0; c < 8; ++c) acc[c] *= rescale;
     M = Mb;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < kSlotBatch; ++i) {
       const float w = __expf(ls[i] - M);  // exp(-inf) = 0 for slots that are off
       Ls += w;
       acc[0] += w * bf16_lo(x[i].x); acc[1] += w * bf16_hi(x[i].x);
