@@ -26,8 +26,8 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by
 # the copy-kernel calibration); see profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
-    ("headline", "bwd_main"): 26.5e9,   # profiles/hot_path_headline_64k_g4.txt: fetch 17.60 GB + write 8.91 GB
-    ("headline", "fwd_main"): 16.36e9,
+    ("headline", "bwd_main"): 26.5e9,   # profiles/hot_path_headline_64k_g4.txt: fetch 17.62 GB + write 8.91 GB
+    ("headline", "fwd_main"): 16.66e9,
 }
 
 
