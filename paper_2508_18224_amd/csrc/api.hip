@@ -2,7 +2,7 @@
 #include "common.h"
 
 namespace nsa {
-int64_t index_scan_tmp_ints(int64_t n_counters);
+int64_t index_scan_tmp_ints(int64_t n_lists);
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -62,7 +62,7 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.b_nu = take(4 * (size_t)(L.n_lists + 1));
   L.b_list = take(4 * (size_t)(L.bwd_units_max + 1));
   L.b_start = take(4 * (size_t)(L.bwd_units_max + 1));
-  L.scan_tmp = take(4 * (size_t)index_scan_tmp_ints(L.n_counters));
+  L.scan_tmp = take(4 * (size_t)index_scan_tmp_ints(L.n_lists));
   L.total = o;
   return L;
 }

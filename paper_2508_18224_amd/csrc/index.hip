@@ -3,7 +3,9 @@
 // Sec. 3.2 "FSA token selection kernel") together with the column each entry came from, and, per kept
 // (token, kv head, column), the entry's position in its list, which is where its partial result lives in the
 // compact partial buffers (the role of the paper's O_i), plus the work-unit tables of the attention kernels.
-// Pipeline: per-(kv head, block, token chunk) histogram -> exclusive scan -> ordered scatter.
+// Pipeline: per-(kv head, token chunk, block) histogram -> prefix over the chunks of every list -> exclusive scan
+// of the list lengths -> ordered scatter.  The counters are stored chunk-major, [kv head][chunk][block], so that
+// the histogram and the scatter of one (chunk, kv head) touch one contiguous row.
 // The scatter is deterministic: a chunk is walked by one wavefront in rounds of 64 tokens, and a token's rank
 // inside a round is a popcount over a 64-bit membership mask, so no ordering depends on atomics.
 #include "common.h"
@@ -52,12 +54,6 @@ __global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int bk, 
   }
 }
 
-__global__ void k_zero(int32_t* __restrict__ p, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) p[i] = 0;
-}
-
 // Bit m of the result is set when column m of the row is a kept selection: in range for the sequence, not in
 // the token's future when causal, and not a repeat of an earlier column.
 __device__ __forceinline__ uint32_t kept_columns(const int32_t* row, int k, int b_s, int cur, int causal) {
@@ -85,8 +81,9 @@ __device__ __forceinline__ void chunk_window(const int32_t* cu, const int32_t* b
 }
 
 // ------------------------------------------------------------------------------------------------ histogram
-// grid (n_chunks, hkv), 256 threads.  counters[(j*b_cap + gb)*n_chunks + chunk] = number of tokens of the
-// chunk that keep block gb for kv head j.  Dynamic LDS: b_cap ints + 256*(k+1) ints.
+// grid (n_chunks, hkv), 256 threads.  counters[(j*n_chunks + chunk)*b_cap + gb] = number of tokens of the
+// chunk that keep block gb for kv head j; the whole row is written (zeros outside the chunk's window), so the
+// array needs no clearing.  Dynamic LDS: b_cap ints + 256*(k+1) ints.
 __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                               const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
                                               int bk, int causal, int b_cap, int n_chunks,
@@ -116,8 +113,65 @@ __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, c
       if ((vm >> m) & 1u) atomicAdd(&hist[base + row[m]], 1);
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < win; i += blockDim.x)
-    counters[((size_t)j * b_cap + gb_lo + i) * n_chunks + chunk] = hist[i];
+  int32_t* out = counters + ((size_t)j * n_chunks + chunk) * b_cap;
+  for (int i = threadIdx.x; i < b_cap; i += blockDim.x) out[i] = (i >= gb_lo && i < gb_hi) ? hist[i - gb_lo] : 0;
+}
+
+// ------------------------------------------------------------------------------------------------ chunk prefix
+// For every list (kv head j, block gb): counters[j][chunk][gb] becomes the number of entries the list gets from
+// earlier chunks, and cnt / len_scan receive the list's length.  A workgroup owns 64 consecutive blocks of one kv
+// head; its four wavefronts take a quarter of the chunks each (sum, exchange through LDS, then prefix), so the
+// column walk is a handful of coalesced row accesses per thread.  grid (ceil(b_cap / 64), hkv), 256 threads.
+__global__ void __launch_bounds__(256) k_chunk_prefix(int32_t* __restrict__ counters, int b_cap, int n_chunks,
+                                                      int n_lists, int32_t* __restrict__ cnt,
+                                                      int32_t* __restrict__ len_scan) {
+  __shared__ int32_t part[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6, j = blockIdx.y;
+  const int gb = blockIdx.x * 64 + lane;
+  const bool live = gb < b_cap;
+  const int per = (n_chunks + 3) / 4;
+  const int c0 = min(q * per, n_chunks), c1 = min(c0 + per, n_chunks);
+  int32_t* col = counters + (size_t)j * n_chunks * b_cap + (live ? gb : 0);
+  int32_t sum = 0;
+  if (live) {
+    int c = c0;
+    for (; c + 8 <= c1; c += 8) {
+      int32_t v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = col[(size_t)(c + i) * b_cap];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sum += v[i];
+    }
+    for (; c < c1; ++c) sum += col[(size_t)c * b_cap];
+  }
+  part[q][lane] = sum;
+  __syncthreads();
+  int32_t run = 0;
+  for (int w = 0; w < q; ++w) run += part[w][lane];
+  if (live) {
+    int c = c0;
+    for (; c + 8 <= c1; c += 8) {
+      int32_t v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = col[(size_t)(c + i) * b_cap];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        col[(size_t)(c + i) * b_cap] = run;
+        run += v[i];
+      }
+    }
+    for (; c < c1; ++c) {
+      const int32_t v = col[(size_t)c * b_cap];
+      col[(size_t)c * b_cap] = run;
+      run += v;
+    }
+    if (q == 3) {
+      const int L = j * b_cap + gb;
+      cnt[L] = run;
+      len_scan[L] = run;
+    }
+  }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) len_scan[n_lists] = 0;
 }
 
 // ------------------------------------------------------------------------------------------------ scan
@@ -186,14 +240,15 @@ static void scan_exclusive(int32_t* a, int64_t n, int32_t* tmp, hipStream_t st) 
 }
 
 // ------------------------------------------------------------------------------------------------ scatter
-// grid (n_chunks, hkv), ONE wavefront per group.  chunk_off holds the scanned counters, i.e. for every
-// (kv head, block, chunk) the position in qent where that chunk's tokens start.  Every kept column costs one
+// grid (n_chunks, hkv), ONE wavefront per group.  off[list] + chunk_off[kv head][chunk][block] is the position in
+// qent where the chunk's tokens of that list start.  Every kept column costs one
 // scattered 8-byte store (the list entry); the positions of a token's columns are collected in LDS and leave
 // as one contiguous row of slotpos.  Dynamic LDS: b_cap u64 masks + b_cap int cursors + 2 * 64*(k+1) ints.
 __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                                 const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
                                                 int bk, int causal, int b_cap, int n_chunks,
-                                                const int32_t* __restrict__ chunk_off, int2* __restrict__ qent,
+                                                const int32_t* __restrict__ chunk_off,
+                                                const int32_t* __restrict__ off, int2* __restrict__ qent,
                                                 const uint32_t* __restrict__ vmask, int32_t* __restrict__ slotpos) {
   extern __shared__ int32_t lds[];
   unsigned long long* mask = reinterpret_cast<unsigned long long*>(lds);
@@ -207,7 +262,7 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
   const int win = gb_hi - gb_lo;
   for (int i = lane; i < win; i += 64) {
     mask[i] = 0ull;
-    cursor[i] = chunk_off[((size_t)j * b_cap + gb_lo + i) * n_chunks + chunk];
+    cursor[i] = off[j * b_cap + gb_lo + i] + chunk_off[((size_t)j * n_chunks + chunk) * b_cap + gb_lo + i];
   }
   __syncthreads();
   int32_t* row = rows + lane * (k + 1);
@@ -293,22 +348,18 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
 }
 
 // ------------------------------------------------------------------------------------------------ finalize
-// cnt/off per list from the scanned counters; number of work units per list for both unit sizes.
-__global__ void k_finalize(const int32_t* __restrict__ chunk_off, int n_lists, int n_chunks, int32_t* __restrict__ cnt,
-                           int32_t* __restrict__ off, int32_t* __restrict__ f_nu, int32_t* __restrict__ b_nu,
-                           int32_t* __restrict__ hdr) {
+// number of work units per list for both unit sizes (off is the scanned list lengths, n_lists + 1 entries)
+__global__ void k_finalize(const int32_t* __restrict__ cnt, const int32_t* __restrict__ off, int n_lists,
+                           int32_t* __restrict__ f_nu, int32_t* __restrict__ b_nu, int32_t* __restrict__ hdr) {
   const int L = blockIdx.x * blockDim.x + threadIdx.x;
   if (L > n_lists) return;
-  const int32_t o = chunk_off[(size_t)L * n_chunks];
-  off[L] = o;
   if (L == n_lists) {
-    hdr[HDR_NPAIRS] = o;
+    hdr[HDR_NPAIRS] = off[n_lists];
     f_nu[L] = 0;
     b_nu[L] = 0;
     return;
   }
-  const int32_t c = chunk_off[(size_t)(L + 1) * n_chunks] - o;
-  cnt[L] = c;
+  const int32_t c = cnt[L];
   f_nu[L] = (c + kFwdUnit - 1) / kFwdUnit;
   b_nu[L] = (c + kBwdUnit - 1) / kBwdUnit;
 }
@@ -340,22 +391,21 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
   { ProfScope ps(KID_INDEX_PREP, st);
   hipLaunchKernelGGL(k_prep, dim3(1), dim3(256), 0, st, cu, L.nseq, L.T, L.bk, L.b_cap, p.blk_base, p.blk_tok0, p.blk_len,
                      p.hdr); }
-  const int64_t nc = L.n_counters + 1;
-  { ProfScope ps(KID_INDEX_ZERO, st);
-  hipLaunchKernelGGL(k_zero, dim3((unsigned)((nc + 1023) / 1024 > 4096 ? 4096 : (nc + 1023) / 1024)), dim3(256), 0, st,
-                     p.chunk_off, nc); }
   { ProfScope ps(KID_INDEX_HIST, st);
   hipLaunchKernelGGL(k_hist, dim3(L.n_chunks, L.hkv), dim3(256), lds_hist, st, idx, cu, p.blk_base, L.nseq, L.T, L.hkv,
                      L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.vmask); }
+  const int nl1 = L.n_lists + 1;
+  { ProfScope ps(KID_INDEX_CHUNK_PREFIX, st);
+  hipLaunchKernelGGL(k_chunk_prefix, dim3((L.b_cap + 63) / 64, L.hkv), dim3(256), 0, st, p.chunk_off, L.b_cap, L.n_chunks,
+                     L.n_lists, p.cnt, p.off); }
   { ProfScope ps(KID_INDEX_SCAN, st);
-  scan_exclusive(p.chunk_off, nc, p.scan_tmp, st); }
+  scan_exclusive(p.off, nl1, p.scan_tmp, st); }
   { ProfScope ps(KID_INDEX_SCATTER, st);
   hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
-                     L.hkv, L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.qent, p.vmask, p.slotpos); }
-  const int nl1 = L.n_lists + 1;
+                     L.hkv, L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.off, p.qent, p.vmask, p.slotpos); }
   { ProfScope ps(KID_INDEX_FINALIZE, st);
-  hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.chunk_off, L.n_lists, L.n_chunks, p.cnt,
-                     p.off, p.f_nu, p.b_nu, p.hdr); }
+  hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.cnt, p.off, L.n_lists, p.f_nu, p.b_nu,
+                     p.hdr); }
   { ProfScope ps(KID_INDEX_SCAN, st);
   scan_exclusive(p.f_nu, nl1, p.scan_tmp, st);
   scan_exclusive(p.b_nu, nl1, p.scan_tmp, st); }
@@ -367,6 +417,7 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
   return hipGetLastError();
 }
 
-int64_t index_scan_tmp_ints(int64_t n_counters) { return scan_tmp_ints(n_counters + 1); }
+// scratch of the scans: the longest scanned array has one entry per list plus one
+int64_t index_scan_tmp_ints(int64_t n_lists) { return scan_tmp_ints(n_lists + 1); }
 
 }  // namespace nsa

@@ -12,7 +12,7 @@ struct Rec {
 std::vector<Rec> g_recs;
 int g_used = 0;
 bool g_on = false;
-const char* const kNames[KID_COUNT] = {"index_prep", "index_zero", "index_hist", "index_scan", "index_scatter",
+const char* const kNames[KID_COUNT] = {"index_prep", "index_chunk_prefix", "index_hist", "index_scan", "index_scatter",
                                        "index_finalize", "index_units", "fwd_main", "fwd_merge", "bwd_delta",
                                        "bwd_main", "bwd_dq_reduce", "bwd_dkv_reduce"};
 }  // namespace
