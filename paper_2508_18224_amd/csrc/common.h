@@ -11,7 +11,7 @@
 
 namespace nsa {
 
-constexpr int kBlock = 64;         // keys per MFMA key tile (B_K = 64 is one tile, B_K = 128 two)
+constexpr int kBlock = 64;         // tokens of the smaller of the two block sizes (B_K = 64 or 2 * 64)
 constexpr int kD = 128;            // head dimension
 constexpr int kChunkTokens = 512;  // token chunk of the inversion histogram / scatter
 constexpr int kFwdUnit = 2048;     // list entries per forward work unit
@@ -42,12 +42,13 @@ struct IndexPtrs {
   int32_t* blk_base;
   int32_t* blk_tok0;
   int32_t* blk_len;
-  int32_t* chunk_off;
-  int32_t* cnt;
-  int32_t* off;
+  int32_t* chunk_off;  // [hkv][n_chunks][b_cap]: entries a list receives from the chunks before this one
+  int32_t* cnt;        // [n_lists] list lengths
+  int32_t* off;        // [n_lists + 1] exclusive scan of cnt: first position of every list in qent
   int2* qent;        // list entries: (token, column of idx it came from)
   uint32_t* vmask;
   int32_t* slotpos;  // [T, hkv, topk]: position in qent of the entry a kept column produced
+  // forward / backward work units: scanned units per list, and per unit its list and first entry
   int32_t *f_nu, *f_list, *f_start, *b_nu, *b_list, *b_start;
   int32_t* scan_tmp;
 };
