@@ -394,7 +394,9 @@ k_bwd_dq_reduce(Problem P, const bf16_t* __restrict__ dqpart, const uint32_t* __
   *reinterpret_cast<uint4*>(dQ + row * kD + 8 * sub) = o;
 }
 
-// grid (n_lists, 2): y = 0 -> dK, 1 -> dV.  Thread handles 4 consecutive channels of 8 keys.
+// grid (n_lists, 2, B_K / 8): y = 0 -> dK, 1 -> dV; z = group of 8 keys, so that the units of a long list (the sink
+// block's list has 32 of them) are walked by B_K / 8 workgroups side by side.  Thread = 4 consecutive channels of
+// one key; the sum runs in unit order.
 __global__ void __launch_bounds__(256)
 k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* __restrict__ blk_tok0,
                  const int32_t* __restrict__ blk_len, const float* __restrict__ dkv_part, bf16_t* __restrict__ dK,
@@ -409,7 +411,8 @@ k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* 
   if (u1 - u0 == 1) return;  // a single unit wrote the final values itself
   bf16_t* out = which ? dV : dK;
   const int d4 = (threadIdx.x & 31) * 4;
-  for (int key = threadIdx.x >> 5; key < blen; key += 8) {
+  const int key = 8 * blockIdx.z + (threadIdx.x >> 5);
+  if (key < blen) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int u = u0; u < u1; ++u) {
       const float4 x =
@@ -459,7 +462,7 @@ hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
     hipLaunchKernelGGL(k_bwd_dq_reduce, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P,
                        (const bf16_t*)dqpart, p.vmask, p.slotpos, p.off, (bf16_t*)dQ); }
     ProfScope ps(KID_BWD_DKV_REDUCE, st);
-    hipLaunchKernelGGL(k_bwd_dkv_reduce, dim3(P.nj * P.b_cap, 2), dim3(256), 0, st, P, p.b_nu, p.blk_tok0, p.blk_len,
+    hipLaunchKernelGGL(k_bwd_dkv_reduce, dim3(P.nj * P.b_cap, 2, P.bk / 8), dim3(256), 0, st, P, p.b_nu, p.blk_tok0, p.blk_len,
                        (const float*)dkv_part, (bf16_t*)dK, (bf16_t*)dV);
   }
   return hipGetLastError();
