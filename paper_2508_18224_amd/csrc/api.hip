@@ -42,8 +42,8 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   if (L.n_chunks < 1) L.n_chunks = 1;
   L.n_counters = (int64_t)L.n_lists * L.n_chunks;
   L.p_max = (int64_t)s->total_tokens * s->hkv * L.topk;
-  L.fwd_units_max = (int32_t)(L.n_lists + L.p_max / kFwdUnit);
-  L.bwd_units_max = (int32_t)(L.n_lists + L.p_max / kBwdUnit);
+  L.unit = work_unit_entries(L.p_max);
+  L.units_max = (int32_t)units_bound(L.hkv, L.b_cap, L.T, L.topk, L.unit);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };
   L.hdr = take(64);
@@ -56,12 +56,9 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.qent = take(8 * (size_t)(L.p_max + 1));
   L.vmask = take(4 * ((size_t)L.T * L.hkv + 1));
   L.slotpos = take(4 * (size_t)(L.p_max + 1));
-  L.f_nu = take(4 * (size_t)(L.n_lists + 1));
-  L.f_list = take(4 * (size_t)(L.fwd_units_max + 1));
-  L.f_start = take(4 * (size_t)(L.fwd_units_max + 1));
-  L.b_nu = take(4 * (size_t)(L.n_lists + 1));
-  L.b_list = take(4 * (size_t)(L.bwd_units_max + 1));
-  L.b_start = take(4 * (size_t)(L.bwd_units_max + 1));
+  L.u_nu = take(4 * (size_t)(L.n_lists + 1));
+  L.u_list = take(4 * (size_t)(L.units_max + 1));
+  L.u_start = take(4 * (size_t)(L.units_max + 1));
   L.scan_tmp = take(4 * (size_t)index_scan_tmp_ints(L.n_lists));
   L.total = o;
   return L;
@@ -78,6 +75,7 @@ static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
   P.causal = s->causal ? 1 : 0;
   P.b_cap = L.b_cap;
   P.bk = L.bk;
+  P.unit = L.unit;
   P.g_magic = (uint32_t)(((uint64_t)1 << 32) / (uint64_t)P.g + 1);  // wraps to 1 for g = 1, where it is unused
   P.j0 = 0;
   P.nj = s->hkv;
@@ -99,7 +97,7 @@ static size_t fwd_ws_bytes(const nsa_sel_shape* s, int nj) {
 static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L, int nj) {
   const size_t rows = partial_rows(s, nj);
   return align256(rows * kD * 2) + align256((size_t)s->total_tokens * s->hq * 8) +
-         align256((size_t)bwd_units_bound(nj, L.b_cap, L.T, L.topk) * 2 * L.bk * kD * 4);
+         align256((size_t)units_bound(nj, L.b_cap, L.T, L.topk, L.unit) * 2 * L.bk * kD * 4);
 }
 
 // Largest number of KV heads per pass that `bytes` can hold; 0 when not even one fits.

@@ -5,7 +5,7 @@
 //
 //   k_bwd_delta       delta[t,h] = <dO[t,h], O[t,h]>, stored next to LSE[t,h] log2(e) as one 8-byte pair so that the
 //                     main kernel fetches both row statistics with one gather
-//   k_bwd_tiled<NKB>  one work unit = (kv head j, KV block i, up to kBwdUnit list entries); NKB = B_K / 32.  With
+//   k_bwd_tiled<NKB>  one work unit = (kv head j, KV block i, up to P.unit list entries); NKB = B_K / 32.  With
 //                     B_K = 64: four wavefronts and half of a CU's LDS, so two workgroups share a CU and cover each
 //                     other's barriers and waits; with B_K = 128: eight wavefronts, one workgroup per CU.  The waves
 //                     share tiles of 64 gathered rows and take three roles per tile (see the comment above the
@@ -130,7 +130,7 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
   const int gb = L - j * P.b_cap;
   const int e0 = u_start[u];
   const int pos0 = off[P.j0 * P.b_cap];
-  const int ne = min(kBwdUnit, off[L + 1] - e0);
+  const int ne = min(P.unit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int col = lane & 31, qh = lane >> 5;  // not const: made opaque at the top of the tile loop
@@ -451,18 +451,18 @@ hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
     Problem P = P0;
     P.j0 = j0;
     P.nj = min(heads_per_pass, P0.hkv - j0);
-    const unsigned units_max = (unsigned)bwd_units_bound(P.nj, P.b_cap, P.T, P.topk);
+    const unsigned units_max = (unsigned)units_bound(P.nj, P.b_cap, P.T, P.topk, P.unit);
     const int64_t rows = (int64_t)P.T * P.nj * P.g;
     { ProfScope ps(KID_BWD_MAIN, st);
     hipLaunchKernelGGL(main_kernel, dim3(units_max), dim3(main_threads), main_lds, st, P, (const bf16_t*)Q,
-                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, (const float2*)delta, p.b_list,
-                       p.b_start, p.off, p.blk_tok0, p.blk_len, p.qent, p.b_nu, (bf16_t*)dqpart, dkv_part,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, (const float2*)delta, p.u_list,
+                       p.u_start, p.off, p.blk_tok0, p.blk_len, p.qent, p.u_nu, (bf16_t*)dqpart, dkv_part,
                        (bf16_t*)dK, (bf16_t*)dV); }
     { ProfScope ps(KID_BWD_DQ_REDUCE, st);
     hipLaunchKernelGGL(k_bwd_dq_reduce, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P,
                        (const bf16_t*)dqpart, p.vmask, p.slotpos, p.off, (bf16_t*)dQ); }
     ProfScope ps(KID_BWD_DKV_REDUCE, st);
-    hipLaunchKernelGGL(k_bwd_dkv_reduce, dim3(P.nj * P.b_cap, 2, P.bk / 8), dim3(256), 0, st, P, p.b_nu, p.blk_tok0, p.blk_len,
+    hipLaunchKernelGGL(k_bwd_dkv_reduce, dim3(P.nj * P.b_cap, 2, P.bk / 8), dim3(256), 0, st, P, p.u_nu, p.blk_tok0, p.blk_len,
                        (const float*)dkv_part, (bf16_t*)dK, (bf16_t*)dV);
   }
   return hipGetLastError();

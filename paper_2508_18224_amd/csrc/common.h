@@ -14,8 +14,8 @@ namespace nsa {
 constexpr int kBlock = 64;         // tokens of the smaller of the two block sizes (B_K = 64 or 2 * 64)
 constexpr int kD = 128;            // head dimension
 constexpr int kChunkTokens = 512;  // token chunk of the inversion histogram / scatter
-constexpr int kFwdUnit = 2048;     // list entries per forward work unit
-constexpr int kBwdUnit = 2048;     // list entries per backward work unit
+constexpr int kMaxUnit = 2048;     // most list entries of one work unit (the size used for long inputs)
+constexpr int kMinUnit = 256;
 constexpr int kMaxTopk = 32;
 constexpr int kSlotBatch = 4;      // slots of a row the two reduction kernels gather at a time
 
@@ -28,14 +28,15 @@ struct IndexLayout {
   int32_t n_chunks;     // ceil(T / kChunkTokens)
   int64_t n_counters;   // n_lists * n_chunks
   int64_t p_max;        // T * hkv * topk
-  int32_t fwd_units_max, bwd_units_max;
+  int32_t unit;         // list entries per work unit of the attention kernels (see work_unit_entries)
+  int32_t units_max;    // upper bound of the number of work units
   size_t hdr, blk_base, blk_tok0, blk_len, chunk_off, cnt, off, qent, vmask, slotpos;
-  size_t f_nu, f_list, f_start, b_nu, b_list, b_start, scan_tmp;
+  size_t u_nu, u_list, u_start, scan_tmp;
   size_t total;
 };
 
 // hdr words
-enum { HDR_BTOT = 0, HDR_NPAIRS = 1, HDR_FUNITS = 2, HDR_BUNITS = 3 };
+enum { HDR_BTOT = 0, HDR_NPAIRS = 1, HDR_UNITS = 2 };
 
 struct IndexPtrs {
   int32_t* hdr;
@@ -48,8 +49,8 @@ struct IndexPtrs {
   int2* qent;        // list entries: (token, column of idx it came from)
   uint32_t* vmask;
   int32_t* slotpos;  // [T, hkv, topk]: position in qent of the entry a kept column produced
-  // forward / backward work units: scanned units per list, and per unit its list and first entry
-  int32_t *f_nu, *f_list, *f_start, *b_nu, *b_list, *b_start;
+  // work units (shared by forward and backward): scanned units per list, and per unit its list and first entry
+  int32_t *u_nu, *u_list, *u_start;
   int32_t* scan_tmp;
 };
 
@@ -66,12 +67,9 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
   r.qent = (int2*)(p + L.qent);
   r.vmask = (uint32_t*)(p + L.vmask);
   r.slotpos = (int32_t*)(p + L.slotpos);
-  r.f_nu = (int32_t*)(p + L.f_nu);
-  r.f_list = (int32_t*)(p + L.f_list);
-  r.f_start = (int32_t*)(p + L.f_start);
-  r.b_nu = (int32_t*)(p + L.b_nu);
-  r.b_list = (int32_t*)(p + L.b_list);
-  r.b_start = (int32_t*)(p + L.b_start);
+  r.u_nu = (int32_t*)(p + L.u_nu);
+  r.u_list = (int32_t*)(p + L.u_list);
+  r.u_start = (int32_t*)(p + L.u_start);
   r.scan_tmp = (int32_t*)(p + L.scan_tmp);
   return r;
 }
@@ -80,17 +78,24 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
 struct Problem {
   int32_t T, nseq, hq, hkv, g, topk, causal, b_cap, bk;
   uint32_t g_magic;  // floor(2^32 / g) + 1: row / g as one multiply-high (see div_g); unused when g == 1
+  int32_t unit;    // list entries per work unit
   int32_t j0, nj;  // KV heads [j0, j0 + nj) handled by this launch (all of them unless the workspace is capped)
   float scale;
 };
 
-// Upper bounds of the work units of nj KV heads (one per non-empty list plus one per full unit of entries);
-// the real counts are only known on the device.
-inline int64_t fwd_units_bound(int nj, int b_cap, int T, int topk) {
-  return (int64_t)nj * b_cap + (int64_t)nj * T * topk / kFwdUnit + 1;
+// List entries per work unit.  Long inputs use kMaxUnit (splitting lists further only adds dK/dV partial sums);
+// short inputs use smaller units so that the ~512 workgroup slots of the chip each get several units and the sink
+// block's list (every token) does not become one slot's whole share.  Sizes swept on the paper's 8K .. 64K grid.
+inline int work_unit_entries(int64_t total_pairs) {
+  int u = kMinUnit;
+  while (u < kMaxUnit && (int64_t)u * 2 * 2048 <= total_pairs) u *= 2;  // largest power of two <= pairs / 2048
+  return u;
 }
-inline int64_t bwd_units_bound(int nj, int b_cap, int T, int topk) {
-  return (int64_t)nj * b_cap + (int64_t)nj * T * topk / kBwdUnit + 1;
+
+// Upper bound of the work units of nj KV heads (one per non-empty list plus one per full unit of entries); the
+// real count is only known on the device.
+inline int64_t units_bound(int nj, int b_cap, int T, int topk, int unit) {
+  return (int64_t)nj * b_cap + (int64_t)nj * T * topk / unit + 1;
 }
 
 // ---- optional per-kernel timing (off unless nsa_sel_profile_enable was called) ---------------------------

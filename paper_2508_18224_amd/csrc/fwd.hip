@@ -1,7 +1,7 @@
 // Forward selected-block attention for gfx950 (paper Sec. 3.2, the KV-outer "token selection" step and the
 // reduction step; Eq. (2), c = sel).
 //
-// k_fwd_main (B_K = 64): one work unit = (kv head j, KV block i, up to kFwdUnit entries of the block's query list).
+// k_fwd_main (B_K = 64): one work unit = (kv head j, KV block i, up to P.unit entries of the block's query list).
 //   The block's K_i stays in registers for the whole unit (the A operand of S^T = K_i Q^T) and V_i^T sits in LDS,
 //   transposed and key-permuted once per unit (the A operand of O^T = V_i^T P^T), so the inner loop reads no K/V
 //   from memory: each wavefront walks tiles of 32 query rows (row = (list entry, head of the group), flattened so
@@ -50,7 +50,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
            float* __restrict__ lse_part) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kD * kVtStride];
   __shared__ __attribute__((aligned(16))) bf16_t tiles[4][32 * kTileStride];
-  __shared__ int32_t ent[kFwdUnit];  // tokens of the unit's list entries
+  __shared__ int32_t ent[kMaxUnit];  // tokens of the unit's list entries
   // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
   const int u = nu_scan[P.j0 * P.b_cap] + blockIdx.x;
   if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
@@ -59,7 +59,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int gb = L - j * P.b_cap;
   const int e0 = u_start[u];
   const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
-  const int ne = min(kFwdUnit, off[L + 1] - e0);
+  const int ne = min(P.unit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
   const int crow = lane >> 4, cchunk = (lane & 15) * 8;  // coalesced layout: 16 lanes per row, 4 rows per access
@@ -227,7 +227,7 @@ constexpr int kF128K = 0;
 constexpr int kF128V = kF128K + 128 * kPitch128 * 2;
 constexpr int kF128Tiles = kF128V + 128 * kPitch128 * 2;
 constexpr int kF128Ent = kF128Tiles + kWaves128 * 32 * kTileStride * 2;
-constexpr int kF128Bytes = kF128Ent + kFwdUnit * 4;
+constexpr int kF128Bytes = kF128Ent + kMaxUnit * 4;
 static_assert(kF128Bytes <= 160 * 1024, "forward 128-key tile set must fit the CU's LDS");
 
 // ds_read_b64_tr_b16: every lane passes the address of 8 bytes (four 16-bit elements); within each group of 16
@@ -258,7 +258,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   const int gb = L - j * P.b_cap;
   const int e0 = u_start[u];
   const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
-  const int ne = min(kFwdUnit, off[L + 1] - e0);
+  const int ne = min(P.unit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int col = lane & 31, qh = lane >> 5;                 // not const: see the top of the tile loop
@@ -499,16 +499,16 @@ hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
     P.j0 = j0;
     P.nj = min(heads_per_pass, P0.hkv - j0);
     // upper bound of the work units of the pass (the real count is only known on the device)
-    const unsigned units_max = (unsigned)fwd_units_bound(P.nj, P.b_cap, P.T, P.topk);
+    const unsigned units_max = (unsigned)units_bound(P.nj, P.b_cap, P.T, P.topk, P.unit);
     if (P.bk == 128) {
       ProfScope ps(KID_FWD_MAIN, st);
       hipLaunchKernelGGL(k_fwd_main128, dim3(units_max), dim3(64 * kWaves128), kF128Bytes, st, P, (const bf16_t*)Q,
-                         (const bf16_t*)K, (const bf16_t*)V, p.f_nu, p.f_list, p.f_start, p.off, p.blk_tok0,
+                         (const bf16_t*)K, (const bf16_t*)V, p.u_nu, p.u_list, p.u_start, p.off, p.blk_tok0,
                          p.blk_len, p.qent, (bf16_t*)opart, lse_part);
     } else {
       ProfScope ps(KID_FWD_MAIN, st);
       hipLaunchKernelGGL(k_fwd_main, dim3(units_max), dim3(256), 0, st, P, (const bf16_t*)Q, (const bf16_t*)K,
-                         (const bf16_t*)V, p.f_nu, p.f_list, p.f_start, p.off, p.blk_tok0, p.blk_len, p.qent,
+                         (const bf16_t*)V, p.u_nu, p.u_list, p.u_start, p.off, p.blk_tok0, p.blk_len, p.qent,
                          (bf16_t*)opart, lse_part);
     }
     const int64_t rows = (int64_t)P.T * P.nj * P.g;

@@ -348,20 +348,18 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
 }
 
 // ------------------------------------------------------------------------------------------------ finalize
-// number of work units per list for both unit sizes (off is the scanned list lengths, n_lists + 1 entries)
-__global__ void k_finalize(const int32_t* __restrict__ cnt, const int32_t* __restrict__ off, int n_lists,
-                           int32_t* __restrict__ f_nu, int32_t* __restrict__ b_nu, int32_t* __restrict__ hdr) {
+// number of work units per list (off is the scanned list lengths, n_lists + 1 entries)
+__global__ void k_finalize(const int32_t* __restrict__ cnt, const int32_t* __restrict__ off, int n_lists, int unit,
+                           int32_t* __restrict__ u_nu, int32_t* __restrict__ hdr) {
   const int L = blockIdx.x * blockDim.x + threadIdx.x;
   if (L > n_lists) return;
   if (L == n_lists) {
     hdr[HDR_NPAIRS] = off[n_lists];
-    f_nu[L] = 0;
-    b_nu[L] = 0;
+    u_nu[L] = 0;
     return;
   }
   const int32_t c = cnt[L];
-  f_nu[L] = (c + kFwdUnit - 1) / kFwdUnit;
-  b_nu[L] = (c + kBwdUnit - 1) / kBwdUnit;
+  u_nu[L] = (c + unit - 1) / unit;
 }
 
 // nu_scan is the exclusive scan of units per list (n_lists + 1 entries).
@@ -404,16 +402,13 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
   hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
                      L.hkv, L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.off, p.qent, p.vmask, p.slotpos); }
   { ProfScope ps(KID_INDEX_FINALIZE, st);
-  hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.cnt, p.off, L.n_lists, p.f_nu, p.b_nu,
+  hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.cnt, p.off, L.n_lists, L.unit, p.u_nu,
                      p.hdr); }
   { ProfScope ps(KID_INDEX_SCAN, st);
-  scan_exclusive(p.f_nu, nl1, p.scan_tmp, st);
-  scan_exclusive(p.b_nu, nl1, p.scan_tmp, st); }
+  scan_exclusive(p.u_nu, nl1, p.scan_tmp, st); }
   { ProfScope ps(KID_INDEX_UNITS, st);
-  hipLaunchKernelGGL(k_units, dim3((L.n_lists + 255) / 256), dim3(256), 0, st, p.f_nu, p.off, L.n_lists, kFwdUnit,
-                     p.f_list, p.f_start, p.hdr + HDR_FUNITS);
-  hipLaunchKernelGGL(k_units, dim3((L.n_lists + 255) / 256), dim3(256), 0, st, p.b_nu, p.off, L.n_lists, kBwdUnit,
-                     p.b_list, p.b_start, p.hdr + HDR_BUNITS); }
+  hipLaunchKernelGGL(k_units, dim3((L.n_lists + 255) / 256), dim3(256), 0, st, p.u_nu, p.off, L.n_lists, L.unit,
+                     p.u_list, p.u_start, p.hdr + HDR_UNITS); }
   return hipGetLastError();
 }
 
