@@ -54,3 +54,11 @@ def test_list_length_at_unit_boundaries(n_tokens, g):
     w.idx[:] = -1
     w.idx[:, :, 1] = 0
     _check(w)
+
+
+@pytest.mark.parametrize("n_tokens,g,block", [(1, 1, 64), (2, 8, 64), (63, 3, 64), (64, 4, 128), (65, 1, 128), (129, 8, 128)])
+def test_very_short_sequences(n_tokens, g, block):
+    """Sequences shorter than, equal to and just past one block (one tile, one chunk, one work unit)."""
+    print("short case", n_tokens, g, block, flush=True)
+    w = wl.realise(wl.Workload("s", [n_tokens], hq=2 * g, hkv=2, topk=3, block=block, seed=n_tokens + g))
+    _check(w)
