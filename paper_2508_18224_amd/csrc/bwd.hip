@@ -256,6 +256,8 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
       {  // role keys/chans: dV_i += P^T dO, dK_i += dS^T Q for keys 32 kb2.., channels 64 hf + 32 cb..
         int tr_row = tr_lane + 64 * hf;
         asm volatile("" : "+v"(tr_row));
+        const bf16_t* do_tr = dOs + tr_row;  // one base per tile: the reads below differ by immediate offsets only
+        const bf16_t* q_tr = Qs + tr_row;
         const bf16_t* parow = Pt + (32 * kb2 + col) * kPStride + 8 * qh;
         const bf16_t* sarow = dSt + (32 * kb2 + col) * kPStride + 8 * qh;
 #pragma unroll
@@ -264,10 +266,10 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
           const bf16x8 sa = *reinterpret_cast<const bf16x8*>(sarow + 16 * qs);
 #pragma unroll
           for (int cb = 0; cb < 2; ++cb) {
-            const bf16x4 d0 = lds_read_tr(&dOs[16 * qs * kRowStride + tr_row + 32 * cb]);
-            const bf16x4 d1 = lds_read_tr(&dOs[(16 * qs + 4) * kRowStride + tr_row + 32 * cb]);
-            const bf16x4 q0 = lds_read_tr(&Qs[16 * qs * kRowStride + tr_row + 32 * cb]);
-            const bf16x4 q1 = lds_read_tr(&Qs[(16 * qs + 4) * kRowStride + tr_row + 32 * cb]);
+            const bf16x4 d0 = lds_read_tr(do_tr + (16 * qs * kRowStride + 32 * cb));
+            const bf16x4 d1 = lds_read_tr(do_tr + ((16 * qs + 4) * kRowStride + 32 * cb));
+            const bf16x4 q0 = lds_read_tr(q_tr + (16 * qs * kRowStride + 32 * cb));
+            const bf16x4 q1 = lds_read_tr(q_tr + ((16 * qs + 4) * kRowStride + 32 * cb));
             const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
             const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
             dvacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc[cb], 0, 0, 0);
@@ -284,15 +286,17 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
         int tr_key = tr_lane + kCW * kb;
         int tr_ds = tr_lane_p + 32 * rb;
         asm volatile("" : "+v"(tr_key), "+v"(tr_ds));
+        const bf16_t* k_tr = Ks + tr_key;
+        const bf16_t* ds_tr = dSt + tr_ds;
 #pragma unroll
         for (int sp = 0; sp < kKeys / 16; ++sp) {
-          const bf16x4 b0 = lds_read_tr(&dSt[16 * sp * kPStride + tr_ds]);
-          const bf16x4 b1 = lds_read_tr(&dSt[(16 * sp + 4) * kPStride + tr_ds]);
+          const bf16x4 b0 = lds_read_tr(ds_tr + 16 * sp * kPStride);
+          const bf16x4 b1 = lds_read_tr(ds_tr + (16 * sp + 4) * kPStride);
           const bf16x8 dsb = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
           for (int db = 0; db < kNDB; ++db) {
-            const bf16x4 a0 = lds_read_tr(&Ks[16 * sp * kRowStride + tr_key + 32 * db]);
-            const bf16x4 a1 = lds_read_tr(&Ks[(16 * sp + 4) * kRowStride + tr_key + 32 * db]);
+            const bf16x4 a0 = lds_read_tr(k_tr + (16 * sp * kRowStride + 32 * db));
+            const bf16x4 a1 = lds_read_tr(k_tr + ((16 * sp + 4) * kRowStride + 32 * db));
             const bf16x8 ktf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
             dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsb, dqacc[db], 0, 0, 0);
           }
