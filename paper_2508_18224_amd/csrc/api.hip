@@ -18,6 +18,7 @@ static int check_shape(const nsa_sel_shape* s) {
   if (s->d != kD || (s->block != kBlock && s->block != 2 * kBlock)) return NSA_SEL_EUNSUPPORTED;
   if (s->topk < 1 || s->topk > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
   if (s->nseq > (1 << 20)) return NSA_SEL_EUNSUPPORTED;
+  if ((int64_t)s->total_tokens * s->hq >= ((int64_t)1 << 31)) return NSA_SEL_EUNSUPPORTED;  // 32-bit row indices
   const int64_t b_cap = (int64_t)s->total_tokens / s->block + s->nseq;
   // LDS tables of the inversion (12 bytes per block) must fit in one CU's 160 KB
   if (b_cap * 12 + 2 * 64 * (int64_t)(s->topk + 1) * 4 > 160 * 1024) return NSA_SEL_EUNSUPPORTED;
@@ -76,7 +77,7 @@ static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
   P.b_cap = L.b_cap;
   P.bk = L.bk;
   P.unit = L.unit;
-  P.g_magic = (uint32_t)(((uint64_t)1 << 32) / (uint64_t)P.g + 1);  // wraps to 1 for g = 1, where it is unused
+  P.g_magic = P.g == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint64_t)P.g + 1);
   P.j0 = 0;
   P.nj = s->hkv;
   P.scale = s->scale > 0.f ? s->scale : 0.08838834764831845f;  // 1/sqrt(128)

@@ -163,7 +163,6 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
     }
 
   const float c2 = P.scale * 1.4426950408889634f;
-  const size_t hq = P.hq;
   const int hbase = j * P.g;
   const int grp = lane >> 4, sl = lane & 15;
   // this lane's share of a transposing read of four rows x 16 columns (see lds_read_tr), for the two row pitches
@@ -185,13 +184,15 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
     for (int i = 0; i < kNP; ++i) {
       const int r = min(tile0 + 32 * rb + kRPP * i + srow, rows_end - 1);
       const int e = div_g(r, P.g, P.g_magic);
-      const size_t o = ((size_t)ent[e - seg0] * hq + hbase + (r - e * P.g)) * kD + schunk;
+      // (token, head) row index in 32 bits (total_tokens * hq < 2^31 is checked on the host), widened once
+      const uint32_t grow = (uint32_t)ent[e - seg0] * (uint32_t)P.hq + (uint32_t)(hbase + (r - e * P.g));
+      const size_t o = (size_t)grow * kD + schunk;
       qc[i] = *reinterpret_cast<const u32x4*>(Q + o);
       dc[i] = *reinterpret_cast<const u32x4*>(dO + o);
     }
     const int rc = min(tile0 + 32 * rb + col, rows_end - 1);
     const int ec = div_g(rc, P.g, P.g_magic);
-    const float2 st = stats[(size_t)ent[ec - seg0] * hq + hbase + (rc - ec * P.g)];  // (LSE in log2 domain, delta)
+    const float2 st = stats[(uint32_t)ent[ec - seg0] * (uint32_t)P.hq + (uint32_t)(hbase + (rc - ec * P.g))];  // (LSE in log2 domain, delta)
     lse2_n = st.x;
     dl_n = st.y;
   };

@@ -77,7 +77,7 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
 // Problem description handed to the attention kernels.
 struct Problem {
   int32_t T, nseq, hq, hkv, g, topk, causal, b_cap, bk;
-  uint32_t g_magic;  // floor(2^32 / g) + 1: row / g as one multiply-high (see div_g); unused when g == 1
+  uint32_t g_magic;  // floor(2^32 / g) + 1, or 0 when g == 1: row / g as one multiply-high (see div_g)
   int32_t unit;    // list entries per work unit
   int32_t j0, nj;  // KV heads [j0, j0 + nj) handled by this launch (all of them unless the workspace is capped)
   float scale;
@@ -155,8 +155,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 
 // r / g for 0 <= r < 2^20 and g in [1, 8] without an integer division: the error of the rounded-up reciprocal,
 // r (magic - 2^32 / g) < r, stays far below 2^32 / g, so the high word of the product is the exact quotient.
+// g = 1 has no 32-bit reciprocal; its magic is 0 and r is added instead (a select, not a branch).
 __device__ __forceinline__ int div_g(int r, int g, uint32_t g_magic) {
-  return g == 1 ? r : (int)(((uint64_t)(uint32_t)r * g_magic) >> 32);
+  return (int)(((uint64_t)(uint32_t)r * g_magic) >> 32) + (g == 1 ? r : 0);
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }

@@ -92,7 +92,6 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   if (wave >= n_tiles) return;  // no block-wide barrier below this point
   const float c2 = P.scale * 1.4426950408889634f;  // scores in the log2 domain
   bf16_t* tile_lds = tiles[wave];
-  const size_t hq = P.hq;
   const int hbase = j * P.g;
 
   // gather the 32 rows of Q of a tile in coalesced form (a row = 16 lanes x 16 bytes, 4 rows per access)
@@ -102,7 +101,9 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       // rows past the end of the list re-read the last row: they are masked out below and never stored
       const int r = min(tile * 32 + 4 * i + crow, rows_total - 1);
       const int e = div_g(r, P.g, P.g_magic);
-      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)ent[e] * hq + hbase + (r - e * P.g)) * kD + cchunk);
+      // (token, head) row index in 32 bits (total_tokens * hq < 2^31 is checked on the host), widened once
+      const uint32_t grow = (uint32_t)ent[e] * (uint32_t)P.hq + (uint32_t)(hbase + (r - e * P.g));
+      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)grow * kD + cchunk));
     }
   };
 
@@ -284,7 +285,6 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   const int n_tiles = (rows_total + 31) >> 5;
   if (wave >= n_tiles) return;  // no block-wide barrier below this point
   const float c2 = P.scale * 1.4426950408889634f;
-  const size_t hq = P.hq;
   const int hbase = j * P.g;
   // this lane's share of a transposing read of four key rows x 16 channels; lane half qh = grp / 2 holds keys
   // k0 + 4 qh + {0..3} (first read) and the same + 8 (second read) of contraction step sp, k0 = 32 (sp/2) + 16 (sp&1)
@@ -298,7 +298,9 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
       // rows past the end of the list re-read the last row: they are masked out below and never stored
       const int r = min(tile * 32 + 4 * i + crow, rows_total - 1);
       const int e = div_g(r, P.g, P.g_magic);
-      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)ent[e] * hq + hbase + (r - e * P.g)) * kD + cchunk);
+      // (token, head) row index in 32 bits (total_tokens * hq < 2^31 is checked on the host), widened once
+      const uint32_t grow = (uint32_t)ent[e] * (uint32_t)P.hq + (uint32_t)(hbase + (r - e * P.g));
+      qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)grow * kD + cchunk));
     }
   };
   issue_q(wave);
