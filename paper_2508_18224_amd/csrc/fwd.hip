@@ -111,12 +111,13 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       *reinterpret_cast<u32x4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
+    // this wave's next tile: its rows fly during the compute (issued before anything waits on the LDS)
+    if (tile + 4 < n_tiles) issue_q(tile + 4, qc);
     wave_sync();
     bf16x8 qf[8];
 #pragma unroll
     for (int s = 0; s < 8; ++s)
       qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kTileStride + 16 * s + 8 * qh]);
-    if (tile + 4 < n_tiles) issue_q(tile + 4, qc);  // this wave's next tile: its rows fly during the compute
 
     f32x16 sacc[2];
 #pragma unroll
@@ -311,12 +312,12 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       *reinterpret_cast<u32x4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
+    if (tile + kWaves128 < n_tiles) issue_q(tile + kWaves128);  // next rows fly during this tile's compute
     wave_sync();
     bf16x8 qf[8];
 #pragma unroll
     for (int s = 0; s < 8; ++s)
       qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kTileStride + 16 * s + 8 * qh]);
-    if (tile + kWaves128 < n_tiles) issue_q(tile + kWaves128);  // next rows fly during this tile's compute
 
     f32x16 sacc[4];
 #pragma unroll
