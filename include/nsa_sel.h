@@ -104,6 +104,10 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
  * entries), clears the record and returns the number of kinds written (or a negative code).  Not thread-safe;
  * launches of a group that consists of several small kernels (the scans) are timed as one. */
 int nsa_sel_profile_enable(int capacity);
+/* Restricts the recording to some kernel kinds: bit i of `mask` stands for the i-th name nsa_sel_profile_collect
+ * reports (all bits set by default).  An event pair costs a few microseconds on the stream, so a benchmark that
+ * times whole steps records only the kernels it needs inside its timed region. */
+int nsa_sel_profile_select(unsigned mask);
 int nsa_sel_profile_collect(int max_kernels, const char** names, float* total_ms, int* calls);
 
 /* Measurement aid: a plain streaming copy kernel (k_calib_copy) that reads `bytes` and writes `bytes`

@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
 _lib = None
 
 SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_workspace_bytes_min", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd",
-           "nsa_sel_profile_enable", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_mfma_probe", "nsa_sel_strerror"]
+           "nsa_sel_profile_enable", "nsa_sel_profile_select", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_mfma_probe", "nsa_sel_strerror"]
 
 
 class NsaSelError(RuntimeError):
@@ -40,6 +40,7 @@ def lib():
         L.nsa_sel_fwd.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, sz, vp]
         L.nsa_sel_bwd.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, sz, vp]
         L.nsa_sel_profile_enable.argtypes = [C.c_int]
+        L.nsa_sel_profile_select.argtypes = [C.c_uint]
         L.nsa_sel_profile_collect.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                               C.POINTER(C.c_int)]
         L.nsa_sel_calibration_copy.argtypes = [vp, vp, sz, vp]
@@ -111,6 +112,19 @@ def nsa_sel_bwd(shape, q, k, v, o, lse, do, cu, index_ws, dq, dk, dv, ws):
 
 def profile_enable(capacity: int):
     _check(lib().nsa_sel_profile_enable(int(capacity)), "nsa_sel_profile_enable")
+
+
+def profile_select(names=None):
+    """Record only the named kernel kinds (None: all).  Names are those profile_collect reports; call it before
+    recording starts (it drops launches recorded so far)."""
+    if names is None:
+        mask = 0xFFFFFFFF
+    else:
+        order = list(profile_collect())
+        mask = 0
+        for nm in names:
+            mask |= 1 << order.index(nm)
+    _check(lib().nsa_sel_profile_select(mask), "nsa_sel_profile_select")
 
 
 def profile_collect():

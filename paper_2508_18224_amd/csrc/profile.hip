@@ -12,13 +12,14 @@ struct Rec {
 std::vector<Rec> g_recs;
 int g_used = 0;
 bool g_on = false;
+unsigned g_mask = ~0u;  // kernel kinds that are recorded (bit = index in kNames)
 const char* const kNames[KID_COUNT] = {"index_prep", "index_chunk_prefix", "index_hist", "index_scan", "index_scatter",
                                        "index_finalize", "index_units", "fwd_main", "fwd_merge", "bwd_delta",
                                        "bwd_main", "bwd_dq_reduce", "bwd_dkv_reduce"};
 }  // namespace
 
 ProfScope::ProfScope(int kid, hipStream_t stream) : slot(-1), st(stream) {
-  if (!g_on || g_used >= (int)g_recs.size()) return;
+  if (!g_on || !((g_mask >> kid) & 1u) || g_used >= (int)g_recs.size()) return;
   slot = g_used++;
   g_recs[slot].kid = kid;
   (void)hipEventRecord(g_recs[slot].a, st);
@@ -94,6 +95,11 @@ int nsa_sel_profile_enable(int capacity) {
     if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return NSA_SEL_EHIP;
   }
   g_on = true;
+  return NSA_SEL_OK;
+}
+
+int nsa_sel_profile_select(unsigned mask) {
+  g_mask = mask;
   return NSA_SEL_OK;
 }
 
