@@ -251,3 +251,53 @@ def draw_adversarial_indices(rng: np.random.Generator, seqlens: Sequence[int], h
         tab = np.where(dup, np.roll(tab, 1, axis=2), tab)
         per_seq.append(tab)
     return np.concatenate(per_seq, axis=0).astype(np.int32)
+
+
+# ----------------------------------------------------------------------------- block scores (input of the selection step)
+def draw_block_scores(seed: int, seqlens: Sequence[int], hkv: int, block: int = BLOCK, *, kind: str = "heavy",
+                      stride: Optional[int] = None, trap_future: bool = True) -> np.ndarray:
+    """float32 [total_tokens, hkv, stride] block-importance scores, stride >= blocks of the longest sequence.
+
+    The paper publishes no score data; the recipe imitates what the compression branch of NSA hands over
+    (attention mass per block, summed over the heads of a group): positive, heavy-tailed, with more mass on
+    recent blocks.
+      'heavy'  exp(1.5 z) * (1 + 2 exp(-(cur - b) / 8)), z standard normal
+      'ties'   the same, quantised to 8 levels, so that most comparisons are ties
+      'wild'   standard normal with a sprinkle of +-inf, NaN, +-0 and denormals
+    With trap_future the columns of blocks after the token's own block hold huge values: a causal selection must
+    never read them.  Every slab of 2048 tokens has its own generator, like the bf16 tensors."""
+    T = int(sum(seqlens))
+    nb = max(-(-int(L) // block) for L in seqlens)
+    stride = nb if stride is None else stride
+    assert stride >= nb
+    cu = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int64)
+    out = np.empty((T, hkv, stride), dtype=np.float32)
+    cols = np.arange(stride, dtype=np.int64)
+
+    def work(t0: int):
+        t1 = min(t0 + _SLAB_TOKENS, T)
+        r = np.random.default_rng([seed, 7, t0 // _SLAB_TOKENS])
+        z = r.standard_normal((t1 - t0, hkv, stride), dtype=np.float32)
+        tok = np.arange(t0, t1, dtype=np.int64)
+        s = np.searchsorted(cu, tok, side="right") - 1
+        cur = ((tok - cu[s]) // block)[:, None, None]
+        if kind in ("heavy", "ties"):
+            age = np.maximum(cur - cols[None, None, :], 0).astype(np.float32)
+            x = np.exp(np.float32(1.5) * z) * (1 + 2 * np.exp(-age / np.float32(8)))
+            if kind == "ties":
+                x = np.floor(np.minimum(x, 7.0))
+        elif kind == "wild":
+            x = z.copy()
+            u = r.random((t1 - t0, hkv, stride))
+            for lo, val in ((0.00, np.inf), (0.03, -np.inf), (0.06, np.nan), (0.09, 0.0), (0.12, -0.0),
+                            (0.15, 1e-42), (0.18, -1e-42)):
+                x[(u >= lo) & (u < lo + 0.03)] = val
+        else:
+            raise KeyError(kind)
+        if trap_future:
+            x = np.where(cols[None, None, :] > cur, np.float32(3e38), x)
+        out[t0:t1] = x.astype(np.float32)
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        list(pool.map(work, range(0, T, _SLAB_TOKENS)))
+    return out
