@@ -96,6 +96,23 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
                 const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws,
                 size_t index_bytes, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
 
+/* The step in front of the path: block scores -> selection tensor, on the device, so that nsa_sel_build_index /
+ * nsa_sel_fwd can consume idx without a host round trip.  The paper takes the selection tensor T as given
+ * (Sec. 2.2) and notes only that block 0, the attention sink, is selected by every token (App. E); the rule used
+ * here is: for token t (own block cur, sequence of b_s blocks) and KV head j,
+ *   visible = blocks b < b_s, and b <= cur when shape->causal;
+ *   forced  = the first n_sink blocks, then the n_local most recent ones (cur, cur - 1, ...), each once and only
+ *             if visible;
+ *   idx[t, j, :] = forced, then the other visible blocks by descending score (equal scores: smaller id first;
+ *             NaN ranks as -infinity), cut to shape->topk columns, padded with -1.
+ * scores is DEVICE fp32 [total_tokens, hkv, score_stride], column b = score of block b of the token's own sequence;
+ * score_stride (floats, 1 .. 16384) must be at least the block count of the longest sequence; only visible,
+ * non-forced columns are read.  idx is DEVICE int32 [total_tokens, hkv, topk], fully overwritten.  Uses
+ * shape->total_tokens, nseq, hkv, block, topk and causal; the other fields are ignored.  Exact: scores are only
+ * compared, never altered.  16-byte loads are used when scores is 16-byte aligned and score_stride % 4 == 0. */
+int nsa_sel_select_blocks(const nsa_sel_shape* shape, const float* scores, int64_t score_stride,
+                          const int32_t* cu_seqlens, int32_t n_sink, int32_t n_local, int32_t* idx, void* stream);
+
 /* Optional per-kernel timing for benchmarks (not part of the paper's method).  After
  * nsa_sel_profile_enable(capacity > 0) every kernel launch of the calls above is bracketed by a pair of HIP
  * events on the caller's stream, up to `capacity` launches (later ones are not recorded); capacity <= 0 turns

@@ -43,14 +43,16 @@ def forced_blocks(cur: int, b_vis: int, n_sink: int, n_local: int):
 
 
 def select_blocks(scores: np.ndarray, cu: np.ndarray, topk: int, *, block: int = 64, causal: bool = True,
-                  n_sink: int = 1, n_local: int = 2) -> np.ndarray:
-    """scores: float32 [total_tokens, hkv, >= max blocks per sequence]; returns int32 [total_tokens, hkv, topk]."""
+                  n_sink: int = 1, n_local: int = 2, tokens=None) -> np.ndarray:
+    """scores: float32 [total_tokens, hkv, >= max blocks per sequence]; returns int32 [total_tokens, hkv, topk].
+    With `tokens` only those rows are computed (the others stay -1)."""
     T, hkv, _ = scores.shape
     out = np.full((T, hkv, topk), -1, dtype=np.int32)
+    wanted = None if tokens is None else set(int(t) for t in tokens)
     for s in range(len(cu) - 1):
         c0, c1 = int(cu[s]), int(cu[s + 1])
         b_s = -(-(c1 - c0) // block)
-        for t in range(c0, c1):
+        for t in (range(c0, c1) if wanted is None else sorted(x for x in wanted if c0 <= x < c1)):
             cur = (t - c0) // block
             b_vis = min(cur + 1, b_s) if causal else b_s
             forced = forced_blocks(cur, b_vis, n_sink, n_local)[:topk]

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
 _lib = None
 
-SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_workspace_bytes_min", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd",
+SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_workspace_bytes_min", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd", "nsa_sel_select_blocks",
            "nsa_sel_profile_enable", "nsa_sel_profile_select", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_mfma_probe", "nsa_sel_strerror"]
 
 
@@ -39,6 +39,7 @@ def lib():
         L.nsa_sel_index_view.argtypes = [C.POINTER(Shape), vp] + [C.POINTER(vp)] * 4 + [C.POINTER(C.c_int32)]
         L.nsa_sel_fwd.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, sz, vp]
         L.nsa_sel_bwd.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, sz, vp]
+        L.nsa_sel_select_blocks.argtypes = [C.POINTER(Shape), vp, C.c_int64, i32p, C.c_int32, C.c_int32, i32p, vp]
         L.nsa_sel_profile_enable.argtypes = [C.c_int]
         L.nsa_sel_profile_select.argtypes = [C.c_uint]
         L.nsa_sel_profile_collect.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
@@ -108,6 +109,21 @@ def nsa_sel_bwd(shape, q, k, v, o, lse, do, cu, index_ws, dq, dk, dv, ws):
     _check(lib().nsa_sel_bwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(cu),
                              _ptr(index_ws), index_ws.numel(), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(),
                              _stream()), "nsa_sel_bwd")
+
+
+def select_blocks(scores: torch.Tensor, cu: Optional[torch.Tensor], topk: int, *, block: int = 64,
+                  causal: bool = True, n_sink: int = 1, n_local: int = 2, out: Optional[torch.Tensor] = None):
+    """idx int32 [tokens, hkv, topk] from fp32 scores [tokens, hkv, stride] (nsa_sel_select_blocks)."""
+    if scores.dtype != torch.float32 or scores.dim() != 3:
+        raise NsaSelError("scores must be float32 [tokens, hkv, stride]")
+    T, hkv, stride = scores.shape
+    nseq = 1 if cu is None else cu.numel() - 1
+    shape = Shape(T, nseq, hkv, hkv, 128, block, topk, int(causal), 0.0, 0)
+    if out is None:
+        out = torch.empty(T, hkv, topk, dtype=torch.int32, device=scores.device)
+    _check(lib().nsa_sel_select_blocks(C.byref(shape), _ptr(scores), stride, _ptr(cu), n_sink, n_local, _ptr(out),
+                                       _stream()), "nsa_sel_select_blocks")
+    return out
 
 
 def profile_enable(capacity: int):

@@ -102,7 +102,7 @@ inline int64_t units_bound(int nj, int b_cap, int T, int topk, int unit) {
 enum KernelId {
   KID_INDEX_PREP = 0, KID_INDEX_CHUNK_PREFIX, KID_INDEX_HIST, KID_INDEX_SCAN, KID_INDEX_SCATTER, KID_INDEX_FINALIZE,
   KID_INDEX_UNITS, KID_FWD_MAIN, KID_FWD_MERGE, KID_BWD_DELTA, KID_BWD_MAIN, KID_BWD_DQ_REDUCE, KID_BWD_DKV_REDUCE,
-  KID_COUNT
+  KID_SELECT_BLOCKS, KID_COUNT
 };
 // Records a HIP event on `st` at construction and destruction when profiling is on; does nothing otherwise.
 struct ProfScope {
