@@ -52,6 +52,43 @@ def cpu_baseline(w, budget_tokens: int):
                       f"backward contributions of those rows, {dt:.1f} s"}
 
 
+def bench_select_blocks(nsa, wl, w, cu, steps):
+    """The step in front of the path, measured on its own (it is not part of the metric's step): seeded fp32 block
+    scores of the workload's shape -> selection tensor.  HBM-bound: every visible score is read once."""
+    import torch
+    nb_max = max(-(-L // w.block) for L in w.seqlens)
+    if 4 * w.total_tokens * w.hkv * nb_max > 12e9:
+        return {"skipped": "the score tensor of this shape exceeds 12 GB of host memory to draw"}
+    t0 = time.time()
+    x = torch.from_numpy(wl.draw_block_scores(w.seed, w.seqlens, w.hkv, w.block, kind="heavy")).cuda()
+    print(f"[bench] block scores drawn in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    out = torch.empty(w.total_tokens, w.hkv, w.topk, dtype=torch.int32, device="cuda")
+    kw = dict(block=w.block, causal=w.causal, n_sink=1, n_local=2, out=out)
+    for _ in range(3):
+        nsa.select_blocks(x, cu, w.topk, **kw)
+    torch.cuda.synchronize()
+    nsa.profile_select(["select_blocks"])
+    nsa.profile_enable(steps)
+    for _ in range(steps):
+        nsa.select_blocks(x, cu, w.topk, **kw)
+    torch.cuda.synchronize()
+    tot, n = nsa.profile_collect()["select_blocks"]
+    nsa.profile_enable(0)
+    nsa.profile_select(None)
+    ms = tot / n
+    # algorithmic bytes: the visible scores (4 B each) plus the idx rows written
+    vis = 0
+    for L in w.seqlens:
+        nb = -(-L // w.block)
+        cur = np.arange(L, dtype=np.int64) // w.block
+        vis += int((cur + 1).sum()) if w.causal else L * nb
+    nbytes = 4 * (vis * w.hkv + w.total_tokens * w.hkv * w.topk)
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"ms_per_launch": ms, "algorithmic_bytes": nbytes, "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
+            "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "scores": "seeded 'heavy' recipe of workloads.draw_block_scores, "
+            "1 sink + 2 local blocks forced"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +99,8 @@ def main():
                     help="also launch the library's 1 GiB copy kernel once (for scaling rocprofv3 byte counters)")
     ap.add_argument("--ws-cap-gb", type=float, default=0.0,
                     help="cap each workspace at this many GB: the library then reuses it over groups of KV heads")
+    ap.add_argument("--no-select", action="store_true",
+                    help="skip the separate measurement of the selection step (block scores -> idx) in front of the path")
     ap.add_argument("--cpu-tokens", type=int, default=1280, help="query tokens of the CPU-oracle sample (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -192,6 +231,8 @@ def main():
         "measured_peaks": {"mfma_loop_TFLOPs": mfma_measured, "stream_copy_GBps": copy_measured,
                            "frac_of_measured_mfma": (f + b) / (ms * 1e-3) / 1e12 / mfma_measured},
     }
+    if not args.no_select:
+        out["upstream"] = {"select_blocks": bench_select_blocks(nsa, wl, w, cu, args.steps)}
     if args.cpu_tokens > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_tokens)
     print(json.dumps(out), flush=True)

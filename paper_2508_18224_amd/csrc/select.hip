@@ -1,12 +1,12 @@
 // Block selection in front of the attention path: per (token, KV head) the forced sink / most-recent blocks and
 // then the visible blocks with the highest scores (see nsa_sel_select_blocks in nsa_sel.h for the rule).
 //
-// One wavefront owns one row.  The visible scores of up to 1024 blocks sit in 16 registers per lane as order-
-// preserving unsigned keys (0 = not a candidate); a pick is two wave-wide 32-bit reductions (largest key, then the
-// smallest block id holding it) after which the winner's key is cleared.  Rows with more than 1024 visible blocks
-// are handled 1024 at a time: the picks of every chunk go to a small LDS list that one more selection of the same
-// kind reduces to the final picks.  HBM-bound: each visible score is read once, with 16-byte loads when the rows
-// are 16-byte aligned.
+// One wavefront owns one row and looks at it in chunks of up to 1024 blocks, 16 scores per lane held in registers
+// as order-preserving unsigned keys.  The fast method (select_by_threshold) bounds the picks from below with the
+// r-th largest lane maximum, compacts the few elements above that bound into the LDS and ranks them against each
+// other: ~400 instructions per row.  Rows where too many scores tie at the bound fall back to the general method
+// (select_by_rounds): one pick per round, each round two wave-wide reductions.  Each visible score is read from
+// HBM once, with 16-byte loads when the rows are 16-byte aligned.
 #include "common.h"
 
 namespace nsa {
@@ -17,6 +17,7 @@ constexpr int kChunkBlocks = 1024;            // blocks examined at a time: 16 k
 constexpr int kKeys = kChunkBlocks / 64;
 constexpr int kMaxChunks = 16;                // rows of up to 16384 blocks
 constexpr int kCandPerLane = kMaxChunks * kMaxTopk / 64;   // chunk picks each lane holds in the final selection
+constexpr int kMaxSurv = 128;                 // survivors the fast method ranks; rows with more take the general one
 
 // All four steps stay inside a row of 16 lanes (quad swaps, then mirrors of 8 and of 16 lanes), after which every
 // lane of a row holds the row's result; the four rows are combined on the scalar unit.
@@ -68,82 +69,81 @@ __device__ __forceinline__ int pick_rounds(uint32_t (&key)[E], int ne, int want,
   return got;
 }
 
+// What one row needs to know about itself.
+struct RowInfo {
+  const float* srow;  // the row's scores
+  int b_vis;          // visible blocks are [0, b_vis)
+  int ns;             // forced sinks are [0, ns)
+  int nl, loc_lo, loc_hi;   // forced local blocks are [loc_lo, loc_hi] when nl > 0
+  int n_forced;       // columns taken by forced blocks
+  int want;           // columns to fill by score
+  __device__ __forceinline__ bool forced(int b) const { return b < ns || (nl > 0 && b >= loc_lo && b <= loc_hi); }
+};
+
+// Block of element e of a lane in the chunk that starts at `base`: four consecutive blocks per 16-byte load, or
+// one block per 4-byte load.  Ascends with e inside a lane in both layouts.
 template <bool kVec>
-__global__ void __launch_bounds__(64 * kSelWaves)
-k_select_blocks(const float* __restrict__ scores, int64_t stride, const int32_t* __restrict__ cu, int T, int nseq,
-                int hkv, int bk, int topk, int causal, int n_sink, int n_local, int32_t* __restrict__ idx) {
-  __shared__ uint32_t cand_key[kSelWaves][kMaxChunks * kMaxTopk];
-  __shared__ int32_t cand_blk[kSelWaves][kMaxChunks * kMaxTopk];
-  const int lane = threadIdx.x & 63;
-  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t row = (int64_t)blockIdx.x * kSelWaves + w;
-  if (row >= (int64_t)T * hkv) return;     // whole wavefront leaves together
-  const int t = (int)(row / hkv);
-  int s, c0, c1;
-  seq_bounds(cu, nseq, T, t, s, c0, c1);
-  const int cur = (t - c0) / bk;
-  const int b_s = (c1 - c0 + bk - 1) / bk;
-  int b_vis = causal ? (cur + 1 < b_s ? cur + 1 : b_s) : b_s;
-  if ((int64_t)b_vis > stride) b_vis = (int)stride;   // never read past a row, whatever cu says
-  // forced blocks: sinks 0 .. ns-1, then cur - r0, cur - r0 - 1, ... (nl of them, all >= ns and < b_vis)
-  const int ns = n_sink < b_vis ? n_sink : b_vis;
-  const int r0 = cur - b_vis + 1 > 0 ? cur - b_vis + 1 : 0;
-  int r_last = n_local - 1 < cur - ns ? n_local - 1 : cur - ns;
-  const int nl = r_last - r0 + 1 > 0 ? r_last - r0 + 1 : 0;
-  const int loc_hi = cur - r0, loc_lo = loc_hi - nl + 1;    // local forced blocks are [loc_lo, loc_hi] when nl > 0
-  const int n_forced = ns + nl < topk ? ns + nl : topk;
-  const int want = topk - n_forced;                          // picks by score
-  const float* __restrict__ srow = scores + row * stride;
+__device__ __forceinline__ int blk_of(int base, int lane, int e) {
+  return kVec ? base + ((e >> 2) << 8) + (lane << 2) + (e & 3) : base + (e << 6) + lane;
+}
 
-  int mine = -1;                           // lane i ends up holding column i of the output row
-  if (lane < n_forced) mine = lane < ns ? lane : loc_hi - (lane - ns);
-
-  const int n_chunks = (b_vis + kChunkBlocks - 1) / kChunkBlocks;
-  int n_cand = 0;                          // chunk picks parked in the LDS (only when n_chunks > 1)
-  for (int c = 0; c < n_chunks && want > 0; ++c) {
-    const int base = c * kChunkBlocks;
-    const int left = b_vis - base;                                   // > 0
-    const int ne = left >= kChunkBlocks ? kKeys : (kVec ? ((left + 255) >> 8) << 2 : (left + 63) >> 6);
-    // element e of a lane is block base + blk_in(e): four consecutive blocks per 16-byte load, or one per load
-    auto blk_of = [&](int e) { return kVec ? base + ((e >> 2) << 8) + (lane << 2) + (e & 3) : base + (e << 6) + lane; };
-    uint32_t key[kKeys];
-    if (kVec) {
+// Raw score bits of E elements per lane; what lies at or past b_vis in a lane's FIRST element is not loaded and
+// reads as `fill` (a 16-byte load may bring up to three blocks past b_vis along; callers deal with those).
+template <bool kVec, int E>
+__device__ __forceinline__ void load_bits(const RowInfo& R, int base, int lane, uint32_t fill, uint32_t (&x)[E]) {
+  if (kVec) {
 #pragma unroll
-      for (int q = 0; q < kKeys / 4; ++q) {
-        u32x4 x = {0u, 0u, 0u, 0u};
-        const int b = base + (q << 8) + (lane << 2);
-        if (q * 4 < ne && b < b_vis) x = *reinterpret_cast<const u32x4*>(srow + b);   // b + 3 < stride: both multiples of 4
+    for (int q = 0; q < E / 4; ++q) {
+      const int b = base + (q << 8) + (lane << 2);
+      u32x4 v = {fill, fill, fill, fill};
+      if (b < R.b_vis) v = *reinterpret_cast<const u32x4*>(R.srow + b);   // b + 3 < stride: both multiples of 4
 #pragma unroll
-        for (int i = 0; i < 4; ++i) key[q * 4 + i] = x[i];
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < kKeys; ++e) {
-        const int b = base + (e << 6) + lane;
-        key[e] = (e < ne && b < b_vis) ? __builtin_bit_cast(uint32_t, srow[b]) : 0u;
-      }
+      for (int i = 0; i < 4; ++i) x[q * 4 + i] = v[i];
     }
+  } else {
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int b = base + (e << 6) + lane;
+      x[e] = b < R.b_vis ? __builtin_bit_cast(uint32_t, R.srow[b]) : fill;
+    }
+  }
+}
+
+// ---- the general method: `want` rounds of "take the largest remaining key".  Exact for any input, also when
+// most scores are equal; ~150 instructions per pick, so it only serves rows the fast method hands over.
+template <bool kVec>
+__device__ __forceinline__ int select_by_rounds(const RowInfo& R, int lane, uint32_t* lds_wave, int mine) {
+  uint32_t* cand_key = lds_wave;
+  int32_t* cand_blk = reinterpret_cast<int32_t*>(lds_wave + kMaxChunks * kMaxTopk);
+  const int n_chunks = (R.b_vis + kChunkBlocks - 1) / kChunkBlocks;
+  int n_cand = 0;                          // chunk picks parked in the LDS (only when n_chunks > 1)
+  for (int c = 0; c < n_chunks; ++c) {
+    const int base = c * kChunkBlocks;
+    const int left = R.b_vis - base;       // > 0
+    const int ne = left >= kChunkBlocks ? kKeys : (kVec ? ((left + 255) >> 8) << 2 : (left + 63) >> 6);
+    uint32_t key[kKeys];
+    load_bits<kVec, kKeys>(R, base, lane, 0u, key);
 #pragma unroll
     for (int e = 0; e < kKeys; ++e) {
-      const int b = blk_of(e);
-      const bool forced = b < ns || (nl > 0 && b >= loc_lo && b <= loc_hi);
-      key[e] = (e < ne && b < b_vis && !forced) ? order_key(key[e]) : 0u;
+      const int b = blk_of<kVec>(base, lane, e);
+      key[e] = (b < R.b_vis && !R.forced(b)) ? order_key(key[e]) : 0u;
     }
+    auto blk = [&](int e) { return blk_of<kVec>(base, lane, e); };
     if (n_chunks == 1) {
-      pick_rounds<kKeys>(key, ne, want, blk_of, [&](int i, int blk, uint32_t) {
-        if (lane == n_forced + i) mine = blk;
+      pick_rounds<kKeys>(key, ne, R.want, blk, [&](int i, int b, uint32_t) {
+        if (lane == R.n_forced + i) mine = b;
       });
     } else {
-      const int got = pick_rounds<kKeys>(key, ne, want, blk_of, [&](int i, int blk, uint32_t k) {
+      const int got = pick_rounds<kKeys>(key, ne, R.want, blk, [&](int i, int b, uint32_t k) {
         if (lane == 0) {
-          cand_key[w][n_cand + i] = k;
-          cand_blk[w][n_cand + i] = blk;
+          cand_key[n_cand + i] = k;
+          cand_blk[n_cand + i] = b;
         }
       });
       n_cand += got;
     }
   }
-  if (n_chunks > 1 && want > 0) {
+  if (n_chunks > 1) {
     // final selection over the chunk picks (written by lane 0 of this wavefront, read by all of its lanes)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -153,16 +153,136 @@ k_select_blocks(const float* __restrict__ scores, int64_t stride, const int32_t*
 #pragma unroll
     for (int e = 0; e < kCandPerLane; ++e) {
       const int q = (e << 6) + lane;
-      key[e] = q < n_cand ? cand_key[w][q] : 0u;
-      blk[e] = q < n_cand ? cand_blk[w][q] : 0x7fffffff;
+      key[e] = q < n_cand ? cand_key[q] : 0u;
+      blk[e] = q < n_cand ? cand_blk[q] : 0x7fffffff;
     }
     // within a lane the candidates of later chunks have larger block ids, so blocks ascend with e as required
-    pick_rounds<kCandPerLane>(key, (n_cand + 63) >> 6, want, [&](int e) { return blk[e]; },
+    pick_rounds<kCandPerLane>(key, (n_cand + 63) >> 6, R.want, [&](int e) { return blk[e]; },
                               [&](int i, int b, uint32_t) {
-                                if (lane == n_forced + i) mine = b;
+                                if (lane == R.n_forced + i) mine = b;
                               });
   }
-  if (lane < topk) idx[row * topk + lane] = mine;
+  return mine;
+}
+
+// ---- the fast method.  Per chunk of up to 1024 blocks:
+//   1. every lane takes the largest of its keys; tau = the r-th largest of the 64 lane maxima, found bit by bit
+//      with ballots (scalar work).  r = want + (forced blocks) + 3, so at least `want` selectable blocks of the
+//      chunk have a key >= tau (forced blocks and the up to three blocks a 16-byte load brings along past b_vis
+//      are not masked beforehand: they are dropped in step 3), hence no block with a key < tau can be a pick;
+//   2. the elements with key >= tau ("survivors", a few more than r unless many scores tie) are compacted into
+//      an LDS list of (key, ~block) pairs;
+//   3. after all chunks every survivor counts the survivors that beat it; that rank is its output column.
+// Returns false, having written nothing, when the survivors do not fit the list.
+template <bool kVec, int E>
+__device__ __forceinline__ void chunk_survivors(const RowInfo& R, int base, int lane, int r, uint64_t* surv, int& n_surv) {
+  uint32_t key[E];
+  load_bits<kVec, E>(R, base, lane, 0u, key);
+  uint32_t lmax = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    // +0 turns -0 into +0 and max(., -inf) turns a NaN into -inf, as the order of the scores demands; then the
+    // sign-magnitude bits become an unsigned key of the same order (always > 0).  What was not loaded gets key 0,
+    // "nothing here".
+    const bool hole = blk_of<kVec>(base, lane, kVec ? (e & ~3) : e) >= R.b_vis;   // not loaded
+    float f = __builtin_bit_cast(float, key[e]) + 0.0f;
+    f = __builtin_fmaxf(f, -__builtin_inff());
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    const uint32_t k = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+    key[e] = hole ? 0u : k;
+    lmax = key[e] > lmax ? key[e] : lmax;
+  }
+  uint32_t tau = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t trial = tau | (1u << bit);
+    const int c = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lmax >= trial));
+    tau = c >= r ? trial : tau;
+  }
+  const uint32_t thr = tau ? tau : 1u;     // fewer than r lanes hold anything: every loaded element survives
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const bool sv = key[e] >= thr;
+    const uint64_t m = __builtin_amdgcn_ballot_w64(sv);
+    if (m != 0) {
+      const int pos = n_surv + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+      if (sv && pos < kMaxSurv)
+        surv[pos] = ((uint64_t)key[e] << 32) | (uint32_t)~(uint32_t)blk_of<kVec>(base, lane, e);
+      n_surv += __builtin_popcountll(m);
+    }
+  }
+}
+
+template <bool kVec>
+__device__ __forceinline__ bool select_by_threshold(const RowInfo& R, int lane, uint64_t* surv, int32_t* out_row) {
+  const int r = R.want + R.ns + R.nl + 3;   // <= topk + 3 whenever want > 0
+  const int n_chunks = (R.b_vis + kChunkBlocks - 1) / kChunkBlocks;
+  int n_surv = 0;
+  for (int c = 0; c < n_chunks; ++c) {
+    const int base = c * kChunkBlocks;
+    const int nq = (R.b_vis - base + 255) >> 8;   // quarter chunks with visible blocks (>= 1)
+    if (nq >= 4) chunk_survivors<kVec, 16>(R, base, lane, r, surv, n_surv);
+    else if (nq == 3) chunk_survivors<kVec, 12>(R, base, lane, r, surv, n_surv);
+    else if (nq == 2) chunk_survivors<kVec, 8>(R, base, lane, r, surv, n_surv);
+    else chunk_survivors<kVec, 4>(R, base, lane, r, surv, n_surv);
+    if (n_surv > kMaxSurv) return false;
+  }
+  // drop what may not be picked: forced blocks and blocks past the visible range
+  for (int q = lane; q < n_surv; q += 64) {
+    const int b = (int)~(uint32_t)surv[q];
+    if (b >= R.b_vis || R.forced(b)) surv[q] = 0;
+  }
+  for (int q0 = 0; q0 < n_surv; q0 += 64) {
+    const int q = q0 + lane;
+    const uint64_t my = q < n_surv ? surv[q] : 0;
+    int rank = 0;
+#pragma unroll 4
+    for (int s = 0; s < n_surv; ++s) rank += surv[s] > my ? 1 : 0;   // same address in every lane: a broadcast
+    if (my != 0 && rank < R.want) out_row[R.n_forced + rank] = (int32_t)~(uint32_t)my;
+  }
+  return true;
+}
+
+template <bool kVec>
+__global__ void __launch_bounds__(64 * kSelWaves)
+k_select_blocks(const float* __restrict__ scores, int64_t stride, const int32_t* __restrict__ cu, int T, int nseq,
+                int hkv, int bk, int topk, int causal, int n_sink, int n_local, int32_t* __restrict__ idx) {
+  // per wavefront: the survivor list of the fast method, or the chunk picks of the general one
+  __shared__ uint64_t lds[kSelWaves][kMaxChunks * kMaxTopk];
+  static_assert(kMaxSurv <= kMaxChunks * kMaxTopk, "survivor list must fit");
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t row = (int64_t)blockIdx.x * kSelWaves + w;
+  if (row >= (int64_t)T * hkv) return;     // whole wavefront leaves together
+  const int t = (int)(row / hkv);
+  int s, c0, c1;
+  seq_bounds(cu, nseq, T, t, s, c0, c1);
+  const int cur = (t - c0) / bk;
+  const int b_s = (c1 - c0 + bk - 1) / bk;
+  RowInfo R;
+  R.b_vis = causal ? (cur + 1 < b_s ? cur + 1 : b_s) : b_s;
+  if ((int64_t)R.b_vis > stride) R.b_vis = (int)stride;   // never read past a row, whatever cu says
+  // forced blocks: sinks 0 .. ns-1, then cur - r0, cur - r0 - 1, ... (nl of them, all >= ns and < b_vis)
+  R.ns = n_sink < R.b_vis ? n_sink : R.b_vis;
+  const int r0 = cur - R.b_vis + 1 > 0 ? cur - R.b_vis + 1 : 0;
+  const int r_last = n_local - 1 < cur - R.ns ? n_local - 1 : cur - R.ns;
+  R.nl = r_last - r0 + 1 > 0 ? r_last - r0 + 1 : 0;
+  R.loc_hi = cur - r0;
+  R.loc_lo = R.loc_hi - R.nl + 1;
+  R.n_forced = R.ns + R.nl < topk ? R.ns + R.nl : topk;
+  R.want = topk - R.n_forced;
+  R.srow = scores + row * stride;
+  int32_t* out_row = idx + row * topk;
+
+  int mine = -1;                           // lane i holds column i of the output row: forced blocks, then -1
+  if (lane < R.n_forced) mine = lane < R.ns ? lane : R.loc_hi - (lane - R.ns);
+  const int n_free = R.b_vis - R.ns - R.nl;                  // selectable blocks
+  const int n_picks = R.want < n_free ? R.want : n_free;     // columns the selection fills
+  bool by_rank = true;                     // pick columns already written, each by the lane that ranked there
+  if (n_picks > 0) {
+    by_rank = select_by_threshold<kVec>(R, lane, lds[w], out_row);
+    if (!by_rank) mine = select_by_rounds<kVec>(R, lane, reinterpret_cast<uint32_t*>(lds[w]), mine);
+  }
+  if (lane < topk && (!by_rank || lane < R.n_forced || lane >= R.n_forced + n_picks)) out_row[lane] = mine;
 }
 
 }  // namespace

@@ -69,6 +69,42 @@ def test_rows_longer_than_one_chunk(n_tokens, causal, kind, stride):
     assert np.array_equal(got[tokens], ref[tokens])
 
 
+@pytest.mark.parametrize("n_tokens,causal,fill", [(70000, False, 0.25), (140000, True, -np.inf), (3000, True, np.nan)])
+def test_all_scores_equal(n_tokens, causal, fill):
+    """Every score the same: the bound the fast method derives keeps every block, so the row is handed to the general
+    method (in rows of more than 128 blocks); the picks are then the smallest selectable block ids."""
+    print("case all equal", n_tokens, causal, fill, flush=True)
+    seqlens = [n_tokens]
+    cu = _cu(seqlens)
+    nb = -(-n_tokens // 64)
+    x = np.full((n_tokens, 1, nb), fill, dtype=np.float32)
+    rng = np.random.default_rng(7)
+    tokens = np.unique(np.concatenate([rng.integers(0, n_tokens, 120), [0, 64, 2047, 2048, n_tokens - 1]]))
+    ref = tko.select_blocks(x, cu, 16, causal=causal, tokens=tokens)
+    got = _gpu_select(x, cu, 16, causal=causal)
+    assert np.array_equal(got[tokens], ref[tokens])
+    last = ref[n_tokens - 1, 0].tolist()
+    assert last[:3] == ([0, (n_tokens - 1) // 64, (n_tokens - 1) // 64 - 1]) and last[3:] == list(range(1, 14))
+
+
+def test_many_ties_at_the_bound():
+    """A few distinct large scores over a sea of equal ones: more picks than distinct values, so the last picks are
+    decided by block id among hundreds of equal scores."""
+    print("case ties at the bound", flush=True)
+    n_tokens, hkv = 100000, 2
+    seqlens = [60000, 40000]
+    cu = _cu(seqlens)
+    rng = np.random.default_rng(8)
+    x = np.ones((n_tokens, hkv, 938), dtype=np.float32)
+    hot = rng.integers(0, 938, size=(n_tokens, hkv, 6))
+    np.put_along_axis(x, hot, rng.random((n_tokens, hkv, 6)).astype(np.float32) + 2, axis=2)
+    tokens = np.unique(np.concatenate([rng.integers(0, n_tokens, 150), [59999, 60000, n_tokens - 1]]))
+    for causal in (True, False):
+        ref = tko.select_blocks(x, cu, 16, causal=causal, tokens=tokens)
+        got = _gpu_select(x, cu, 16, causal=causal)
+        assert np.array_equal(got[tokens], ref[tokens])
+
+
 def test_headline_shape_sampled_rows_and_properties():
     """N = 64K, 8 KV heads, 1024 blocks per row, top-16 with the sink and two local blocks forced: sampled rows
     against the oracle, and on every row the properties that hold at any size."""
