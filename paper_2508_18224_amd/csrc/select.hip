@@ -17,6 +17,7 @@ constexpr int kChunkBlocks = 1024;            // blocks examined at a time: 16 k
 constexpr int kKeys = kChunkBlocks / 64;
 constexpr int kMaxChunks = 16;                // rows of up to 16384 blocks
 constexpr int kCandPerLane = kMaxChunks * kMaxTopk / 64;   // chunk picks each lane holds in the final selection
+constexpr int kTauLowBit = 16;                // the bound is searched on the upper 16 bits of the keys (looser, still a bound)
 constexpr int kMaxSurv = 128;                 // survivors the fast method ranks; rows with more take the general one
 
 // All four steps stay inside a row of 16 lanes (quad swaps, then mirrors of 8 and of 16 lanes), after which every
@@ -193,7 +194,7 @@ __device__ __forceinline__ void chunk_survivors(const RowInfo& R, int base, int 
     lmax = key[e] > lmax ? key[e] : lmax;
   }
   uint32_t tau = 0;
-  for (int bit = 31; bit >= 0; --bit) {
+  for (int bit = 31; bit >= kTauLowBit; --bit) {
     const uint32_t trial = tau | (1u << bit);
     const int c = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lmax >= trial));
     tau = c >= r ? trial : tau;
