@@ -29,6 +29,14 @@ Index inversion (paper Sec. 3.2: the per-KV-block query list I_i; here with the 
   `idx` holding the first occurrence.  Global block ids number the blocks of the packed sequences
   consecutively (sequence 0's blocks, then sequence 1's, ...).
 
+Gated combination (paper Eq. (2): the layer output is the sum over the three branches c of tau^c_t times the
+branch's attention output).  With the other two branches' gated sum given as `O_acc`:
+
+      O_out[t,h] = O_acc[t,h] + gate[t,h] * O[t,h]
+  backward:  dO[t,h] = gate[t,h] * dO_out[t,h]  (then the backward above)     dgate[t,h] = <dO_out[t,h], O[t,h]>
+
+  (the paper writes one gate per token and branch; a [token, head] array covers that and per-head gates alike).
+
 All arithmetic is float64 on inputs that are bf16 values widened exactly.  No tiling, no online softmax.
 Pins (tests/test_oracle_*.py): dense attention under the equivalent mask, torch's scaled_dot_product_attention
 when every block is selected, torch autograd of a dense masked formulation, central finite differences, and
@@ -213,3 +221,19 @@ def backward_kv_blocks(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarr
                 dVb[rows] += np.outer(p[inblk], dO[t, h])
         out.append((dKb, dVb))
     return out
+
+
+def gated_forward(O: np.ndarray, gate: np.ndarray, O_acc: Optional[np.ndarray] = None) -> np.ndarray:
+    """Eq. (2) with the `sel` output O [T, hq, d], its gate [T, hq] and the other branches' gated sum O_acc."""
+    out = gate[:, :, None] * O
+    return out if O_acc is None else O_acc + out
+
+
+def gated_backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO_out: np.ndarray, gate: np.ndarray, idx: np.ndarray,
+                   cu: np.ndarray, *, block: int = 64, causal: bool = True, scale=None, tokens=None):
+    """Gradients of a loss through O_out = O_acc + gate * O: (dQ, dK, dV, dgate).  dO_acc is dO_out itself."""
+    O, _ = forward(Q, K, V, idx, cu, block=block, causal=causal, scale=scale, tokens=tokens)
+    dQ, dK, dV = backward(Q, K, V, gate[:, :, None] * dO_out, idx, cu, block=block, causal=causal, scale=scale,
+                          tokens=tokens)
+    dgate = (dO_out * O).sum(axis=2)
+    return dQ, dK, dV, dgate

@@ -102,3 +102,24 @@ def test_inversion_mistake_is_caught(monkeypatch):
     monkeypatch.setattr(orc, "invert_index", descending)
     with pytest.raises(AssertionError):
         pins.test_inversion_against_mask_and_invariants(pins.CASES[0])
+
+
+@pytest.mark.parametrize("kind", ["gate_not_applied_to_dO", "dgate_from_gated_output", "acc_dropped"])
+def test_gated_combination_mistake_is_caught(monkeypatch, kind):
+    real_fwd, real_bwd = orc.gated_forward, orc.gated_backward
+
+    def fwd(O, gate, O_acc=None):
+        return real_fwd(O, gate, None if kind == "acc_dropped" else O_acc)
+
+    def bwd(Q, K, V, dO_out, gate, idx, cu, **kw):
+        dQ, dK, dV, dgate = real_bwd(Q, K, V, dO_out, gate, idx, cu, **kw)
+        if kind == "gate_not_applied_to_dO":
+            dQ, dK, dV = orc.backward(Q, K, V, dO_out, idx, cu, **kw)
+        if kind == "dgate_from_gated_output":
+            dgate = dgate * gate
+        return dQ, dK, dV, dgate
+    pins.test_gated_combination_equals_autograd_of_dense_formulation()
+    monkeypatch.setattr(orc, "gated_forward", fwd)
+    monkeypatch.setattr(orc, "gated_backward", bwd)
+    with pytest.raises(AssertionError):
+        pins.test_gated_combination_equals_autograd_of_dense_formulation()

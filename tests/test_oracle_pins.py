@@ -123,6 +123,31 @@ def test_backward_equals_autograd_of_dense_masked_attention(case):
     np.testing.assert_allclose(dV, tv.grad.numpy(), rtol=0, atol=1e-11)
 
 
+def test_gated_combination_equals_autograd_of_dense_formulation():
+    """Eq. (2): out = acc + gate * attention.  Forward and all four gradients against torch autograd of the dense
+    masked formulation; a zero gate must switch the branch (and its gradients) off."""
+    Q, K, V, dO, idx, cu = _rand_problem(31, [130, 90], hq=4, hkv=2, k=3)
+    rng = np.random.default_rng(32)
+    gate = rng.random(Q.shape[:2])
+    gate[5] = 0.0
+    acc = rng.standard_normal(Q.shape)
+    scale = 0.3
+    O, _ = orc.forward(Q, K, V, idx, cu, scale=scale)
+    out = orc.gated_forward(O, gate, acc)
+    dQ, dK, dV, dgate = orc.gated_backward(Q, K, V, dO, gate, idx, cu, scale=scale)
+    M = _dense_mask(idx, cu, True)
+    tq, tk, tv, tg = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V, gate))
+    tout = torch.from_numpy(acc) + tg[:, :, None] * _dense_torch(tq, tk, tv, M, scale)
+    np.testing.assert_allclose(out, tout.detach().numpy(), rtol=0, atol=1e-12)
+    tout.backward(torch.from_numpy(dO))
+    np.testing.assert_allclose(dQ, tq.grad.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dK, tk.grad.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dV, tv.grad.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dgate, tg.grad.numpy(), rtol=0, atol=1e-11)
+    assert not dQ[5].any()
+    np.testing.assert_array_equal(orc.gated_forward(O, gate)[5], 0.0)
+
+
 @pytest.mark.parametrize("causal", [True, False])
 def test_all_blocks_selected_is_full_attention(causal):
     """Top-k covering every block reduces the sel branch to Eq. (1); torch's SDPA is the library routine."""
