@@ -96,6 +96,28 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
                 const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws,
                 size_t index_bytes, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
 
+/* Gated combination with the other attention branches, fused into the forward's merge kernel (the step after the
+ * path; Eq. (2): the layer output is the sum over the branches c of tau^c_t times the branch's attention output).
+ * Like nsa_sel_fwd, and in addition  O_out[t,h,:] = O_acc[t,h,:] + gate[t,h] * O[t,h,:],  formed from the fp32 result
+ * before it is rounded.  gate is DEVICE fp32 [total_tokens, hq] (the paper's per-token gate broadcast over heads, or
+ * per-head gates); O_acc is DEVICE bf16 [total_tokens, hq, d], the gated sum of the other branches, or NULL for
+ * zero; O_out is DEVICE bf16 of the same shape and may be the buffer O_acc points to, but not O.  O and LSE are still
+ * written ungated: the backward needs them. */
+int nsa_sel_fwd_gated(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                      const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
+                      float* LSE, const float* gate, const void* O_acc, void* O_out, void* ws, size_t ws_bytes,
+                      void* stream);
+
+/* Backward of nsa_sel_fwd_gated with respect to Q, K, V and gate: dO_out is the gradient of O_out (it is also the
+ * gradient of O_acc, which this call does not touch), O and LSE are the forward's ungated outputs.  Writes dQ, dK,
+ * dV as nsa_sel_bwd would for dO = gate * dO_out, and dgate[t,h] = <dO_out[t,h,:], O[t,h,:]> (DEVICE fp32
+ * [total_tokens, hq]).  Gates must be >= 0 (the paper's lie in [0, 1]); a zero gate gives zero gradients for the row.
+ * The gate costs no extra pass: it is folded into the per-row log-sum-exp the main kernel already gathers. */
+int nsa_sel_bwd_gated(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
+                      const float* LSE, const void* dO_out, const float* gate, const int32_t* cu_seqlens,
+                      const void* index_ws, size_t index_bytes, void* dQ, void* dK, void* dV, float* dgate, void* ws,
+                      size_t ws_bytes, void* stream);
+
 /* The step in front of the path: block scores -> selection tensor, on the device, so that nsa_sel_build_index /
  * nsa_sel_fwd can consume idx without a host round trip.  The paper takes the selection tensor T as given
  * (Sec. 2.2) and notes only that block 0, the attention sink, is selected by every token (App. E); the rule used

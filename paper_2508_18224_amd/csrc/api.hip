@@ -161,9 +161,9 @@ int nsa_sel_index_view(const nsa_sel_shape* shape, const void* index_ws, const i
   return NSA_SEL_OK;
 }
 
-int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
-                const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O, float* LSE,
-                void* ws, size_t ws_bytes, void* stream) {
+static int fwd_impl(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                    const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
+                    float* LSE, const GateArgs& G, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!Q || !K || !V || !index_ws || !O || !LSE || !ws) return NSA_SEL_EINVAL;
@@ -181,12 +181,31 @@ int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   const size_t rows = partial_rows(shape, hpp);
   void* opart = ws;
   float* lse_part = (float*)((char*)ws + align256(rows * kD * 2));
-  return launch_fwd(P, L, hpp, Q, K, V, index_ws, opart, lse_part, O, LSE, st) == hipSuccess ? NSA_SEL_OK : NSA_SEL_EHIP;
+  return launch_fwd(P, L, hpp, Q, K, V, index_ws, opart, lse_part, O, LSE, G, st) == hipSuccess ? NSA_SEL_OK
+                                                                                                 : NSA_SEL_EHIP;
 }
 
-int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
-                const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws, size_t index_bytes,
-                void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream) {
+int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O, float* LSE,
+                void* ws, size_t ws_bytes, void* stream) {
+  return fwd_impl(shape, Q, K, V, idx, cu_seqlens, rebuild_index, index_ws, index_bytes, O, LSE,
+                  GateArgs{nullptr, nullptr, nullptr, nullptr}, ws, ws_bytes, stream);
+}
+
+int nsa_sel_fwd_gated(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                      const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
+                      float* LSE, const float* gate, const void* O_acc, void* O_out, void* ws, size_t ws_bytes,
+                      void* stream) {
+  if (!gate || !O_out || !aligned16(O_out) || (O_acc && !aligned16(O_acc)) || ((uintptr_t)gate & 3) || O_out == O)
+    return NSA_SEL_EINVAL;
+  return fwd_impl(shape, Q, K, V, idx, cu_seqlens, rebuild_index, index_ws, index_bytes, O, LSE,
+                  GateArgs{gate, O_acc, O_out, nullptr}, ws, ws_bytes, stream);
+}
+
+static int bwd_impl(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
+                    const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws,
+                    size_t index_bytes, void* dQ, void* dK, void* dV, const GateArgs& G, void* ws, size_t ws_bytes,
+                    void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!Q || !K || !V || !O || !LSE || !dO || !index_ws || !dQ || !dK || !dV || !ws) return NSA_SEL_EINVAL;
@@ -204,10 +223,26 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
   void* dqpart = w;
   float* delta = (float*)(w + align256(rows * kD * 2));
   float* dkv_part = (float*)((char*)delta + align256((size_t)shape->total_tokens * shape->hq * 8));
-  return launch_bwd(P, L, hpp, Q, K, V, O, LSE, dO, index_ws, dqpart, delta, dkv_part, dQ, dK, dV, (hipStream_t)stream) ==
-                 hipSuccess
+  return launch_bwd(P, L, hpp, Q, K, V, O, LSE, dO, index_ws, dqpart, delta, dkv_part, dQ, dK, dV, G,
+                    (hipStream_t)stream) == hipSuccess
              ? NSA_SEL_OK
              : NSA_SEL_EHIP;
+}
+
+int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
+                const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws, size_t index_bytes,
+                void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream) {
+  return bwd_impl(shape, Q, K, V, O, LSE, dO, cu_seqlens, index_ws, index_bytes, dQ, dK, dV,
+                  GateArgs{nullptr, nullptr, nullptr, nullptr}, ws, ws_bytes, stream);
+}
+
+int nsa_sel_bwd_gated(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
+                      const float* LSE, const void* dO_out, const float* gate, const int32_t* cu_seqlens,
+                      const void* index_ws, size_t index_bytes, void* dQ, void* dK, void* dV, float* dgate, void* ws,
+                      size_t ws_bytes, void* stream) {
+  if (!gate || !dgate || ((uintptr_t)gate & 3) || ((uintptr_t)dgate & 3)) return NSA_SEL_EINVAL;
+  return bwd_impl(shape, Q, K, V, O, LSE, dO_out, cu_seqlens, index_ws, index_bytes, dQ, dK, dV,
+                  GateArgs{gate, nullptr, nullptr, dgate}, ws, ws_bytes, stream);
 }
 
 const char* nsa_sel_strerror(int code) {

@@ -46,7 +46,7 @@ __device__ __forceinline__ void wave_sync_bwd() {  // orders a wavefront's own L
 
 __global__ void __launch_bounds__(256)
 k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, const float* __restrict__ LSE,
-            float2* __restrict__ stats) {
+            float2* __restrict__ stats, const float* __restrict__ gate, float* __restrict__ dgate) {
   const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   const int sub = threadIdx.x & 15;
   float acc = 0.f;
@@ -61,7 +61,18 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
   acc += __shfl_xor(acc, 4);
   acc += __shfl_xor(acc, 2);
   acc += __shfl_xor(acc, 1);
-  if (row < rows && sub == 0) stats[row] = make_float2(LSE[row] * 1.4426950408889634f, acc);
+  if (row < rows && sub == 0) {
+    float lse2 = LSE[row] * 1.4426950408889634f;
+    if (gate != nullptr) {
+      // Gated output (Eq. (2)): the gradient that reaches this branch is gate * dO.  Every place the main kernel
+      // uses it carries a factor P = exp2(s - lse2) (dV += P^T dO, dS = P (dP - delta)), so the gate is folded into
+      // the row's log-sum-exp, lse2 - log2(gate), and dO and delta stay as they are; a zero gate gives +inf, P = 0.
+      // d(loss)/d(gate) is the same <dO, O> as delta.
+      if (lse2 > -INFINITY) lse2 -= log2f(gate[row]);
+      dgate[row] = acc;
+    }
+    stats[row] = make_float2(lse2, acc);
+  }
 }
 
 // ---- the tiled backward main kernel ----------------------------------------------------------------------------
@@ -433,7 +444,8 @@ k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* 
 
 hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
                       const void* V, const void* O, const float* LSE, const void* dO, const void* index_ws,
-                      void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st) {
+                      void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, const GateArgs& G,
+                      hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
   // 64-token blocks: four waves, two workgroups per CU; 128-token blocks: eight waves, one workgroup per CU
   const bool b128 = P0.bk == 128;
@@ -449,7 +461,7 @@ hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
     const int64_t rows = (int64_t)P0.T * P0.hq;
     ProfScope ps(KID_BWD_DELTA, st);
     hipLaunchKernelGGL(k_bwd_delta, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, rows, (const bf16_t*)O,
-                       (const bf16_t*)dO, LSE, (float2*)delta);
+                       (const bf16_t*)dO, LSE, (float2*)delta, G.gate, G.dgate);
   }
   // KV heads are processed heads_per_pass at a time, every pass reusing the partial-dQ and unit-partial buffers
   for (int j0 = 0; j0 < P0.hkv; j0 += heads_per_pass) {

@@ -125,16 +125,25 @@ inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<u
   return e;
 }
 
+// Optional gated combination with the other attention branches (Eq. (2)); all null for the plain entry points.
+struct GateArgs {
+  const float* gate;  // [T, hq]
+  const void* o_acc;  // bf16 [T, hq, d] or null
+  void* o_out;        // bf16 [T, hq, d]
+  float* dgate;       // [T, hq] (backward)
+};
+
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) -------------------------------------
 hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
                               hipStream_t st);
 // heads_per_pass: KV heads whose partial results the workspace can hold at once (1 .. hkv)
 hipError_t launch_fwd(const Problem& P, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
                       const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
-                      hipStream_t st);
+                      const GateArgs& G, hipStream_t st);
 hipError_t launch_bwd(const Problem& P, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
                       const void* V, const void* O, const float* LSE, const void* dO, const void* index_ws,
-                      void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, hipStream_t st);
+                      void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, const GateArgs& G,
+                      hipStream_t st);
 
 // ---- device helpers ------------------------------------------------------------------------------------
 #if defined(__HIPCC__)

@@ -419,7 +419,7 @@ __global__ void __launch_bounds__(256)
 k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict__ lse_part,
             const uint32_t* __restrict__ vmask, const int32_t* __restrict__ slotpos,
             const int32_t* __restrict__ off, bf16_t* __restrict__ O,
-            float* __restrict__ LSE) {
+            float* __restrict__ LSE, const float* __restrict__ gate, const bf16_t* Oacc, bf16_t* Oout) {
   // rows of the pass: (token, head of the KV heads [j0, j0 + nj))
   const int hp = P.nj * P.g;
   const int64_t prow = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
@@ -435,6 +435,9 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
   if (vm == 0u) {
     *reinterpret_cast<uint4*>(orow) = make_uint4(0, 0, 0, 0);
     if (sub == 0) LSE[row] = -INFINITY;
+    if (gate != nullptr)  // nothing to add: the gated sum is what the other branches gave
+      *reinterpret_cast<uint4*>(Oout + row * kD + 8 * sub) =
+          Oacc != nullptr ? *reinterpret_cast<const uint4*>(Oacc + row * kD + 8 * sub) : make_uint4(0, 0, 0, 0);
     return;
   }
   const int32_t* sp = slotpos + ((size_t)t * P.hkv + j) * P.topk;
@@ -484,11 +487,23 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
   o.w = pack_bf16x2(acc[6] * inv, acc[7] * inv);
   *reinterpret_cast<uint4*>(orow) = o;
   if (sub == 0) LSE[row] = M + __logf(Ls);
+  if (gate != nullptr) {
+    // Eq. (2): O_out = O_acc + gate * O, from the fp32 result (Oout may be the buffer Oacc points to: every lane
+    // reads its own 16 bytes before it writes them)
+    const float tau = gate[row] * inv;
+    uint4 a = make_uint4(0, 0, 0, 0);
+    if (Oacc != nullptr) a = *reinterpret_cast<const uint4*>(Oacc + row * kD + 8 * sub);
+    o.x = pack_bf16x2(bf16_lo(a.x) + tau * acc[0], bf16_hi(a.x) + tau * acc[1]);
+    o.y = pack_bf16x2(bf16_lo(a.y) + tau * acc[2], bf16_hi(a.y) + tau * acc[3]);
+    o.z = pack_bf16x2(bf16_lo(a.z) + tau * acc[4], bf16_hi(a.z) + tau * acc[5]);
+    o.w = pack_bf16x2(bf16_lo(a.w) + tau * acc[6], bf16_hi(a.w) + tau * acc[7]);
+    *reinterpret_cast<uint4*>(Oout + row * kD + 8 * sub) = o;
+  }
 }
 
 hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
                       const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
-                      hipStream_t st) {
+                      const GateArgs& G, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
   if (P0.bk == 128) {
     static std::atomic<uint64_t> ready;
@@ -517,7 +532,8 @@ hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
     const int64_t rows = (int64_t)P.T * P.nj * P.g;
     ProfScope ps(KID_FWD_MERGE, st);
     hipLaunchKernelGGL(k_fwd_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P, (const bf16_t*)opart,
-                       (const float*)lse_part, p.vmask, p.slotpos, p.off, (bf16_t*)O, LSE);
+                       (const float*)lse_part, p.vmask, p.slotpos, p.off, (bf16_t*)O, LSE, G.gate,
+                       (const bf16_t*)G.o_acc, (bf16_t*)G.o_out);
   }
   return hipGetLastError();
 }

@@ -301,3 +301,20 @@ def draw_block_scores(seed: int, seqlens: Sequence[int], hkv: int, block: int = 
     with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
         list(pool.map(work, range(0, T, _SLAB_TOKENS)))
     return out
+
+
+# ----------------------------------------------------------------------------- gates (input of the gated combination)
+def draw_gates(seed: int, T: int, hq: int) -> np.ndarray:
+    """float32 [T, hq] gate values in [0, 1]: a logistic squashing of standard normals (what a sigmoid gate layer
+    emits), with about 2 % of the entries set to exactly 0 and 2 % to exactly 1."""
+    r = np.random.default_rng([seed, 8])
+    g = (1.0 / (1.0 + np.exp(-1.5 * r.standard_normal((T, hq))))).astype(np.float32)
+    u = r.random((T, hq))
+    g[u < 0.02] = 0.0
+    g[u > 0.98] = 1.0
+    return g
+
+
+def draw_other_branches(seed: int, T: int, hq: int, d: int = HEAD_DIM) -> np.ndarray:
+    """bf16 bit patterns [T, hq, d]: a stand-in for the gated sum of the other attention branches."""
+    return _draw_bf16(seed, 4, T, hq, d)
