@@ -243,6 +243,8 @@ __device__ __forceinline__ bool select_by_threshold(const RowInfo& R, int lane, 
   return true;
 }
 
+}  // namespace
+
 template <bool kVec>
 __global__ void __launch_bounds__(64 * kSelWaves)
 k_select_blocks(const float* __restrict__ scores, int64_t stride, const int32_t* __restrict__ cu, int T, int nseq,
@@ -286,7 +288,6 @@ k_select_blocks(const float* __restrict__ scores, int64_t stride, const int32_t*
   if (lane < topk && (!by_rank || lane < R.n_forced || lane >= R.n_forced + n_picks)) out_row[lane] = mine;
 }
 
-}  // namespace
 }  // namespace nsa
 
 using namespace nsa;
