@@ -24,6 +24,11 @@ Backward (the paper gives no formulas; this is the derivative of the definition 
       dQ[t,h] = scale * sum_u ds_u K[u,j]
       dK[u,j] += scale * ds_u Q[t,h]          dV[u,j] += p_u dO[t,h]      (summed over all (t,h) that see u)
 
+Sliding window (the `win` term of Eq. (2); the paper gives neither a window length nor a kernel for it): with
+window = w > 0 (causal only) a key u is visible to token t only if t - w < u <= t; run with idx listing the blocks
+the window touches (the token's own block and the ceil((w - 1) / B_K) before it) the definitions above give softmax
+attention over the last w tokens.  A selected block that lies wholly before the window is dropped like a future one.
+
 Index inversion (paper Sec. 3.2: the per-KV-block query list I_i; here with the slot it came from):
   for every (KV head, global block) the ascending list of tokens that validly select it and the column of
   `idx` holding the first occurrence.  Global block ids number the blocks of the packed sequences
@@ -55,8 +60,10 @@ def _seq_of(cu: np.ndarray, t: int) -> int:
     return int(np.searchsorted(cu, t, side="right") - 1)
 
 
-def selected_set(idx_row: Sequence[int], cur: int, b_s: int, causal: bool) -> List[int]:
-    """Valid block ids of one (token, kv head) row, ascending, each once."""
+def selected_set(idx_row: Sequence[int], cur: int, b_s: int, causal: bool, *, window: int = 0, p: int = 0,
+                 block: int = 64) -> List[int]:
+    """Valid block ids of one (token, kv head) row, ascending, each once.  With a window (see visible_keys) a block
+    whose last token lies before the window of the token at local position p is dropped like a future block."""
     out = set()
     for x in idx_row:
         x = int(x)
@@ -64,23 +71,31 @@ def selected_set(idx_row: Sequence[int], cur: int, b_s: int, causal: bool) -> Li
             continue
         if causal and x > cur:
             continue
+        if window > 0 and x != cur and (x + 1) * block - 1 < p - window + 1:
+            continue
         out.add(x)
     return sorted(out)
 
 
-def visible_keys(cu: np.ndarray, t: int, idx_row: Sequence[int], block: int, causal: bool) -> np.ndarray:
-    """Global token ids of the keys token t may attend to for one kv head, ascending."""
+def visible_keys(cu: np.ndarray, t: int, idx_row: Sequence[int], block: int, causal: bool,
+                 window: int = 0) -> np.ndarray:
+    """Global token ids of the keys token t may attend to for one kv head, ascending.  window > 0 (causal only)
+    additionally hides the keys u <= t - window: with idx listing the blocks the window touches this is the
+    sliding-window term of Eq. (2), softmax over the last `window` tokens."""
+    assert window == 0 or causal
     s = _seq_of(cu, t)
     c0, c1 = int(cu[s]), int(cu[s + 1])
     p = t - c0
     b_s = -(-(c1 - c0) // block)
     keys: List[int] = []
-    for x in selected_set(idx_row, p // block, b_s, causal):
+    for x in selected_set(idx_row, p // block, b_s, causal, window=window, p=p, block=block):
         lo = c0 + x * block
         hi = min(lo + block, c1)
         for u in range(lo, hi):
             if causal and u > t:
                 break
+            if window > 0 and u <= t - window:
+                continue
             keys.append(u)
     return np.asarray(keys, dtype=np.int64)
 
@@ -96,7 +111,8 @@ def _row_forward(q: np.ndarray, Kv: np.ndarray, Vv: np.ndarray, scale: float):
 
 
 def forward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, idx: np.ndarray, cu: np.ndarray, *, block: int = 64,
-            causal: bool = True, scale: Optional[float] = None, tokens: Optional[Iterable[int]] = None):
+            causal: bool = True, scale: Optional[float] = None, tokens: Optional[Iterable[int]] = None,
+            window: int = 0):
     """O [T, hq, d] and LSE [T, hq] (float64).  With `tokens`, only those rows are computed (others stay 0 /
     -inf) so that a sample of a large problem can be checked."""
     T, hq, d = Q.shape
@@ -107,7 +123,7 @@ def forward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, idx: np.ndarray, cu: np
     LSE = np.full((T, hq), -np.inf, dtype=np.float64)
     for t in (range(T) if tokens is None else tokens):
         for j in range(hkv):
-            keys = visible_keys(cu, t, idx[t, j], block, causal)
+            keys = visible_keys(cu, t, idx[t, j], block, causal, window)
             if keys.size == 0:
                 continue
             Kv = K[keys, j]
@@ -119,7 +135,7 @@ def forward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, idx: np.ndarray, cu: np
 
 def backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarray, idx: np.ndarray, cu: np.ndarray, *,
              block: int = 64, causal: bool = True, scale: Optional[float] = None,
-             tokens: Optional[Iterable[int]] = None):
+             tokens: Optional[Iterable[int]] = None, window: int = 0):
     """dQ [T, hq, d], dK, dV [T, hkv, d] (float64).  With `tokens`, only those query rows contribute (dQ of
     those rows is complete; dK/dV are then partial sums and only useful for additivity checks)."""
     T, hq, d = Q.shape
@@ -131,7 +147,7 @@ def backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarray, idx: n
     dV = np.zeros(V.shape, dtype=np.float64)
     for t in (range(T) if tokens is None else tokens):
         for j in range(hkv):
-            keys = visible_keys(cu, t, idx[t, j], block, causal)
+            keys = visible_keys(cu, t, idx[t, j], block, causal, window)
             if keys.size == 0:
                 continue
             Kv = K[keys, j]
@@ -148,7 +164,7 @@ def backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarray, idx: n
 
 
 def invert_index(idx: np.ndarray, cu: np.ndarray, *, block: int = 64, causal: bool = True,
-                 kv_heads: Optional[Iterable[int]] = None):
+                 kv_heads: Optional[Iterable[int]] = None, window: int = 0):
     """Per-(kv head, global block) query lists, built by one sequential pass in token order.
 
     Returns (cnt [hkv, b_tot] int32, off [hkv*b_tot + 1] int64 row-major over (kv head, block),
@@ -173,6 +189,8 @@ def invert_index(idx: np.ndarray, cu: np.ndarray, *, block: int = 64, causal: bo
                 x = int(idx[t, j, m])
                 if x < 0 or x >= nblk[s] or (causal and x > cur) or x in seen:
                     continue
+                if not selected_set([x], cur, nblk[s], causal, window=window, p=t - int(cu[s]), block=block):
+                    continue                            # wholly before the token's window
                 seen.add(x)
                 bits |= 1 << m
                 lists[j * b_tot + int(base[s]) + x].append((t, m))

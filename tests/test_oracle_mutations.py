@@ -33,7 +33,7 @@ def _row_forward_no_scale(q, Kv, Vv, scale):
     return orc_row_forward(q, Kv, Vv, 1.0)
 
 
-def _visible_keys_no_inblock_mask(cu, t, idx_row, block, causal):
+def _visible_keys_no_inblock_mask(cu, t, idx_row, block, causal, window=0):
     s = orc._seq_of(cu, t)
     c0, c1 = int(cu[s]), int(cu[s + 1])
     keys = []
@@ -42,11 +42,11 @@ def _visible_keys_no_inblock_mask(cu, t, idx_row, block, causal):
     return np.asarray(keys, dtype=np.int64)
 
 
-def _selected_set_drops_current(idx_row, cur, b_s, causal):
+def _selected_set_drops_current(idx_row, cur, b_s, causal, **kw):
     return sorted({int(x) for x in idx_row if 0 <= int(x) < b_s and (not causal or int(x) < cur)})   # < for <=
 
 
-def _selected_set_multiset(idx_row, cur, b_s, causal):
+def _selected_set_multiset(idx_row, cur, b_s, causal, **kw):
     return sorted(int(x) for x in idx_row if 0 <= int(x) < b_s and (not causal or int(x) <= cur))   # repeats kept
 
 
@@ -123,3 +123,14 @@ def test_gated_combination_mistake_is_caught(monkeypatch, kind):
     monkeypatch.setattr(orc, "gated_backward", bwd)
     with pytest.raises(AssertionError):
         pins.test_gated_combination_equals_autograd_of_dense_formulation()
+
+
+def test_window_off_by_one_is_caught(monkeypatch):
+    real = orc.visible_keys
+
+    def wider(cu, t, idx_row, block, causal, window=0):            # keeps u = t - window as well
+        return real(cu, t, idx_row, block, causal, window + 1 if window else 0)
+    pins.test_window_rows_give_banded_attention(100)
+    monkeypatch.setattr(orc, "visible_keys", wider)
+    with pytest.raises(AssertionError):
+        pins.test_window_rows_give_banded_attention(100)

@@ -148,6 +148,59 @@ def test_gated_combination_equals_autograd_of_dense_formulation():
     np.testing.assert_array_equal(orc.gated_forward(O, gate)[5], 0.0)
 
 
+def _band_mask(cu, hkv, window):
+    T = int(cu[-1])
+    tok = np.arange(T)
+    seq = np.searchsorted(cu, tok, side="right") - 1
+    m = (seq[:, None] == seq[None, :]) & (tok[None, :] <= tok[:, None]) & (tok[None, :] > tok[:, None] - window)
+    return np.broadcast_to(m, (hkv, T, T)).copy()
+
+
+@pytest.mark.parametrize("window", [1, 64, 100, 129, 1000])
+def test_window_rows_give_banded_attention(window):
+    """The sliding-window term of Eq. (2): with idx listing the blocks the window touches and window = w, forward
+    and backward equal dense attention under the band mask t - w < u <= t (torch softmax + autograd)."""
+    seqlens = [300, 70, 1, 200]
+    rng = np.random.default_rng(40 + window)
+    T, hq, hkv, d = sum(seqlens), 4, 2, 16
+    cu = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int32)
+    idx = wl.window_block_indices(seqlens, hkv, window)
+    Q, K, V, dO = (rng.standard_normal((T, h, d)) for h in (hq, hkv, hkv, hq))
+    scale = 0.25
+    O, LSE = orc.forward(Q, K, V, idx, cu, scale=scale, window=window)
+    dQ, dK, dV = orc.backward(Q, K, V, dO, idx, cu, scale=scale, window=window)
+    M = _band_mask(cu, hkv, window)
+    O2, LSE2 = _dense_forward_np(Q, K, V, M, scale)
+    np.testing.assert_allclose(O, O2, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(LSE, LSE2, rtol=0, atol=1e-12)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    _dense_torch(tq, tk, tv, M, scale).backward(torch.from_numpy(dO))
+    np.testing.assert_allclose(dQ, tq.grad.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dK, tk.grad.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dV, tv.grad.numpy(), rtol=0, atol=1e-11)
+
+
+def test_window_drops_blocks_wholly_outside_and_inversion_follows():
+    """A listed (token, block) pair survives the inversion exactly when the block holds a key inside the window."""
+    seqlens = [400, 130]
+    window = 100
+    cu = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int32)
+    rng = np.random.default_rng(50)
+    idx = wl.draw_block_indices(rng, seqlens, 2, 5, sink=True, recent=2, local_picks=2, local_window=4)
+    cnt, off, qlist, qslot, vmask = orc.invert_index(idx, cu, window=window)
+    M = _dense_mask(idx, cu, True) & _band_mask(cu, 2, window)
+    nblk = [-(-L // B) for L in seqlens]
+    base = [0, nblk[0]]
+    for j in range(2):
+        for s in range(2):
+            for x in range(nblk[s]):
+                lst = qlist[off[j * sum(nblk) + base[s] + x]: off[j * sum(nblk) + base[s] + x + 1]]
+                keys = slice(int(cu[s]) + x * B, min(int(cu[s]) + (x + 1) * B, int(cu[s + 1])))
+                expect = np.nonzero(M[j][:, keys].any(axis=1))[0]
+                assert np.array_equal(lst, expect), (j, s, x)
+    assert cnt.sum() < orc.invert_index(idx, cu)[0].sum()       # the window did drop pairs
+
+
 @pytest.mark.parametrize("causal", [True, False])
 def test_all_blocks_selected_is_full_attention(causal):
     """Top-k covering every block reduces the sel branch to Eq. (1); torch's SDPA is the library routine."""

@@ -318,3 +318,18 @@ def draw_gates(seed: int, T: int, hq: int) -> np.ndarray:
 def draw_other_branches(seed: int, T: int, hq: int, d: int = HEAD_DIM) -> np.ndarray:
     """bf16 bit patterns [T, hq, d]: a stand-in for the gated sum of the other attention branches."""
     return _draw_bf16(seed, 4, T, hq, d)
+
+
+# ----------------------------------------------------------------------------- sliding-window rows
+def window_block_indices(seqlens: Sequence[int], hkv: int, window: int, block: int = BLOCK) -> np.ndarray:
+    """int32 [total_tokens, hkv, R + 1], R = ceil((window - 1) / block): the token's own block and the R blocks before
+    it, most recent first, -1 where the sequence has no such block.  These are the blocks a causal window of
+    `window` tokens can touch; which of their keys are inside the window is decided by whoever consumes the table."""
+    R = -(-(window - 1) // block)
+    per_seq = []
+    for L in seqlens:
+        cur = np.arange(L, dtype=np.int64) // block
+        tab = cur[:, None] - np.arange(R + 1, dtype=np.int64)[None, :]
+        tab = np.where(tab >= 0, tab, -1)
+        per_seq.append(np.repeat(tab[:, None, :], hkv, axis=1))
+    return np.concatenate(per_seq, axis=0).astype(np.int32)
