@@ -36,7 +36,8 @@ extern "C" {
 #endif
 
 #define NSA_SEL_OK            0
-#define NSA_SEL_EINVAL       -1   /* null/misaligned pointer, g not in [1,8], hq % hkv != 0, nseq < 1, negative size */
+#define NSA_SEL_EINVAL       -1   /* null/misaligned pointer, g not in [1,8], hq % hkv != 0, nseq < 1, negative size,
+                                     window < 0 or window without causal                                      */
 #define NSA_SEL_EUNSUPPORTED -2   /* d != 128, block not 64 or 128, topk outside [1,32], too many tokens      */
 #define NSA_SEL_EWORKSPACE   -3   /* index workspace too small, or ws below nsa_sel_workspace_bytes_min       */
 #define NSA_SEL_EHIP         -4   /* the HIP runtime refused a launch or attribute                            */
@@ -51,6 +52,11 @@ typedef struct {
   int32_t causal;         /* 1: key u visible to token t only if u <= t (per sequence); 0: no mask           */
   float   scale;          /* softmax scale; <= 0 selects 1/sqrt(d) (Eq. (1))                                 */
   int32_t max_seqlen;     /* upper bound of the longest sequence; informational, may be 0                    */
+  int32_t window;         /* 0: none.  w > 0 (needs causal = 1): key u is visible to token t only if u > t - w;
+                             a selected block wholly before the window is ignored like a future one.  With idx
+                             listing the blocks a window can touch (the token's own and the ceil((w-1)/block)
+                             before it; nsa_sel_select_blocks with scores = NULL writes that table) the path
+                             computes the sliding-window term of Eq. (2), softmax over the last w tokens       */
 } nsa_sel_shape;
 
 /* Bytes of the three caller-owned workspaces for `shape` (any of the outputs may be NULL).
@@ -129,7 +135,8 @@ int nsa_sel_bwd_gated(const nsa_sel_shape* shape, const void* Q, const void* K, 
  *             NaN ranks as -infinity), cut to shape->topk columns, padded with -1.
  * scores is DEVICE fp32 [total_tokens, hkv, score_stride], column b = score of block b of the token's own sequence;
  * score_stride (floats, 1 .. 16384) must be at least the block count of the longest sequence; only visible,
- * non-forced columns are read.  idx is DEVICE int32 [total_tokens, hkv, topk], fully overwritten.  Uses
+ * non-forced columns are read.  scores may be NULL: then only the forced blocks are written (with n_sink = 0 and
+ * n_local = topk = ceil((w - 1) / block) + 1 that is the block table of a sliding window of w tokens).  idx is DEVICE int32 [total_tokens, hkv, topk], fully overwritten.  Uses
  * shape->total_tokens, nseq, hkv, block, topk and causal; the other fields are ignored.  Exact: scores are only
  * compared, never altered.  16-byte loads are used when scores is 16-byte aligned and score_stride % 4 == 0. */
 int nsa_sel_select_blocks(const nsa_sel_shape* shape, const float* scores, int64_t score_stride,

@@ -5,4 +5,4 @@ only; every step of the path runs in the library's HIP kernels.  There is no CPU
 library, or without a GPU, the calls raise.
 """
 from .binding import (NsaSelError, Shape, build_index, index_view, lib, nsa_sel_bwd, nsa_sel_fwd,  # noqa: F401
-                      workspace_bytes, workspace_bytes_min, SelAttention, select_blocks, profile_enable, profile_select, profile_collect, calibration_copy, mfma_probe, SYMBOLS)
+                      workspace_bytes, workspace_bytes_min, SelAttention, select_blocks, window_blocks, profile_enable, profile_select, profile_collect, calibration_copy, mfma_probe, SYMBOLS)

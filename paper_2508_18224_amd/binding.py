@@ -22,7 +22,7 @@ class NsaSelError(RuntimeError):
 class Shape(C.Structure):
     _fields_ = [("total_tokens", C.c_int32), ("nseq", C.c_int32), ("hq", C.c_int32), ("hkv", C.c_int32),
                 ("d", C.c_int32), ("block", C.c_int32), ("topk", C.c_int32), ("causal", C.c_int32),
-                ("scale", C.c_float), ("max_seqlen", C.c_int32)]
+                ("scale", C.c_float), ("max_seqlen", C.c_int32), ("window", C.c_int32)]
 
 
 def lib():
@@ -128,6 +128,19 @@ def select_blocks(scores: torch.Tensor, cu: Optional[torch.Tensor], topk: int, *
     return out
 
 
+def window_blocks(total_tokens: int, hkv: int, window: int, cu: Optional[torch.Tensor] = None, *, block: int = 64,
+                  device="cuda:0"):
+    """idx int32 [tokens, hkv, R + 1], R = ceil((window - 1) / block): the blocks a causal window of `window` tokens
+    can touch, most recent first (nsa_sel_select_blocks with no scores: forced local blocks only)."""
+    topk = -(-(window - 1) // block) + 1
+    nseq = 1 if cu is None else cu.numel() - 1
+    shape = Shape(total_tokens, nseq, hkv, hkv, 128, block, topk, 1, 0.0, 0)
+    out = torch.empty(total_tokens, hkv, topk, dtype=torch.int32, device=device)
+    _check(lib().nsa_sel_select_blocks(C.byref(shape), None, 0, _ptr(cu), 0, topk, _ptr(out), _stream()),
+           "nsa_sel_select_blocks")
+    return out
+
+
 def profile_enable(capacity: int):
     _check(lib().nsa_sel_profile_enable(int(capacity)), "nsa_sel_profile_enable")
 
@@ -173,10 +186,10 @@ class SelAttention:
     """Owns the workspaces for one shape and calls the library (buffers are torch uint8 tensors)."""
 
     def __init__(self, total_tokens, hq, hkv, topk, *, nseq=1, causal=True, scale=0.0, device="cuda:0", bwd=True,
-                 block=64, ws_cap_bytes=None):
+                 block=64, ws_cap_bytes=None, window=0):
         """ws_cap_bytes caps each of the forward / backward workspaces (never below the library's minimum);
         the library then works through the KV heads in as many passes as needed."""
-        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0)
+        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0, int(window))
         fb, bb, ib = workspace_bytes(self.shape)
         if ws_cap_bytes is not None:
             fmin, bmin = workspace_bytes_min(self.shape)

@@ -15,6 +15,7 @@ static int check_shape(const nsa_sel_shape* s) {
   if (s->hq % s->hkv != 0) return NSA_SEL_EINVAL;
   const int g = s->hq / s->hkv;
   if (g < 1 || g > 8) return NSA_SEL_EINVAL;
+  if (s->window < 0 || (s->window > 0 && !s->causal)) return NSA_SEL_EINVAL;
   if (s->d != kD || (s->block != kBlock && s->block != 2 * kBlock)) return NSA_SEL_EUNSUPPORTED;
   if (s->topk < 1 || s->topk > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
   if (s->nseq > (1 << 20)) return NSA_SEL_EUNSUPPORTED;
@@ -37,6 +38,7 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.topk = s->topk;
   L.bk = s->block;
   L.causal = s->causal ? 1 : 0;
+  L.window = s->window;
   L.b_cap = s->total_tokens / s->block + s->nseq;
   L.n_lists = s->hkv * L.b_cap;
   L.n_chunks = (s->total_tokens + kChunkTokens - 1) / kChunkTokens;
@@ -74,6 +76,7 @@ static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
   P.g = s->hq / s->hkv;
   P.topk = L.topk;
   P.causal = s->causal ? 1 : 0;
+  P.window = s->window;
   P.b_cap = L.b_cap;
   P.bk = L.bk;
   P.unit = L.unit;

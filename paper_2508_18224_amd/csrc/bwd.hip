@@ -109,7 +109,7 @@ struct BwdLds {
 static_assert(2 * BwdLds<2>::Bytes <= 160 * 1024, "two workgroups of the 64-key backward must fit one CU's LDS");
 static_assert(BwdLds<4>::Bytes <= 160 * 1024, "the 128-key backward must fit one CU's LDS");
 
-template <int NKB>
+template <int NKB, bool kWin>
 __global__ void __launch_bounds__(128 * NKB, NKB == 2 ? 2 : 1)
 k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
             const bf16_t* __restrict__ dO, const float2* __restrict__ stats, const int32_t* __restrict__ u_list,
@@ -232,6 +232,8 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
       const int t = valid ? ent[div_g(r, P.g, P.g_magic) - seg0] : -1;
       int lim = P.causal ? min(blen, t - tok0 + 1) : blen;  // keys [0, lim) of the block are visible to this row
       if (!valid) lim = 0;
+      // kWin: the kernel variant for a sliding window, whose rows also hide the keys before lo
+      const int lo = kWin ? t - P.window + 1 - tok0 : 0;
       __syncthreads();  // Q / dO tile staged by all waves
 
       {  // role rows/keys
@@ -258,7 +260,7 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = 32 * kb + 8 * (v >> 2) + 4 * qh + (v & 3);
-          const float p = key < lim ? __builtin_amdgcn_exp2f(fmaf(sacc[v], c2, -lse2)) : 0.f;
+          const float p = (key < lim && (!kWin || key >= lo)) ? __builtin_amdgcn_exp2f(fmaf(sacc[v], c2, -lse2)) : 0.f;
           const float ds = p * fmaf(dpacc[v], P.scale, -dls);  // P (dP - delta) scale
           pdst[key * kPStride] = (bf16_t)p;
           sdst[key * kPStride] = (bf16_t)ds;
@@ -449,12 +451,14 @@ hipError_t launch_bwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
   // 64-token blocks: four waves, two workgroups per CU; 128-token blocks: eight waves, one workgroup per CU
   const bool b128 = P0.bk == 128;
-  auto* main_kernel = b128 ? k_bwd_tiled<4> : k_bwd_tiled<2>;
+  const bool win = P0.window > 0;
+  auto* main_kernel = b128 ? (win ? k_bwd_tiled<4, true> : k_bwd_tiled<4, false>)
+                           : (win ? k_bwd_tiled<2, true> : k_bwd_tiled<2, false>);
   const int main_threads = b128 ? 512 : 256;
   const int main_lds = b128 ? BwdLds<4>::Bytes : BwdLds<2>::Bytes;
   {
-    static std::atomic<uint64_t> ready[2];
-    hipError_t e = allow_dynamic_lds((const void*)main_kernel, main_lds, ready[b128]);
+    static std::atomic<uint64_t> ready[4];
+    hipError_t e = allow_dynamic_lds((const void*)main_kernel, main_lds, ready[2 * win + b128]);
     if (e != hipSuccess) return e;
   }
   {

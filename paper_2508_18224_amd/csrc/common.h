@@ -22,6 +22,7 @@ constexpr int kSlotBatch = 4;      // slots of a row the two reduction kernels g
 // Host-computed description of the index workspace (byte offsets from its base, all 256-aligned).
 struct IndexLayout {
   int32_t T, nseq, hkv, topk, causal;
+  int32_t window;       // 0 or the sliding-window length in tokens
   int32_t bk;           // B_K: tokens per KV block, 64 or 128
   int32_t b_cap;        // list stride: T / bk + nseq  (>= real number of blocks)
   int32_t n_lists;      // hkv * b_cap
@@ -77,6 +78,7 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
 // Problem description handed to the attention kernels.
 struct Problem {
   int32_t T, nseq, hq, hkv, g, topk, causal, b_cap, bk;
+  int32_t window;    // 0, or: key u is visible to token t only if u > t - window
   uint32_t g_magic;  // floor(2^32 / g) + 1, or 0 when g == 1: row / g as one multiply-high (see div_g)
   int32_t unit;    // list entries per work unit
   int32_t j0, nj;  // KV heads [j0, j0 + nj) handled by this launch (all of them unless the workspace is capped)

@@ -136,11 +136,12 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     const int t = valid ? ent[div_g(r, P.g, P.g_magic)] : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
-    // Only tiles with a row in the block itself (causal diagonal) or a ragged block end need the key mask; the
-    // test is wave-uniform.  The maximum is taken over the raw scores (the scale is positive) and the scale is
+    const int lo = P.window > 0 ? t - P.window + 1 - tok0 : 0;  // with a window, keys before lo are hidden (<= 0: none)
+    // Only tiles with a row in the block itself (causal diagonal), a ragged block end or a window edge need the
+    // key mask; the test is wave-uniform.  The maximum is taken over the raw scores (the scale is positive) and the scale is
     // folded into the exponent: p = 2^(s c2 - m c2).
     float m = -INFINITY;
-    if (__builtin_amdgcn_ballot_w64(lim < kBlock) == 0) {
+    if (__builtin_amdgcn_ballot_w64(lim < kBlock || lo > 0) == 0) {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -151,7 +152,7 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
-          const float x = key < lim ? sacc[mb][v] : -INFINITY;
+          const float x = (key < lim && key >= lo) ? sacc[mb][v] : -INFINITY;
           sacc[mb][v] = x;
           m = fmaxf(m, x);
         }
@@ -337,10 +338,11 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
     const int t = valid ? ent[div_g(r, P.g, P.g_magic)] : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
-    // key mask only where a row lies in the block itself or the block is ragged (wave-uniform test); maximum over
+    const int lo = P.window > 0 ? t - P.window + 1 - tok0 : 0;  // with a window, keys before lo are hidden
+    // key mask only where a row lies in the block itself, the block is ragged or a window edge falls into it (wave-uniform test); maximum over
     // the raw scores, scale folded into the exponent
     float m = -INFINITY;
-    if (__builtin_amdgcn_ballot_w64(lim < 2 * kBlock) == 0) {
+    if (__builtin_amdgcn_ballot_w64(lim < 2 * kBlock || lo > 0) == 0) {
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -351,7 +353,7 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
-          const float x = key < lim ? sacc[mb][v] : -INFINITY;
+          const float x = (key < lim && key >= lo) ? sacc[mb][v] : -INFINITY;
           sacc[mb][v] = x;
           m = fmaxf(m, x);
         }

@@ -55,12 +55,14 @@ __global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int bk, 
 }
 
 // Bit m of the result is set when column m of the row is a kept selection: in range for the sequence, not in
-// the token's future when causal, and not a repeat of an earlier column.
-__device__ __forceinline__ uint32_t kept_columns(const int32_t* row, int k, int b_s, int cur, int causal) {
+// the token's future when causal, not wholly before the token's window (first_blk = the block of the oldest
+// visible key, 0 without a window), and not a repeat of an earlier column.
+__device__ __forceinline__ uint32_t kept_columns(const int32_t* row, int k, int b_s, int cur, int causal,
+                                                 int first_blk) {
   uint32_t vm = 0;
   for (int m = 0; m < k; ++m) {
     int x = row[m];
-    const bool ok = x >= 0 && x < b_s && (!causal || x <= cur);
+    const bool ok = x >= first_blk && x < b_s && (!causal || x <= cur);
     bool dup = false;  // no early exit: the reads of the earlier columns are independent and overlap
     for (int mp = 0; mp < m; ++mp) dup |= row[mp] == x;
     if (ok && !dup) vm |= 1u << m;
@@ -86,7 +88,7 @@ __device__ __forceinline__ void chunk_window(const int32_t* cu, const int32_t* b
 // array needs no clearing.  Dynamic LDS: b_cap ints + 256*(k+1) ints.
 __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
                                               const int32_t* __restrict__ blk_base, int nseq, int T, int hkv, int k,
-                                              int bk, int causal, int b_cap, int n_chunks,
+                                              int bk, int causal, int window, int b_cap, int n_chunks,
                                               int32_t* __restrict__ counters, uint32_t* __restrict__ vmask) {
   extern __shared__ int32_t lds[];
   int32_t* hist = lds;
@@ -106,7 +108,9 @@ __global__ void __launch_bounds__(256) k_hist(const int32_t* __restrict__ idx, c
     for (int m = 0; m < k; ++m) row[m] = src[m];
     const int b_s = (c1 - c0 + bk - 1) / bk;
     const int cur = (t - c0) / bk;
-    const uint32_t vm = kept_columns(row, k, b_s, cur, causal);
+    // oldest key a window of `window` tokens shows to this token: position p - window + 1 of its sequence
+    const int first_blk = window > 0 ? max(t - c0 - window + 1, 0) / bk : 0;
+    const uint32_t vm = kept_columns(row, k, b_s, cur, causal, first_blk);
     vmask[(size_t)t * hkv + j] = vm;
     const int base = blk_base[s] - gb_lo;
     for (int m = 0; m < k; ++m)
@@ -391,7 +395,7 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
                      p.hdr); }
   { ProfScope ps(KID_INDEX_HIST, st);
   hipLaunchKernelGGL(k_hist, dim3(L.n_chunks, L.hkv), dim3(256), lds_hist, st, idx, cu, p.blk_base, L.nseq, L.T, L.hkv,
-                     L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.vmask); }
+                     L.topk, L.bk, L.causal, L.window, L.b_cap, L.n_chunks, p.chunk_off, p.vmask); }
   const int nl1 = L.n_lists + 1;
   { ProfScope ps(KID_INDEX_CHUNK_PREFIX, st);
   hipLaunchKernelGGL(k_chunk_prefix, dim3((L.b_cap + 63) / 64, L.hkv), dim3(256), 0, st, p.chunk_off, L.b_cap, L.n_chunks,

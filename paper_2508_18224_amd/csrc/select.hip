@@ -279,8 +279,11 @@ k_select_blocks(const float* __restrict__ scores, int64_t stride, const int32_t*
   int mine = -1;                           // lane i holds column i of the output row: forced blocks, then -1
   if (lane < R.n_forced) mine = lane < R.ns ? lane : R.loc_hi - (lane - R.ns);
   const int n_free = R.b_vis - R.ns - R.nl;                  // selectable blocks
-  const int n_picks = R.want < n_free ? R.want : n_free;     // columns the selection fills
+  int n_picks = R.want < n_free ? R.want : n_free;           // columns the selection fills
   bool by_rank = true;                     // pick columns already written, each by the lane that ranked there
+  if (n_picks > 0 && scores == nullptr) {
+    n_picks = 0;                           // forced blocks only: the rest of the row is padding
+  }
   if (n_picks > 0) {
     by_rank = select_by_threshold<kVec>(R, lane, lds[w], out_row);
     if (!by_rank) mine = select_by_rounds<kVec>(R, lane, reinterpret_cast<uint32_t*>(lds[w]), mine);
@@ -299,8 +302,9 @@ extern "C" int nsa_sel_select_blocks(const nsa_sel_shape* shape, const float* sc
   if (shape->total_tokens < 0 || shape->nseq < 1 || shape->hkv < 1 || n_sink < 0 || n_local < 0) return NSA_SEL_EINVAL;
   if (shape->block != kBlock && shape->block != 2 * kBlock) return NSA_SEL_EUNSUPPORTED;
   if (shape->topk < 1 || shape->topk > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
+  if (!scores) score_stride = (int64_t)kMaxChunks * kChunkBlocks;   // no rows to stay inside
   if (score_stride < 1 || score_stride > (int64_t)kMaxChunks * kChunkBlocks) return NSA_SEL_EUNSUPPORTED;
-  if (!scores || !idx || ((uintptr_t)scores & 3) || ((uintptr_t)idx & 3)) return NSA_SEL_EINVAL;
+  if (!idx || ((uintptr_t)scores & 3) || ((uintptr_t)idx & 3)) return NSA_SEL_EINVAL;   // scores may be NULL
   if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
   const int64_t rows = (int64_t)shape->total_tokens * shape->hkv;
   if (rows == 0) return NSA_SEL_OK;
