@@ -205,7 +205,7 @@ def invert_index(idx: np.ndarray, cu: np.ndarray, *, block: int = 64, causal: bo
 
 def backward_kv_blocks(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarray, idx: np.ndarray,
                        cu: np.ndarray, blocks: Sequence[Tuple[int, int, int]], *, block: int = 64,
-                       causal: bool = True, scale: Optional[float] = None):
+                       causal: bool = True, scale: Optional[float] = None, window: int = 0):
     """dK, dV of a few KV blocks of a large problem: `blocks` holds (kv head j, sequence s, local block x).
     Every token of sequence s that validly selects the block is revisited in full (its softmax needs all of
     its visible keys).  Returns a list of (dK_blk, dV_blk) float64 arrays of shape [keys_in_block, d]."""
@@ -223,9 +223,9 @@ def backward_kv_blocks(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarr
         dVb = np.zeros((hi - lo, d), dtype=np.float64)
         first = lo if causal else c0
         for t in range(first, c1):
-            if x not in selected_set(idx[t, j], (t - c0) // block, b_s, causal):
+            if x not in selected_set(idx[t, j], (t - c0) // block, b_s, causal, window=window, p=t - c0, block=block):
                 continue
-            keys = visible_keys(cu, t, idx[t, j], block, causal)
+            keys = visible_keys(cu, t, idx[t, j], block, causal, window)
             inblk = (keys >= lo) & (keys < hi)
             Kv = K[keys, j]
             Vv = V[keys, j]

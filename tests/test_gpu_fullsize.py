@@ -37,25 +37,28 @@ def _visible_counts(w):
     return full + diag
 
 
-def _run_case(name, n_tokens, blocks):
-    print("full-size case", name, flush=True)
+def _run_case(name, n_tokens, blocks, window=0):
+    print("full-size case", name, "window", window, flush=True)
     w = wl.realise(wl.named(name))
+    if window:                                               # the sliding-window branch at the same shape
+        w.idx = wl.window_block_indices(w.seqlens, w.hkv, window, w.block)
+        w.topk = w.idx.shape[2]
     T, g = w.total_tokens, w.g
-    c = Case(w)
+    c = Case(w, window=window)
     o, lse = c.forward()
     dq, dk, dv = c.backward(o, lse)
     print("  gpu done", flush=True)
     Q, K, V, dO = (BitsF64(x) for x in (w.q, w.k, w.v, w.do))
     rng = np.random.default_rng(99)
     tokens = sorted({0, 63, 64, T - 1, *[int(x) for x in rng.integers(0, T, n_tokens)]})
-    O_ref, LSE_ref = orc.forward(Q, K, V, w.idx, w.cu_seqlens, block=w.block, tokens=tokens)
-    dQ_ref, _, _ = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, block=w.block, tokens=tokens)
+    O_ref, LSE_ref = orc.forward(Q, K, V, w.idx, w.cu_seqlens, block=w.block, tokens=tokens, window=window)
+    dQ_ref, _, _ = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, block=w.block, tokens=tokens, window=window)
     sel = torch.tensor(tokens, device="cuda")
     assert_close("O", to_f64(o[sel]), O_ref[tokens], TOL_O)
     assert np.abs(to_f64(lse[sel]) - LSE_ref[tokens]).max() <= TOL_LSE
     assert_close("dQ", to_f64(dq[sel]), dQ_ref[tokens], TOL_GRAD)
     print("  sampled rows ok", flush=True)
-    ref = orc.backward_kv_blocks(Q, K, V, dO, w.idx, w.cu_seqlens, blocks, block=w.block)
+    ref = orc.backward_kv_blocks(Q, K, V, dO, w.idx, w.cu_seqlens, blocks, block=w.block, window=window)
     for (j, s, x), (dKb, dVb) in zip(blocks, ref):
         lo = int(w.cu_seqlens[s]) + x * w.block
         hi = lo + dKb.shape[0]
@@ -70,7 +73,12 @@ def _run_case(name, n_tokens, blocks):
     # zero queries: LSE = ln(#visible keys), an integer count
     c.q.zero_()
     _, lse0 = c.forward(rebuild=False)
-    cnt = _visible_counts(w)
+    if window:                                               # the last `window` tokens of the sequence so far
+        tok = np.arange(T)
+        seq = np.searchsorted(w.cu_seqlens, tok, side="right") - 1
+        cnt = np.minimum(tok - w.cu_seqlens[seq] + 1, window)[:, None].repeat(w.hkv, axis=1)
+    else:
+        cnt = _visible_counts(w)
     want0 = torch.from_numpy(np.log(np.repeat(cnt, g, axis=1).astype(np.float64))).cuda()
     assert float((lse0.double() - want0).abs().max()) < 1e-4
     print("  closed forms ok", flush=True)
@@ -78,6 +86,10 @@ def _run_case(name, n_tokens, blocks):
 
 def test_headline_64k_g4():
     _run_case("headline", 12, [(0, 0, 0), (3, 0, 517), (7, 0, 1023)])
+
+
+def test_headline_shape_sliding_window_512():
+    _run_case("headline", 10, [(0, 0, 0), (4, 0, 600), (7, 0, 1023)], window=512)
 
 
 def test_llama8b_32k_g4():

@@ -93,3 +93,45 @@ def test_gated_argument_errors():
                                      a.index_ws.numel(), p(o), p(lse), p(gate), None, p(o), p(a.fwd_ws),
                                      a.fwd_ws.numel(), None)
     assert rc == -1
+
+
+def test_selected_and_window_branches_gated_into_one_output():
+    """Eq. (2) with two of its three branches from this library: out = acc + tau_sel * sel + tau_win * win, the second
+    call accumulating in place into the first one's output; gradients of each branch from its own backward."""
+    print("case two branches", flush=True)
+    w = wl.realise(wl.small("g4"))
+    window = 200
+    T = w.total_tokens
+    c_sel = Case(w, bwd=True)
+    w_win = wl.realise(wl.small("g4"))
+    w_win.idx = wl.window_block_indices(w.seqlens, w.hkv, window)
+    w_win.topk = w_win.idx.shape[2]
+    c_win = Case(w_win, bwd=True, window=window)
+    g_sel, g_win = wl.draw_gates(71, T, w.hq), wl.draw_gates(72, T, w.hq)
+    acc_bits = wl.draw_other_branches(73, T, w.hq)
+    out = dev_bf16(acc_bits).clone()
+    gs, gw = torch.from_numpy(g_sel).cuda(), torch.from_numpy(g_win).cuda()
+    _, o_sel, lse_sel = c_sel.attn.forward_gated(c_sel.q, c_sel.k, c_sel.v, c_sel.idx, gs, out, c_sel.cu, out=out)
+    _, o_win, lse_win = c_win.attn.forward_gated(c_win.q, c_win.k, c_win.v, c_win.idx, gw, out, c_win.cu, out=out)
+    torch.cuda.synchronize()
+    Q, K, V, dO = c_sel.host_f64()
+    r_sel, _ = orc.forward(Q, K, V, w.idx, w.cu_seqlens)
+    r_win, _ = orc.forward(Q, K, V, w_win.idx, w.cu_seqlens, window=window)
+    ref = orc.gated_forward(r_win, g_win.astype(np.float64),
+                            orc.gated_forward(r_sel, g_sel.astype(np.float64), wl.bf16_bits_to_f64(acc_bits)))
+    # three roundings to bf16 on the way (acc, + sel, + win): the absolute part of the tolerance doubles
+    assert_close("out", to_f64(out), ref, (2 * TOL_O[0], TOL_O[1]))
+    dq1, dk1, dv1, dg1 = c_sel.attn.backward_gated(c_sel.q, c_sel.k, c_sel.v, o_sel, lse_sel, c_sel.do, gs, c_sel.cu)
+    dq2, dk2, dv2, dg2 = c_win.attn.backward_gated(c_win.q, c_win.k, c_win.v, o_win, lse_win, c_win.do, gw, c_win.cu)
+    torch.cuda.synchronize()
+    rq1, rk1, rv1, rg1 = orc.gated_backward(Q, K, V, dO, g_sel.astype(np.float64), w.idx, w.cu_seqlens)
+    # the window branch's gradients by the same chain rule, with the window in force
+    O_w, _ = orc.forward(Q, K, V, w_win.idx, w.cu_seqlens, window=window)
+    rq2, rk2, rv2 = orc.backward(Q, K, V, g_win.astype(np.float64)[:, :, None] * dO, w_win.idx, w.cu_seqlens,
+                                 window=window)
+    rg2 = (dO * O_w).sum(axis=2)
+    for name, got, want in (("dQ", dq1.float() + dq2.float(), rq1 + rq2), ("dK", dk1.float() + dk2.float(), rk1 + rk2),
+                            ("dV", dv1.float() + dv2.float(), rv1 + rv2)):
+        assert_close(name, to_f64(got), want, (2 * TOL_GRAD[0], TOL_GRAD[1]))
+    assert_close("dgate sel", to_f64(dg1), rg1, TOL_GRAD)
+    assert_close("dgate win", to_f64(dg2), rg2, TOL_GRAD)
