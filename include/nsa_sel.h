@@ -21,6 +21,7 @@
  *   - cu_seqlens is int32 [nseq + 1] (device), cumulative sequence starts, cu_seqlens[nseq] == total_tokens;
  *     it may be NULL when nseq == 1.  Sequences need not be multiples of 64; the last block is ragged.
  *   - A row with no visible key gets O = 0, LSE = -inf and contributes no gradient.
+ *   - total_tokens == 0 is valid: the calls return NSA_SEL_OK without looking at the tensor pointers.
  *   - ws_bytes may lie anywhere between nsa_sel_workspace_bytes_min and nsa_sel_workspace_bytes (more is ignored).
  *   - Return value: 0 on success, a negative NSA_SEL_E* code otherwise.  Arguments are validated on the host
  *     before anything is launched; on error nothing has been enqueued (except NSA_SEL_EHIP, a launch failure).

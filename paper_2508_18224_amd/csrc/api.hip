@@ -140,6 +140,7 @@ int nsa_sel_build_index(const nsa_sel_shape* shape, const int32_t* idx, const in
                         size_t index_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
+  if (shape->total_tokens == 0) return NSA_SEL_OK;
   if (!idx || !index_ws || !aligned16(index_ws)) return NSA_SEL_EINVAL;
   if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
   IndexLayout L = make_layout(shape);
@@ -169,6 +170,7 @@ static int fwd_impl(const nsa_sel_shape* shape, const void* Q, const void* K, co
                     float* LSE, const GateArgs& G, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
+  if (shape->total_tokens == 0) return NSA_SEL_OK;  // nothing to do: zero-sized tensors may have no address
   if (!Q || !K || !V || !index_ws || !O || !LSE || !ws) return NSA_SEL_EINVAL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(ws) || !aligned16(index_ws))
     return NSA_SEL_EINVAL;
@@ -211,6 +213,7 @@ static int bwd_impl(const nsa_sel_shape* shape, const void* Q, const void* K, co
                     void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
+  if (shape->total_tokens == 0) return NSA_SEL_OK;  // nothing to do: zero-sized tensors may have no address
   if (!Q || !K || !V || !O || !LSE || !dO || !index_ws || !dQ || !dK || !dV || !ws) return NSA_SEL_EINVAL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(dQ) ||
       !aligned16(dK) || !aligned16(dV) || !aligned16(ws) || !aligned16(index_ws))
