@@ -62,20 +62,20 @@ typedef struct {
 
 /* Bytes of the three caller-owned workspaces for `shape` (any of the outputs may be NULL).
  *   index_bytes: query lists and work-unit tables, written by nsa_sel_build_index / nsa_sel_fwd(rebuild_index=1)
- *                and read by nsa_sel_fwd / nsa_sel_bwd (the paper's index tensors I_i, O_i "retrieved from
- *                cache" in the backward pass, Sec. 3.2);
+ *                and read by nsa_sel_fwd / nsa_sel_bwd (the paper's index tensors I_i, O_i, which its
+ *                backward pass reuses from the forward, Sec. 3.2);
  *   fwd_bytes:   per-(token, head, slot) partial outputs and log-sum-exps (the paper's O_buf, Sec. 3.2);
  *   bwd_bytes:   partial dQ, delta, and per-work-unit dK/dV partial sums. */
 int nsa_sel_workspace_bytes(const nsa_sel_shape* shape, size_t* fwd_bytes, size_t* bwd_bytes, size_t* index_bytes);
 
-/* Buffer reuse over head subsets (App. E, "implementation details and optimizations"): nsa_sel_fwd / nsa_sel_bwd
+/* Buffer reuse over head subsets (App. E, the paragraph on implementation details): nsa_sel_fwd / nsa_sel_bwd
  * also accept a ws smaller than the sizes above, down to the minima reported here (the partial results of ONE KV
  * head with its g query heads; for the backward plus the per-row statistics of all heads).  The library then
  * works through the KV heads in groups of as many heads as ws_bytes holds, one group after the other on the
  * stream, reusing the buffers; results are bit-identical to the single-pass ones.  Either output may be NULL. */
 int nsa_sel_workspace_bytes_min(const nsa_sel_shape* shape, size_t* fwd_bytes, size_t* bwd_bytes);
 
-/* Index inversion (Sec. 3.2, "index tensors ... pre-computed from the NSA sparse selection tensor T"):
+/* Index inversion (Sec. 3.2: the index tensors are computed from the selection tensor T before the attention kernels run):
  * histogram -> exclusive scan -> ordered scatter.  For every list L = kv_head * b_cap + global_block
  * (b_cap = total_tokens / block + nseq; global blocks number the blocks of the packed sequences consecutively;
  * lists past the real block count are empty) the result holds the ascending tokens that validly select the

@@ -5,7 +5,7 @@ shares no code with the library and nothing in the product path may import it.
 
 What is computed.  The paper takes the selection tensor (Sec. 2.2: every query token of a GQA group attends to
 its own T KV blocks of B_K tokens) as given and only notes that block 0, the attention sink, ends up selected by
-every token (App. E, "Attention Sink Optimizations").  How the T blocks are chosen belongs to the cited NSA
+every token (App. E, the paragraph on the attention sink).  How the T blocks are chosen belongs to the cited NSA
 method and is not stated in the paper: PARITY UNPINNED by the paper.  The rule implemented here, and pinned in
 tests/test_topk_oracle_pins.py to library sorting routines, brute force and closed forms, is
 

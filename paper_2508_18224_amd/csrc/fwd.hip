@@ -1,4 +1,4 @@
-// Forward selected-block attention for gfx950 (paper Sec. 3.2, the KV-outer "token selection" step and the
+// Forward selected-block attention for gfx950 (paper Sec. 3.2, the KV-outer token-selection step and the
 // reduction step; Eq. (2), c = sel).
 //
 // k_fwd_main (B_K = 64): one work unit = (kv head j, KV block i, up to P.unit entries of the block's query list).

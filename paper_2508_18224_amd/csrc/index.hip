@@ -1,6 +1,6 @@
 // Index inversion for selected-block attention: from the selection table idx[token, kv head, column] build, for
 // every (kv head, KV block), the ascending list of query tokens that select it (the paper's index tensor I_i,
-// Sec. 3.2 "FSA token selection kernel") together with the column each entry came from, and, per kept
+// Sec. 3.2, the paragraph on the token-selection kernel) together with the column each entry came from, and, per kept
 // (token, kv head, column), the entry's position in its list, which is where its partial result lives in the
 // compact partial buffers (the role of the paper's O_i), plus the work-unit tables of the attention kernels.
 // Pipeline: per-(kv head, token chunk, block) histogram -> prefix over the chunks of every list -> exclusive scan

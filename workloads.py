@@ -4,9 +4,9 @@ This module holds no attention arithmetic: it only draws tensors and block-index
 oracle and the HIP library are fed from here so that they see bit-identical bf16 inputs.
 
 Shapes follow the paper's kernel grid (d = 128, B_K = 64, T = 16, Llama/Qwen head counts; Sec. 4.1 and
-App. "Evaluations for Ultra Long Sequence Lengths").  The paper does not say how its selection indices were
-drawn, so each workload states its own recipe: forced blocks (attention sink = block 0, App. E "Attention
-Sink Optimizations"; the current block; optionally the previous block), a number of picks biased to the most
+the appendix on ultra-long sequence lengths).  The paper does not say how its selection indices were
+drawn, so each workload states its own recipe: forced blocks (attention sink = block 0, App. E, the paragraph on
+the attention sink; the current block; optionally the previous block), a number of picks biased to the most
 recent blocks, and the rest uniform without replacement over the remaining earlier blocks.  Rows are left in
 generation order (forced, local, uniform) and padded with -1.
 """
