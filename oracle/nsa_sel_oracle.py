@@ -3,8 +3,8 @@
 TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the HIP library is checked against; it
 shares no code with the library and nothing in the product path may import it.
 
-What is computed (paper Sec. 2.2, Eq. (2), `c = sel`; block semantics "T KV blocks, each with B_K contiguous
-KV tokens"; causal rule from App. E: a block that is partly in the future is masked inside, a block wholly in
+What is computed (paper Sec. 2.2, Eq. (2), `c = sel`; each query attends T blocks of B_K contiguous KV
+tokens; causal rule from App. E: a block that is partly in the future is masked inside, a block wholly in
 the future contributes nothing):
 
   for token t of sequence s (local position p, current block cur = p // B_K, b_s = ceil(L_s / B_K)) and KV
