@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the library's 1 GiB copy kernel once (for scaling rocprofv3 byte counters)")
+    ap.add_argument("--unit", type=int, default=0,
+                    help="list entries per work unit (0: the library's choice; a power of two in 256..2048)")
     ap.add_argument("--ws-cap-gb", type=float, default=0.0,
                     help="cap each workspace at this many GB: the library then reuses it over groups of KV heads")
     ap.add_argument("--no-select", action="store_true",
@@ -126,7 +128,7 @@ def main():
     q, k, v, do = (dev(x) for x in (w.q, w.k, w.v, w.do))
     idx = torch.from_numpy(w.idx).cuda()
     cu = torch.from_numpy(w.cu_seqlens).cuda()
-    attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, block=w.block,
+    attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, block=w.block, unit=args.unit,
                             ws_cap_bytes=int(args.ws_cap_gb * 1e9) if args.ws_cap_gb > 0 else None)
     o = torch.empty_like(q)
     lse = torch.empty(T, w.hq, dtype=torch.float32, device="cuda")

@@ -38,7 +38,7 @@ extern "C" {
 
 #define NSA_SEL_OK            0
 #define NSA_SEL_EINVAL       -1   /* null/misaligned pointer, g not in [1,8], hq % hkv != 0, nseq < 1, negative size,
-                                     window < 0 or window without causal                                      */
+                                     window < 0 or window without causal, unit not 0 or a power of two in range */
 #define NSA_SEL_EUNSUPPORTED -2   /* d != 128, block not 64 or 128, topk outside [1,32], too many tokens      */
 #define NSA_SEL_EWORKSPACE   -3   /* index workspace too small, or ws below nsa_sel_workspace_bytes_min       */
 #define NSA_SEL_EHIP         -4   /* the HIP runtime refused a launch or attribute                            */
@@ -58,6 +58,10 @@ typedef struct {
                              listing the blocks a window can touch (the token's own and the ceil((w-1)/block)
                              before it; nsa_sel_select_blocks with scores = NULL writes that table) the path
                              computes the sliding-window term of Eq. (2), softmax over the last w tokens       */
+  int32_t unit;           /* 0: the library picks.  Else the list entries one workgroup works through (a work
+                             unit; the knob that corresponds to the paper's query batch size B_Q, App. E, which
+                             it picks by online profiling): a power of two in [256, 2048].  It changes speed and
+                             the workspace sizes, not results (dK/dV only in their fp32 summation order)      */
 } nsa_sel_shape;
 
 /* Bytes of the three caller-owned workspaces for `shape` (any of the outputs may be NULL).

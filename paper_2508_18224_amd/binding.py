@@ -22,7 +22,7 @@ class NsaSelError(RuntimeError):
 class Shape(C.Structure):
     _fields_ = [("total_tokens", C.c_int32), ("nseq", C.c_int32), ("hq", C.c_int32), ("hkv", C.c_int32),
                 ("d", C.c_int32), ("block", C.c_int32), ("topk", C.c_int32), ("causal", C.c_int32),
-                ("scale", C.c_float), ("max_seqlen", C.c_int32), ("window", C.c_int32)]
+                ("scale", C.c_float), ("max_seqlen", C.c_int32), ("window", C.c_int32), ("unit", C.c_int32)]
 
 
 def lib():
@@ -186,10 +186,10 @@ class SelAttention:
     """Owns the workspaces for one shape and calls the library (buffers are torch uint8 tensors)."""
 
     def __init__(self, total_tokens, hq, hkv, topk, *, nseq=1, causal=True, scale=0.0, device="cuda:0", bwd=True,
-                 block=64, ws_cap_bytes=None, window=0):
+                 block=64, ws_cap_bytes=None, window=0, unit=0):
         """ws_cap_bytes caps each of the forward / backward workspaces (never below the library's minimum);
         the library then works through the KV heads in as many passes as needed."""
-        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0, int(window))
+        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0, int(window), int(unit))
         fb, bb, ib = workspace_bytes(self.shape)
         if ws_cap_bytes is not None:
             fmin, bmin = workspace_bytes_min(self.shape)
@@ -199,6 +199,31 @@ class SelAttention:
         self.index_ws = torch.empty(ib, dtype=torch.uint8, device=self.device)
         self.fwd_ws = torch.empty(fb, dtype=torch.uint8, device=self.device)
         self.bwd_ws = torch.empty(bb, dtype=torch.uint8, device=self.device) if bwd else None
+
+    @classmethod
+    def autotuned(cls, q, k, v, idx, do, cu=None, *, topk, candidates=(256, 512, 1024, 2048), reps=3, **kw):
+        """The paper picks its query batch size by timing the candidates once per configuration (App. E); this does
+        the same for the work-unit size: builds one object per candidate, times `reps` forward + backward steps on
+        the given tensors with device events, and returns (best object, {unit: ms})."""
+        T, hq = q.shape[0], q.shape[1]
+        hkv = k.shape[1]
+        nseq = 1 if cu is None else cu.numel() - 1
+        timings = {}
+        for unit in candidates:
+            a = cls(T, hq, hkv, topk, nseq=nseq, unit=unit, **kw)
+            o, lse = a.forward(q, k, v, idx, cu)
+            a.backward(q, k, v, o, lse, do, cu)                      # warm-up
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                o, lse = a.forward(q, k, v, idx, cu)
+                a.backward(q, k, v, o, lse, do, cu)
+            e1.record()
+            torch.cuda.synchronize()
+            timings[unit] = e0.elapsed_time(e1) / reps
+            del a
+        best = min(timings, key=timings.get)
+        return cls(T, hq, hkv, topk, nseq=nseq, unit=best, **kw), timings
 
     def build_index(self, idx, cu=None):
         build_index(self.shape, idx, cu, self.index_ws)

@@ -16,6 +16,7 @@ static int check_shape(const nsa_sel_shape* s) {
   const int g = s->hq / s->hkv;
   if (g < 1 || g > 8) return NSA_SEL_EINVAL;
   if (s->window < 0 || (s->window > 0 && !s->causal)) return NSA_SEL_EINVAL;
+  if (s->unit != 0 && (s->unit < kMinUnit || s->unit > kMaxUnit || (s->unit & (s->unit - 1)) != 0)) return NSA_SEL_EINVAL;
   if (s->d != kD || (s->block != kBlock && s->block != 2 * kBlock)) return NSA_SEL_EUNSUPPORTED;
   if (s->topk < 1 || s->topk > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
   if (s->nseq > (1 << 20)) return NSA_SEL_EUNSUPPORTED;
@@ -45,7 +46,7 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   if (L.n_chunks < 1) L.n_chunks = 1;
   L.n_counters = (int64_t)L.n_lists * L.n_chunks;
   L.p_max = (int64_t)s->total_tokens * s->hkv * L.topk;
-  L.unit = work_unit_entries(L.p_max);
+  L.unit = s->unit != 0 ? s->unit : work_unit_entries(L.p_max);
   L.units_max = (int32_t)units_bound(L.hkv, L.b_cap, L.T, L.topk, L.unit);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };

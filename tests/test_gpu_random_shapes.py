@@ -62,3 +62,31 @@ def test_very_short_sequences(n_tokens, g, block):
     print("short case", n_tokens, g, block, flush=True)
     w = wl.realise(wl.Workload("s", [n_tokens], hq=2 * g, hkv=2, topk=3, block=block, seed=n_tokens + g))
     _check(w)
+
+
+def test_work_unit_size_changes_speed_not_results():
+    """Every admissible unit size gives the same O, LSE and dQ bit for bit (a row's arithmetic does not depend on its
+    tile neighbours) and dK/dV within the tolerance (their fp32 partial sums are split differently); the autotuner
+    returns one of the candidates."""
+    print("case unit sizes", flush=True)
+    import paper_2508_18224_amd as nsa
+    from gpu_util import Case, TOL_GRAD, assert_close, to_f64
+    from oracle import nsa_sel_oracle as orc
+    w = wl.realise(wl.Workload("units", [5000], hq=4, hkv=2, topk=6, sink=True, seed=91))
+    c = Case(w)
+    Q, K, V, dO = c.host_f64()
+    _, rk, rv = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens)
+    ref = None
+    for unit in (256, 512, 1024, 2048):
+        a = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, unit=unit)
+        o, lse = a.forward(c.q, c.k, c.v, c.idx, c.cu)
+        dq, dk, dv = a.backward(c.q, c.k, c.v, o, lse, c.do, c.cu)
+        torch.cuda.synchronize()
+        assert_close("dK", to_f64(dk), rk, TOL_GRAD)
+        assert_close("dV", to_f64(dv), rv, TOL_GRAD)
+        if ref is None:
+            ref = (o, lse, dq)
+        else:
+            assert torch.equal(o, ref[0]) and torch.equal(lse, ref[1]) and torch.equal(dq, ref[2])
+    best, timings = nsa.SelAttention.autotuned(c.q, c.k, c.v, c.idx, c.do, c.cu, topk=w.topk, reps=2)
+    assert best.shape.unit in timings and len(timings) == 4
