@@ -159,7 +159,10 @@ def test_argument_errors():
     out = torch.empty(64, 1, 4, dtype=torch.int32, device="cuda")
     shape = nsa.Shape(64, 1, 1, 1, 128, 64, 4, 1, 0.0, 0)
     p = lambda t: C.c_void_p(t.data_ptr())
-    assert L.nsa_sel_select_blocks(C.byref(shape), None, 8, None, 1, 2, p(out), None) == -1
+    assert L.nsa_sel_select_blocks(C.byref(shape), p(x), 8, None, 1, 2, None, None) == -1            # no output
+    assert L.nsa_sel_select_blocks(C.byref(shape), None, 8, None, 1, 2, p(out), None) == 0            # no scores: forced blocks only
+    torch.cuda.synchronize()
+    assert out[63, 0].tolist() == [0, -1, -1, -1] and out[0, 0].tolist() == [0, -1, -1, -1]
     assert L.nsa_sel_select_blocks(C.byref(shape), p(x), 8, None, -1, 2, p(out), None) == -1
     assert L.nsa_sel_select_blocks(C.byref(shape), p(x), 0, None, 1, 2, p(out), None) == -2
     assert L.nsa_sel_select_blocks(C.byref(shape), p(x), 16385, None, 1, 2, p(out), None) == -2
