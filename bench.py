@@ -89,6 +89,60 @@ def bench_select_blocks(nsa, wl, w, cu, steps):
             "1 sink + 2 local blocks forced"}
 
 
+def bench_extras(nsa, wl, w, q, k, v, do, cu, steps):
+    """Steps after the path, measured on their own (not part of the metric): the gated forms of forward and backward
+    against the plain ones, and the sliding-window branch run through the same kernels, on the workload's tensors."""
+    import torch
+    T = w.total_tokens
+
+    def per_kernel(run):
+        for _ in range(2):
+            run()
+        torch.cuda.synchronize()
+        nsa.profile_select(None)
+        nsa.profile_enable(steps * (24 + 8 * w.hkv))
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            run()
+        b.record()
+        torch.cuda.synchronize()
+        prof = nsa.profile_collect()
+        nsa.profile_enable(0)
+        out = {n: t / c for n, (t, c) in prof.items() if c and not n.startswith("index_")}
+        out["step_with_events"] = a.elapsed_time(b) / steps
+        return out
+
+    res = {}
+    idx = torch.from_numpy(w.idx).cuda()
+    attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, block=w.block)
+    gate = torch.from_numpy(wl.draw_gates(w.seed, T, w.hq)).cuda()
+    acc = torch.from_numpy(wl.draw_other_branches(w.seed, T, w.hq).view(np.int16)).cuda().view(torch.bfloat16)
+
+    def plain():
+        o, lse = attn.forward(q, k, v, idx, cu)
+        attn.backward(q, k, v, o, lse, do, cu)
+
+    def gated():
+        _, o, lse = attn.forward_gated(q, k, v, idx, gate, acc, cu, out=acc)
+        attn.backward_gated(q, k, v, o, lse, do, gate, cu)
+    res["plain"] = per_kernel(plain)
+    res["gated"] = per_kernel(gated)
+    del attn, idx
+    if w.causal:
+        for window, blk in ((512, 64), (512, 128)):
+            widx = nsa.window_blocks(T, w.hkv, window, cu, block=blk)
+            wattn = nsa.SelAttention(T, w.hq, w.hkv, widx.shape[2], nseq=len(w.seqlens), causal=True, block=blk,
+                                     window=window)
+
+            def win():
+                o, lse = wattn.forward(q, k, v, widx, cu)
+                wattn.backward(q, k, v, o, lse, do, cu)
+            res[f"window_{window}_block_{blk}"] = dict(per_kernel(win), slots=int(widx.shape[2]))
+            del wattn, widx
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -103,6 +157,8 @@ def main():
                     help="cap each workspace at this many GB: the library then reuses it over groups of KV heads")
     ap.add_argument("--no-select", action="store_true",
                     help="skip the separate measurement of the selection step (block scores -> idx) in front of the path")
+    ap.add_argument("--extras", action="store_true",
+                    help="also measure the gated forms and the sliding-window branch (reported under 'downstream')")
     ap.add_argument("--cpu-tokens", type=int, default=1280, help="query tokens of the CPU-oracle sample (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -235,6 +291,9 @@ def main():
     }
     if not args.no_select:
         out["upstream"] = {"select_blocks": bench_select_blocks(nsa, wl, w, cu, args.steps)}
+    if args.extras:
+        del attn
+        out["downstream"] = bench_extras(nsa, wl, w, q, k, v, do, cu, min(args.steps, 5))
     if args.cpu_tokens > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_tokens)
     print(json.dumps(out), flush=True)
