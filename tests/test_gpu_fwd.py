@@ -34,3 +34,25 @@ def test_forward_custom_scale_and_adversarial_rows():
     assert_close("O", to_f64(o), O_ref, TOL_O)
     assert_lse_close(to_f64(lse), LSE_ref)
     assert np.all(to_f64(o)[100:140] == 0)
+
+
+def test_profile_records_only_selected_kernels():
+    """The event recorder brackets the launches of the selected kernel kinds only and resets on collect."""
+    print("case profile select", flush=True)
+    import paper_2508_18224_amd as nsa
+    w = wl.realise(wl.small("g3_k1"))
+    c = Case(w, bwd=False)
+    c.forward()
+    nsa.profile_select(["fwd_main", "index_hist"])
+    nsa.profile_enable(64)
+    c.forward()
+    c.forward()
+    got = {n: v for n, v in nsa.profile_collect().items() if v[1]}
+    assert set(got) == {"fwd_main", "index_hist"} and got["fwd_main"][1] == 2 and got["fwd_main"][0] > 0
+    nsa.profile_select(None)
+    c.forward()
+    every = {n for n, v in nsa.profile_collect().items() if v[1]}
+    assert {"fwd_main", "fwd_merge", "index_scatter", "index_scan"} <= every
+    nsa.profile_enable(0)
+    c.forward()
+    assert not any(v[1] for v in nsa.profile_collect().values())
