@@ -28,6 +28,11 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("headline", "bwd_main"): 26.5e9,   # profiles/hot_path_headline_64k_g4.txt: fetch 17.62 GB + write 8.91 GB
     ("headline", "fwd_main"): 16.66e9,
+    ("headline_b128", "bwd_main"): 14.06e9,      # profiles/hot_path_headline_b128_64k_g4.txt
+    ("grid_g1_b64_n64", "bwd_main"): 30.29e9,    # profiles/hot_path_grid_g1_b64_n64.txt
+    ("varlen_g1", "bwd_main"): 23.29e9,          # profiles/hot_path_varlen_g1.txt
+    ("qwen_g7", "bwd_main"): 23.18e9,            # profiles/hot_path_qwen_g7.txt
+    ("llama70b_128k", "bwd_main"): 104.58e9,     # profiles/hot_path_llama70b_128k.txt
 }
 
 
