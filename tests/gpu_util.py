@@ -59,6 +59,17 @@ def assert_close(name, got: np.ndarray, ref: np.ndarray, tol):
     return float(err.max()) if err.size else 0.0, fro
 
 
+def assert_dgate_close(name, got: np.ndarray, dO: np.ndarray, O_ref: np.ndarray):
+    """dgate[t, h] = <dO, O> is a 128-term dot product whose O factor the library holds in bf16: each product is off by
+    at most half a bf16 ulp, 2^-9 relative, so the sum may be off by 2^-9 * sum_i |dO_i O_i| even where the sum itself
+    cancels to ~0.  Bound: the gradient tolerance's absolute part plus twice that."""
+    ref = (dO * O_ref).sum(axis=2)
+    err = np.abs(got - ref)
+    bound = TOL_GRAD[0] + 2.0 ** -8 * np.abs(dO * O_ref).sum(axis=2)
+    worst = float((err - bound).max()) if err.size else 0.0
+    assert worst <= 0, f"{name}: error exceeds 4e-2 + 2^-8 sum|dO O| by {worst:.4g}"
+
+
 def assert_lse_close(got: np.ndarray, ref: np.ndarray):
     assert np.array_equal(np.isneginf(got), np.isneginf(ref)), "LSE: -inf pattern differs"
     fin = np.isfinite(ref)

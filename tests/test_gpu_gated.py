@@ -7,7 +7,7 @@ import torch
 import paper_2508_18224_amd as nsa
 import workloads as wl
 from oracle import nsa_sel_oracle as orc
-from gpu_util import Case, TOL_GRAD, TOL_O, assert_close, dev_bf16, to_f64
+from gpu_util import Case, TOL_GRAD, TOL_O, assert_close, assert_dgate_close, dev_bf16, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -39,7 +39,8 @@ def _gated(w, with_acc=True, in_place=False, ws_cap=None):
     assert_close("dQ", to_f64(dq), rq, TOL_GRAD)
     assert_close("dK", to_f64(dk), rk, TOL_GRAD)
     assert_close("dV", to_f64(dv), rv, TOL_GRAD)
-    assert_close("dgate", to_f64(dgate), rg, TOL_GRAD)
+    assert_dgate_close("dgate", to_f64(dgate), dO, rO)
+    assert np.allclose(rg, (dO * rO).sum(axis=2))
     off = gate == 0.0
     assert off.any() and not to_f64(dq)[off].any()                              # a closed gate passes no gradient
     return c
@@ -133,5 +134,6 @@ def test_selected_and_window_branches_gated_into_one_output():
     for name, got, want in (("dQ", dq1.float() + dq2.float(), rq1 + rq2), ("dK", dk1.float() + dk2.float(), rk1 + rk2),
                             ("dV", dv1.float() + dv2.float(), rv1 + rv2)):
         assert_close(name, to_f64(got), want, (2 * TOL_GRAD[0], TOL_GRAD[1]))
-    assert_close("dgate sel", to_f64(dg1), rg1, TOL_GRAD)
-    assert_close("dgate win", to_f64(dg2), rg2, TOL_GRAD)
+    assert_dgate_close("dgate sel", to_f64(dg1), dO, r_sel)
+    assert_dgate_close("dgate win", to_f64(dg2), dO, O_w)
+    assert np.allclose(rg1, (dO * r_sel).sum(axis=2)) and np.allclose(rg2, (dO * O_w).sum(axis=2))
