@@ -107,6 +107,15 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
                 const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws,
                 size_t index_bytes, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
 
+/* The same forward in QUERY-OUTER loop order, the order of the original NSA kernel (Sec. 2.2, 3.1; App. C): one
+ * wavefront per (token, KV head) walks the row's selected blocks with an online softmax, re-loading a K/V block for
+ * every (token, KV head, block).  The paper's fallback for many query heads per group (App. E) would dispatch to
+ * this order; on this chip it does not win for any g <= 8, and the entry point exists for that comparison.  Needs no
+ * workspace and no index; same O and LSE as nsa_sel_fwd up to rounding (fp32 accumulation over all blocks instead
+ * of bf16 partial rows).  block must be 64 and window 0 (NSA_SEL_EUNSUPPORTED otherwise).  Forward only. */
+int nsa_sel_fwd_query_outer(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                            const int32_t* cu_seqlens, void* O, float* LSE, void* stream);
+
 /* Gated combination with the other attention branches, fused into the forward's merge kernel (the step after the
  * path; Eq. (2): the layer output is the sum over the branches c of tau^c_t times the branch's attention output).
  * Like nsa_sel_fwd, and in addition  O_out[t,h,:] = O_acc[t,h,:] + gate[t,h] * O[t,h,:],  formed from the fp32 result

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
 _lib = None
 
-SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_workspace_bytes_min", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd", "nsa_sel_fwd_gated", "nsa_sel_bwd_gated", "nsa_sel_select_blocks",
+SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_workspace_bytes_min", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd", "nsa_sel_fwd_query_outer", "nsa_sel_fwd_gated", "nsa_sel_bwd_gated", "nsa_sel_select_blocks",
            "nsa_sel_profile_enable", "nsa_sel_profile_select", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_mfma_probe", "nsa_sel_strerror"]
 
 
@@ -39,6 +39,7 @@ def lib():
         L.nsa_sel_index_view.argtypes = [C.POINTER(Shape), vp] + [C.POINTER(vp)] * 4 + [C.POINTER(C.c_int32)]
         L.nsa_sel_fwd.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, sz, vp]
         L.nsa_sel_bwd.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, sz, vp]
+        L.nsa_sel_fwd_query_outer.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, vp, vp, vp]
         L.nsa_sel_fwd_gated.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, vp, vp, vp, sz, vp]
         L.nsa_sel_bwd_gated.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, vp, sz, vp]
         L.nsa_sel_select_blocks.argtypes = [C.POINTER(Shape), vp, C.c_int64, i32p, C.c_int32, C.c_int32, i32p, vp]
@@ -245,6 +246,15 @@ class SelAttention:
             dq, dk, dv = out
         nsa_sel_bwd(s, q, k, v, o, lse, do, cu, self.index_ws, dq, dk, dv, self.bwd_ws)
         return dq, dk, dv
+
+    def forward_query_outer(self, q, k, v, idx, cu=None):
+        """(O, LSE) by the query-outer kernel (nsa_sel_fwd_query_outer): the loop order of the original NSA kernel."""
+        s = self.shape
+        o = torch.empty(s.total_tokens, s.hq, 128, dtype=torch.bfloat16, device=self.device)
+        l = torch.empty(s.total_tokens, s.hq, dtype=torch.float32, device=self.device)
+        _check(lib().nsa_sel_fwd_query_outer(C.byref(s), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu), _ptr(o), _ptr(l),
+                                             _stream()), "nsa_sel_fwd_query_outer")
+        return o, l
 
     def forward_gated(self, q, k, v, idx, gate, o_acc=None, cu=None, rebuild_index=True, out=None):
         """(O_out, O, LSE) with O_out = O_acc + gate * O (nsa_sel_fwd_gated); `out` may be the O_acc tensor."""

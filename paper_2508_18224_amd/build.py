@@ -6,7 +6,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ["api.hip", "index.hip", "fwd.hip", "bwd.hip", "select.hip", "profile.hip"]
+SOURCES = ["api.hip", "index.hip", "fwd.hip", "bwd.hip", "select.hip", "qouter.hip", "profile.hip"]
 LIB = os.path.join(HERE, "libnsa_sel.so")
 # -packed-fp32-ops: keep the compiler from forming packed fp32 instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature", "-Xclang",

@@ -198,6 +198,21 @@ int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
                   GateArgs{nullptr, nullptr, nullptr, nullptr}, ws, ws_bytes, stream);
 }
 
+int nsa_sel_fwd_query_outer(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                            const int32_t* cu_seqlens, void* O, float* LSE, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (shape->block != kBlock || shape->window != 0) return NSA_SEL_EUNSUPPORTED;
+  if (shape->total_tokens == 0) return NSA_SEL_OK;
+  if (!Q || !K || !V || !idx || !O || !LSE) return NSA_SEL_EINVAL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return NSA_SEL_EINVAL;
+  if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
+  IndexLayout L = make_layout(shape);
+  Problem P = make_problem(shape, L);
+  return launch_fwd_query_outer(P, Q, K, V, idx, cu_seqlens, O, LSE, (hipStream_t)stream) == hipSuccess ? NSA_SEL_OK
+                                                                                                         : NSA_SEL_EHIP;
+}
+
 int nsa_sel_fwd_gated(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
                       const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
                       float* LSE, const float* gate, const void* O_acc, void* O_out, void* ws, size_t ws_bytes,

@@ -104,7 +104,7 @@ inline int64_t units_bound(int nj, int b_cap, int T, int topk, int unit) {
 enum KernelId {
   KID_INDEX_PREP = 0, KID_INDEX_CHUNK_PREFIX, KID_INDEX_HIST, KID_INDEX_SCAN, KID_INDEX_SCATTER, KID_INDEX_FINALIZE,
   KID_INDEX_UNITS, KID_FWD_MAIN, KID_FWD_MERGE, KID_BWD_DELTA, KID_BWD_MAIN, KID_BWD_DQ_REDUCE, KID_BWD_DKV_REDUCE,
-  KID_SELECT_BLOCKS, KID_COUNT
+  KID_SELECT_BLOCKS, KID_FWD_QUERY_OUTER, KID_COUNT
 };
 // Records a HIP event on `st` at construction and destruction when profiling is on; does nothing otherwise.
 struct ProfScope {
@@ -142,6 +142,9 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
 hipError_t launch_fwd(const Problem& P, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
                       const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
                       const GateArgs& G, hipStream_t st);
+// the same forward in query-outer loop order (no workspaces, no index): see qouter.hip
+hipError_t launch_fwd_query_outer(const Problem& P, const void* Q, const void* K, const void* V, const int32_t* idx,
+                                  const int32_t* cu, void* O, float* LSE, hipStream_t st);
 hipError_t launch_bwd(const Problem& P, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
                       const void* V, const void* O, const float* LSE, const void* dO, const void* index_ws,
                       void* dqpart, float* delta, float* dkv_part, void* dQ, void* dK, void* dV, const GateArgs& G,
