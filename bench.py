@@ -133,6 +133,18 @@ def bench_extras(nsa, wl, w, q, k, v, do, cu, steps):
         attn.backward_gated(q, k, v, o, lse, do, gate, cu)
     res["plain"] = per_kernel(plain)
     res["gated"] = per_kernel(gated)
+    if w.block == 64:
+        # the paper's comparison on this chip: the same forward in the original NSA (query-outer) loop order
+        def kv_outer_fwd():
+            attn.forward(q, k, v, idx, cu)
+
+        def query_outer_fwd():
+            attn.forward_query_outer(q, k, v, idx, cu)
+        a = per_kernel(kv_outer_fwd)
+        b = per_kernel(query_outer_fwd)
+        res["loop_order_forward"] = {"kv_outer_ms": a["step_with_events"], "query_outer_ms": b["step_with_events"],
+                                     "ratio": b["step_with_events"] / a["step_with_events"],
+                                     "note": "kv_outer includes index inversion, main and merge"}
     del attn, idx
     if w.causal:
         for window, blk in ((512, 64), (512, 128)):
