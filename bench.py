@@ -23,38 +23,62 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by
-# the copy-kernel calibration); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {
-    ("headline", "bwd_main"): 26.5e9,   # profiles/hot_path_headline_64k_g4.txt: fetch 17.62 GB + write 8.91 GB
-    ("headline", "fwd_main"): 16.66e9,
-    ("headline_b128", "bwd_main"): 14.06e9,      # profiles/hot_path_headline_b128_64k_g4.txt
-    ("grid_g1_b64_n64", "bwd_main"): 30.29e9,    # profiles/hot_path_grid_g1_b64_n64.txt
-    ("varlen_g1", "bwd_main"): 23.29e9,          # profiles/hot_path_varlen_g1.txt
-    ("qwen_g7", "bwd_main"): 23.18e9,            # profiles/hot_path_qwen_g7.txt
-    ("llama70b_128k", "bwd_main"): 104.58e9,     # profiles/hot_path_llama70b_128k.txt
+# kernel kinds of nsa_sel_profile_collect -> kernel names in the rocprofv3 summaries under profiles/
+KERNEL_NAMES = {
+    "fwd_main": ("nsa::k_fwd_main", "nsa::k_fwd_main128"), "fwd_merge": ("nsa::k_fwd_merge",),
+    "fwd_dense": ("nsa::k_fwd_dense",),
+    "bwd_main": ("nsa::k_bwd_tiled<2>", "nsa::k_bwd_tiled<4>"), "bwd_delta": ("nsa::k_bwd_delta",),
+    "bwd_dq_reduce": ("nsa::k_bwd_dq_reduce",), "bwd_dkv_reduce": ("nsa::k_bwd_dkv_reduce",),
 }
+NOT_IN_STEP = ("nsa::k_select_blocks", "k_calib_copy", "nsa::k_mfma_probe", "nsa::k_fwd_query_outer")
 
 
-def cpu_baseline(w, budget_tokens: int):
-    """The fp64 oracle, as it stands, on evenly spaced tokens of the same workload (forward, then backward)."""
-    from threadpoolctl import threadpool_limits
+def measured_traffic(workload: str):
+    """{kernel name: HBM bytes per launch} from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary of
+    this workload (profiles/hot_path_<workload>.txt, the table headed 'HBM traffic per launch', already scaled by the
+    copy-kernel calibration).  The counters cannot be read inside a timing run, so the summary is the source; a
+    workload without one has no traffic figure and the caller says so loudly."""
+    path = os.path.join(ROOT, "profiles", f"hot_path_{workload}.txt")
+    if not os.path.exists(path):
+        return None, path
+    out, on = {}, False
+    for line in open(path):
+        if line.startswith("HBM traffic per launch"):
+            on = True
+        elif on:
+            parts = line.split()
+            if len(parts) == 4 and parts[0] != "kernel":
+                try:
+                    out[parts[0]] = float(parts[3]) * 1e9
+                except ValueError:
+                    pass
+    return out, path
+
+
+def cpu_baseline(workload: str, budget_tokens: int):
+    """The fp64 oracle, as it stands, on evenly spaced tokens of the same workload (forward, then backward), spread
+    over the host's cores by oracle/sample_cli.py in a child process that never touches the GPU.  Called before this
+    process initialises the GPU."""
+    import subprocess
+    import tempfile
 
     import workloads as wl
-    from oracle import nsa_sel_oracle as orc
     from paper_2508_18224_amd.cost_model import effective_flops
-    Q, K, V, dO = (wl.bf16_bits_to_f64(x) for x in (w.q, w.k, w.v, w.do))
-    T = w.total_tokens
-    tokens = [int(x) for x in np.linspace(0, T - 1, budget_tokens).astype(np.int64)]
-    with threadpool_limits(limits=1):
-        t0 = time.perf_counter()
-        orc.forward(Q, K, V, w.idx, w.cu_seqlens, causal=w.causal, tokens=tokens, block=w.block)
-        orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, causal=w.causal, tokens=tokens, block=w.block)
-        dt = time.perf_counter() - t0
-    f, b = effective_flops(len(tokens), w.hq, w.topk, block=w.block)
-    return {"value": (f + b) / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
-            "sample": f"{len(tokens)} evenly spaced query tokens of the same workload, all heads, forward + "
-                      f"backward contributions of those rows, {dt:.1f} s"}
+    out = tempfile.mktemp(suffix=".npz", prefix="nsa_cpu_baseline_")
+    cmd = [sys.executable, "-m", "oracle.sample_cli", "--workload", workload, "--tokens", f"even:{budget_tokens}",
+           "--out", out]
+    res = subprocess.run(cmd, cwd=ROOT, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.exit("bench.py: the CPU oracle sample failed:\n" + res.stdout + res.stderr)
+    info = json.loads(res.stdout.strip().splitlines()[-1])
+    os.unlink(out)
+    w = wl.named(workload)
+    f, b = effective_flops(info["tokens"], w.hq, w.topk, block=w.block)
+    dt = info["rows_seconds"]
+    return {"value": (f + b) / dt / 1e12, "unit": "TFLOP/s", "cores": info["procs"], "kind": "oracle",
+            "sample": f"{info['tokens']} evenly spaced query tokens of the same workload, all heads, forward + "
+                      f"backward contributions of those rows, {dt:.1f} s wall on {info['procs']} worker processes "
+                      f"(one per host core)"}
 
 
 def bench_select_blocks(nsa, wl, w, cu, steps):
@@ -176,17 +200,23 @@ def main():
                     help="skip the separate measurement of the selection step (block scores -> idx) in front of the path")
     ap.add_argument("--extras", action="store_true",
                     help="also measure the gated forms and the sliding-window branch (reported under 'downstream')")
-    ap.add_argument("--cpu-tokens", type=int, default=1280, help="query tokens of the CPU-oracle sample (0: skip)")
+    ap.add_argument("--cpu-tokens", type=int, default=8192, help="query tokens of the CPU-oracle sample (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over KV heads with no "
                  "communication, so N GPUs would each run this same kernel on hkv / N heads); run with --gpus 1")
 
+    # the CPU baseline first: its worker processes are forked before this process has touched the GPU, and the
+    # host is idle again when the GPU timing starts
+    cpu = cpu_baseline(args.workload, args.cpu_tokens) if args.cpu_tokens > 0 else None
+    if cpu is not None:
+        print(f"[bench] cpu oracle: {cpu['value']:.4f} TFLOP/s on {cpu['cores']} cores", file=sys.stderr, flush=True)
+
     import torch
 
     import paper_2508_18224_amd as nsa
     import workloads as wl
-    from paper_2508_18224_amd.cost_model import effective_flops
+    from paper_2508_18224_amd.cost_model import compulsory_bytes, effective_flops
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -279,16 +309,36 @@ def main():
     # algorithmic work of the dominant kernel: the MFMA contractions it performs (forward main: QK^T and PV,
     # 4 N hq k 64 d; backward main: five such products, 2.5x)
     dom_flops = {"fwd_main": f, "bwd_main": b}.get(dom)
+    alg_f, alg_b = compulsory_bytes(T, w.hq, w.hkv, w.topk)
+    traffic, traffic_file = measured_traffic(args.workload)
+    if traffic is None:
+        print(f"[bench] WARNING: {traffic_file} does not exist: no rocprofv3 byte-counter summary for this workload, "
+              f"roofline.traffic is null", file=sys.stderr, flush=True)
     roof = None
     if dom_flops is not None:
-        ach = dom_flops / (per_kernel[dom] * 1e-3) / 1e12
+        sec = per_kernel[dom] * 1e-3
+        ach = dom_flops / sec / 1e12
+        # the compulsory bytes of the pass the kernel dominates (forward or backward), each tensor once
+        alg = alg_f if dom == "fwd_main" else alg_b
+        tr = None
+        if traffic is not None:
+            tr = next((traffic[k] for k in KERNEL_NAMES[dom] if k in traffic), None)
+            if tr is None:
+                sys.exit(f"bench.py: {traffic_file} has no row for {KERNEL_NAMES[dom]}: regenerate the summary")
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
-                "ms_per_launch": per_kernel[dom]}
-        tr = MEASURED_TRAFFIC_BYTES.get((args.workload, dom))
-        if tr is not None:   # the same kernel against the HBM roofline, from its measured traffic
-            roof["hbm_achieved_GBps"] = tr / (per_kernel[dom] * 1e-3) / 1e9
-            roof["hbm_frac"] = roof["hbm_achieved_GBps"] / PEAK_HBM_GBS
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": tr, "ms_per_launch": per_kernel[dom],
+                "algorithmic_flops": dom_flops, "algorithmic_bytes": alg,
+                # the same launch against the HBM roofline on ALGORITHMIC bytes (wasted traffic lowers it)
+                "hbm_algorithmic": {"achieved": alg / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                    "frac": alg / sec / 1e9 / PEAK_HBM_GBS},
+                "traffic_ratio": None if tr is None else tr / alg,
+                "traffic_source": os.path.relpath(traffic_file, ROOT) if traffic is not None else None}
+    step_traffic = None
+    if traffic is not None:
+        step_bytes = sum(v for k, v in traffic.items() if not k.startswith(NOT_IN_STEP))
+        step_traffic = {"counter_bytes_per_step": step_bytes, "algorithmic_bytes_per_step": alg_f + alg_b,
+                        "traffic_ratio": step_bytes / (alg_f + alg_b),
+                        "hbm_algorithmic_frac": (alg_f + alg_b) / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
     out = {
         "metric": "selected-attn fwd+bwd effective TFLOP/s & ms at N=64k, g=4 (frac of MFMA peak)",
         "value": (f + b) / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -303,6 +353,7 @@ def main():
         "ms": {"index": idx_ms, "fwd": fwd_ms, "bwd": bwd_ms, "per_kernel": per_kernel,
                "step_median": per_step[len(per_step) // 2], "step_min": per_step[0]},
         "roofline": roof,
+        "step_traffic": step_traffic,
         "measured_peaks": {"mfma_loop_TFLOPs": mfma_measured, "stream_copy_GBps": copy_measured,
                            "frac_of_measured_mfma": (f + b) / (ms * 1e-3) / 1e12 / mfma_measured},
     }
@@ -311,8 +362,8 @@ def main():
     if args.extras:
         del attn
         out["downstream"] = bench_extras(nsa, wl, w, q, k, v, do, cu, min(args.steps, 5))
-    if args.cpu_tokens > 0:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_tokens)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out), flush=True)
 
 

@@ -100,9 +100,13 @@ int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
                 const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
                 float* LSE, void* ws, size_t ws_bytes, void* stream);
 
-/* Backward of the above: dQ, dK, dV from dO, the forward's O and LSE and the cached index workspace.
- * dK/dV are accumulated without atomics (per-work-unit partial sums reduced in a fixed order), so results
- * are bit-reproducible. */
+/* Backward of the above (Sec. 3.2, the closing sentences of the token-selection paragraph: the backward pass follows
+ * the forward's KV-outer logic, takes the index tensors from the forward's cache and stores intermediate query
+ * gradients to a buffer that a reduction kernel sums; the formulas are the derivative of Eq. (2), c = sel):
+ * dQ, dK, dV from dO, the forward's O and LSE and the cached index workspace (the call takes no idx: the index
+ * workspace written by nsa_sel_fwd / nsa_sel_build_index for the same idx and shape is its only view of the
+ * selection).  dK/dV are accumulated without atomics (per-work-unit partial sums reduced in a fixed order), so
+ * results are bit-reproducible.  ws: at least the backward size of nsa_sel_workspace_bytes_min. */
 int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
                 const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws,
                 size_t index_bytes, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
@@ -121,8 +125,8 @@ int nsa_sel_fwd_query_outer(const nsa_sel_shape* shape, const void* Q, const voi
  * Like nsa_sel_fwd, and in addition  O_out[t,h,:] = O_acc[t,h,:] + gate[t,h] * O[t,h,:],  formed from the fp32 result
  * before it is rounded.  gate is DEVICE fp32 [total_tokens, hq] (the paper's per-token gate broadcast over heads, or
  * per-head gates); O_acc is DEVICE bf16 [total_tokens, hq, d], the gated sum of the other branches, or NULL for
- * zero; O_out is DEVICE bf16 of the same shape and may be the buffer O_acc points to, but not O.  O and LSE are still
- * written ungated: the backward needs them. */
+ * zero; O_out is DEVICE bf16 of the same shape and may be the buffer O_acc points to, but not O; O_acc must not be O
+ * either (NSA_SEL_EINVAL).  O and LSE are still written ungated: the backward needs them. */
 int nsa_sel_fwd_gated(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
                       const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
                       float* LSE, const float* gate, const void* O_acc, void* O_out, void* ws, size_t ws_bytes,
@@ -161,8 +165,12 @@ int nsa_sel_select_blocks(const nsa_sel_shape* shape, const float* scores, int64
  * events on the caller's stream, up to `capacity` launches (later ones are not recorded); capacity <= 0 turns
  * it off and frees the events.  nsa_sel_profile_collect waits for the recorded events, writes per kernel kind
  * its name, the summed milliseconds and the number of launches into the HOST arrays (each of max_kernels
- * entries), clears the record and returns the number of kinds written (or a negative code).  Not thread-safe;
- * launches of a group that consists of several small kernels (the scans) are timed as one. */
+ * entries), clears the record and returns the number of kinds written (or a negative code).  Launches of a group
+ * that consists of several small kernels (the scans) are timed as one.
+ * RESTRICTION: the record is one process-wide table (host memory; the event objects are created by enable and
+ * destroyed by enable(0)).  While profiling is on, the library must be driven from ONE host thread on ONE stream:
+ * calls from a second thread race on the table, and launches on a second stream would interleave their records
+ * with the first's.  With profiling off (the default) the attention entry points touch no shared state. */
 int nsa_sel_profile_enable(int capacity);
 /* Restricts the recording to some kernel kinds: bit i of `mask` stands for the i-th name nsa_sel_profile_collect
  * reports (all bits set by default).  An event pair costs a few microseconds on the stream, so a benchmark that

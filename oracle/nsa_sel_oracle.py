@@ -205,10 +205,13 @@ def invert_index(idx: np.ndarray, cu: np.ndarray, *, block: int = 64, causal: bo
 
 def backward_kv_blocks(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarray, idx: np.ndarray,
                        cu: np.ndarray, blocks: Sequence[Tuple[int, int, int]], *, block: int = 64,
-                       causal: bool = True, scale: Optional[float] = None, window: int = 0):
+                       causal: bool = True, scale: Optional[float] = None, window: int = 0,
+                       token_range: Optional[Tuple[int, int]] = None):
     """dK, dV of a few KV blocks of a large problem: `blocks` holds (kv head j, sequence s, local block x).
     Every token of sequence s that validly selects the block is revisited in full (its softmax needs all of
-    its visible keys).  Returns a list of (dK_blk, dV_blk) float64 arrays of shape [keys_in_block, d]."""
+    its visible keys).  Returns a list of (dK_blk, dV_blk) float64 arrays of shape [keys_in_block, d].
+    With `token_range` = (lo, hi) only the query tokens lo <= t < hi contribute: the sums are additive over tokens,
+    so disjoint ranges can be computed side by side and added (same terms, grouped by range)."""
     T, hq, d = Q.shape
     hkv = K.shape[1]
     g = hq // hkv
@@ -222,7 +225,10 @@ def backward_kv_blocks(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarr
         dKb = np.zeros((hi - lo, d), dtype=np.float64)
         dVb = np.zeros((hi - lo, d), dtype=np.float64)
         first = lo if causal else c0
-        for t in range(first, c1):
+        last = c1
+        if token_range is not None:
+            first, last = max(first, int(token_range[0])), min(last, int(token_range[1]))
+        for t in range(first, last):
             if x not in selected_set(idx[t, j], (t - c0) // block, b_s, causal, window=window, p=t - c0, block=block):
                 continue
             keys = visible_keys(cu, t, idx[t, j], block, causal, window)

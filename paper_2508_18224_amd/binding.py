@@ -70,8 +70,70 @@ def _ptr(t: Optional[torch.Tensor]):
     return C.c_void_p(t.data_ptr())
 
 
-def _stream():
-    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+def _stream(device=None):
+    """The current stream of `device` (of the current device when None), as the void* the C ABI takes."""
+    return C.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def _nbytes(t: torch.Tensor) -> int:
+    return t.numel() * t.element_size()
+
+
+def _device(device) -> torch.device:
+    """torch.device with an explicit index ("cuda" means the current device)."""
+    d = torch.device(device)
+    if d.type == "cuda" and d.index is None:
+        d = torch.device("cuda", torch.cuda.current_device())
+    return d
+
+
+def expect_tensor(name: str, t, dtype, shape, device, optional: bool = False):
+    """Host-side check of one tensor argument before its address is handed to the library: the kernels trust
+    dtype, extent and device, so a wrong one would be read or written out of bounds."""
+    if t is None:
+        if optional:
+            return
+        raise NsaSelError(f"{name} is required")
+    if not isinstance(t, torch.Tensor):
+        raise NsaSelError(f"{name} must be a torch.Tensor")
+    if t.dtype != dtype:
+        raise NsaSelError(f"{name} must be {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise NsaSelError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    if t.device != _device(device):
+        raise NsaSelError(f"{name} must live on {_device(device)}, got {t.device}")
+    if not t.is_contiguous():
+        raise NsaSelError(f"{name} must be contiguous")
+
+
+def expect_workspace(name: str, t, min_bytes: int, device):
+    if not isinstance(t, torch.Tensor) or t.device != _device(device) or not t.is_contiguous():
+        raise NsaSelError(f"{name} must be a contiguous tensor on {_device(device)}")
+    if _nbytes(t) < min_bytes:
+        raise NsaSelError(f"{name} holds {_nbytes(t)} bytes, {min_bytes} are needed")
+
+
+def expect_attention_args(s: "Shape", device, *, q=None, k=None, v=None, idx=None, cu=None, o=None, lse=None,
+                          do=None, grads=None, gate=None, o_acc=None, o_out=None, dgate=None, need_idx=False):
+    """dtype / shape / device of every tensor of a forward or backward call against the shape `s` (only the
+    tensors given are checked; cu is required when the shape packs several sequences)."""
+    T, hq, hkv, d = s.total_tokens, s.hq, s.hkv, s.d
+    bf, f32, i32 = torch.bfloat16, torch.float32, torch.int32
+    for name, t, heads in (("q", q, hq), ("k", k, hkv), ("v", v, hkv), ("o", o, hq), ("do", do, hq),
+                           ("o_acc", o_acc, hq), ("o_out", o_out, hq)):
+        expect_tensor(name, t, bf, (T, heads, d), device, optional=True)
+    expect_tensor("lse", lse, f32, (T, hq), device, optional=True)
+    expect_tensor("gate", gate, f32, (T, hq), device, optional=True)
+    expect_tensor("dgate", dgate, f32, (T, hq), device, optional=True)
+    expect_tensor("idx", idx, i32, (T, hkv, s.topk), device, optional=not need_idx)
+    expect_tensor("cu_seqlens", cu, i32, (s.nseq + 1,), device, optional=s.nseq == 1)
+    if grads is not None:
+        for name, t, heads in zip(("dq", "dk", "dv"), grads, (hq, hkv, hkv)):
+            expect_tensor(name, t, bf, (T, heads, d), device)
+    if o_out is not None and o is not None and o_out.data_ptr() == o.data_ptr() and T > 0:
+        raise NsaSelError("o_out must not be the tensor o")
+    if o_acc is not None and o is not None and o_acc.data_ptr() == o.data_ptr() and T > 0:
+        raise NsaSelError("o_acc must not be the tensor o (the result would be o + gate * o)")
 
 
 def workspace_bytes(shape: Shape):
@@ -88,8 +150,12 @@ def workspace_bytes_min(shape: Shape):
 
 
 def build_index(shape: Shape, idx: torch.Tensor, cu: Optional[torch.Tensor], index_ws: torch.Tensor):
-    _check(lib().nsa_sel_build_index(C.byref(shape), _ptr(idx), _ptr(cu), _ptr(index_ws), index_ws.numel(), _stream()),
-           "nsa_sel_build_index")
+    dev = index_ws.device
+    expect_attention_args(shape, dev, idx=idx, cu=cu, need_idx=True)
+    expect_workspace("index_ws", index_ws, workspace_bytes(shape)[2], dev)
+    with torch.cuda.device(dev):
+        _check(lib().nsa_sel_build_index(C.byref(shape), _ptr(idx), _ptr(cu), _ptr(index_ws), _nbytes(index_ws),
+                                         _stream(dev)), "nsa_sel_build_index")
 
 
 def index_view(shape: Shape, index_ws: torch.Tensor):
@@ -103,15 +169,25 @@ def index_view(shape: Shape, index_ws: torch.Tensor):
 
 
 def nsa_sel_fwd(shape, q, k, v, idx, cu, rebuild_index, index_ws, o, lse, ws):
-    _check(lib().nsa_sel_fwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu), int(rebuild_index),
-                             _ptr(index_ws), index_ws.numel(), _ptr(o), _ptr(lse), _ptr(ws), ws.numel(), _stream()),
-           "nsa_sel_fwd")
+    dev = index_ws.device
+    expect_attention_args(shape, dev, q=q, k=k, v=v, idx=idx, cu=cu, o=o, lse=lse, need_idx=bool(rebuild_index))
+    expect_workspace("index_ws", index_ws, workspace_bytes(shape)[2], dev)
+    expect_workspace("ws", ws, workspace_bytes_min(shape)[0], dev)
+    with torch.cuda.device(dev):
+        _check(lib().nsa_sel_fwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu), int(rebuild_index),
+                                 _ptr(index_ws), _nbytes(index_ws), _ptr(o), _ptr(lse), _ptr(ws), _nbytes(ws),
+                                 _stream(dev)), "nsa_sel_fwd")
 
 
 def nsa_sel_bwd(shape, q, k, v, o, lse, do, cu, index_ws, dq, dk, dv, ws):
-    _check(lib().nsa_sel_bwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(cu),
-                             _ptr(index_ws), index_ws.numel(), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(),
-                             _stream()), "nsa_sel_bwd")
+    dev = index_ws.device
+    expect_attention_args(shape, dev, q=q, k=k, v=v, cu=cu, o=o, lse=lse, do=do, grads=(dq, dk, dv))
+    expect_workspace("index_ws", index_ws, workspace_bytes(shape)[2], dev)
+    expect_workspace("ws", ws, workspace_bytes_min(shape)[1], dev)
+    with torch.cuda.device(dev):
+        _check(lib().nsa_sel_bwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(cu),
+                                 _ptr(index_ws), _nbytes(index_ws), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), _nbytes(ws),
+                                 _stream(dev)), "nsa_sel_bwd")
 
 
 def select_blocks(scores: torch.Tensor, cu: Optional[torch.Tensor], topk: int, *, block: int = 64,
@@ -122,10 +198,15 @@ def select_blocks(scores: torch.Tensor, cu: Optional[torch.Tensor], topk: int, *
     T, hkv, stride = scores.shape
     nseq = 1 if cu is None else cu.numel() - 1
     shape = Shape(T, nseq, hkv, hkv, 128, block, topk, int(causal), 0.0, 0)
+    dev = scores.device
     if out is None:
-        out = torch.empty(T, hkv, topk, dtype=torch.int32, device=scores.device)
-    _check(lib().nsa_sel_select_blocks(C.byref(shape), _ptr(scores), stride, _ptr(cu), n_sink, n_local, _ptr(out),
-                                       _stream()), "nsa_sel_select_blocks")
+        out = torch.empty(T, hkv, topk, dtype=torch.int32, device=dev)
+    expect_tensor("scores", scores, torch.float32, (T, hkv, stride), dev)
+    expect_tensor("cu_seqlens", cu, torch.int32, (nseq + 1,), dev, optional=True)
+    expect_tensor("out", out, torch.int32, (T, hkv, topk), dev)
+    with torch.cuda.device(dev):
+        _check(lib().nsa_sel_select_blocks(C.byref(shape), _ptr(scores), stride, _ptr(cu), n_sink, n_local, _ptr(out),
+                                           _stream(dev)), "nsa_sel_select_blocks")
     return out
 
 
@@ -136,9 +217,12 @@ def window_blocks(total_tokens: int, hkv: int, window: int, cu: Optional[torch.T
     topk = -(-(window - 1) // block) + 1
     nseq = 1 if cu is None else cu.numel() - 1
     shape = Shape(total_tokens, nseq, hkv, hkv, 128, block, topk, 1, 0.0, 0)
-    out = torch.empty(total_tokens, hkv, topk, dtype=torch.int32, device=device)
-    _check(lib().nsa_sel_select_blocks(C.byref(shape), None, 0, _ptr(cu), 0, topk, _ptr(out), _stream()),
-           "nsa_sel_select_blocks")
+    dev = _device(device)
+    out = torch.empty(total_tokens, hkv, topk, dtype=torch.int32, device=dev)
+    expect_tensor("cu_seqlens", cu, torch.int32, (nseq + 1,), dev, optional=True)
+    with torch.cuda.device(dev):
+        _check(lib().nsa_sel_select_blocks(C.byref(shape), None, 0, _ptr(cu), 0, topk, _ptr(out), _stream(dev)),
+               "nsa_sel_select_blocks")
     return out
 
 
@@ -172,14 +256,20 @@ def profile_collect():
 
 
 def calibration_copy(dst: torch.Tensor, src: torch.Tensor):
-    nbytes = src.numel() * src.element_size()
-    _check(lib().nsa_sel_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream()), "nsa_sel_calibration_copy")
+    nbytes = _nbytes(src)
+    if _nbytes(dst) < nbytes or dst.device != src.device:
+        raise NsaSelError("calibration_copy: dst must be on src's device and at least as large")
+    with torch.cuda.device(src.device):
+        _check(lib().nsa_sel_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(src.device)),
+               "nsa_sel_calibration_copy")
 
 
 def mfma_probe(iters: int, sink: torch.Tensor) -> float:
     """Enqueue the MFMA probe kernel; returns the FLOPs it performs."""
     fl = C.c_double()
-    _check(lib().nsa_sel_mfma_probe(int(iters), _ptr(sink), C.byref(fl), _stream()), "nsa_sel_mfma_probe")
+    expect_tensor("sink", sink, torch.float32, tuple(sink.shape), sink.device)
+    with torch.cuda.device(sink.device):
+        _check(lib().nsa_sel_mfma_probe(int(iters), _ptr(sink), C.byref(fl), _stream(sink.device)), "nsa_sel_mfma_probe")
     return fl.value
 
 
@@ -196,7 +286,7 @@ class SelAttention:
             fmin, bmin = workspace_bytes_min(self.shape)
             fb = min(fb, max(fmin, int(ws_cap_bytes)))
             bb = min(bb, max(bmin, int(ws_cap_bytes)))
-        self.device = torch.device(device)
+        self.device = _device(device)
         self.index_ws = torch.empty(ib, dtype=torch.uint8, device=self.device)
         self.fwd_ws = torch.empty(fb, dtype=torch.uint8, device=self.device)
         self.bwd_ws = torch.empty(bb, dtype=torch.uint8, device=self.device) if bwd else None
@@ -244,6 +334,8 @@ class SelAttention:
             dv = torch.empty_like(v)
         else:
             dq, dk, dv = out
+        if self.bwd_ws is None:
+            raise NsaSelError("this SelAttention was created with bwd=False")
         nsa_sel_bwd(s, q, k, v, o, lse, do, cu, self.index_ws, dq, dk, dv, self.bwd_ws)
         return dq, dk, dv
 
@@ -252,8 +344,10 @@ class SelAttention:
         s = self.shape
         o = torch.empty(s.total_tokens, s.hq, 128, dtype=torch.bfloat16, device=self.device)
         l = torch.empty(s.total_tokens, s.hq, dtype=torch.float32, device=self.device)
-        _check(lib().nsa_sel_fwd_query_outer(C.byref(s), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu), _ptr(o), _ptr(l),
-                                             _stream()), "nsa_sel_fwd_query_outer")
+        expect_attention_args(s, self.device, q=q, k=k, v=v, idx=idx, cu=cu, need_idx=True)
+        with torch.cuda.device(self.device):
+            _check(lib().nsa_sel_fwd_query_outer(C.byref(s), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu), _ptr(o),
+                                                 _ptr(l), _stream(self.device)), "nsa_sel_fwd_query_outer")
         return o, l
 
     def forward_gated(self, q, k, v, idx, gate, o_acc=None, cu=None, rebuild_index=True, out=None):
@@ -262,10 +356,13 @@ class SelAttention:
         o = torch.empty(s.total_tokens, s.hq, 128, dtype=torch.bfloat16, device=self.device)
         l = torch.empty(s.total_tokens, s.hq, dtype=torch.float32, device=self.device)
         o_out = torch.empty_like(o) if out is None else out
-        _check(lib().nsa_sel_fwd_gated(C.byref(s), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu), int(rebuild_index),
-                                       _ptr(self.index_ws), self.index_ws.numel(), _ptr(o), _ptr(l), _ptr(gate),
-                                       _ptr(o_acc), _ptr(o_out), _ptr(self.fwd_ws), self.fwd_ws.numel(), _stream()),
-               "nsa_sel_fwd_gated")
+        expect_attention_args(s, self.device, q=q, k=k, v=v, idx=idx, cu=cu, gate=gate, o_acc=o_acc, o_out=o_out, o=o,
+                              need_idx=bool(rebuild_index))
+        with torch.cuda.device(self.device):
+            _check(lib().nsa_sel_fwd_gated(C.byref(s), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu),
+                                           int(rebuild_index), _ptr(self.index_ws), _nbytes(self.index_ws), _ptr(o),
+                                           _ptr(l), _ptr(gate), _ptr(o_acc), _ptr(o_out), _ptr(self.fwd_ws),
+                                           _nbytes(self.fwd_ws), _stream(self.device)), "nsa_sel_fwd_gated")
         return o_out, o, l
 
     def backward_gated(self, q, k, v, o, lse, do_out, gate, cu=None):
@@ -273,10 +370,14 @@ class SelAttention:
         s = self.shape
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         dgate = torch.empty(s.total_tokens, s.hq, dtype=torch.float32, device=self.device)
-        _check(lib().nsa_sel_bwd_gated(C.byref(s), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do_out),
-                                       _ptr(gate), _ptr(cu), _ptr(self.index_ws), self.index_ws.numel(), _ptr(dq),
-                                       _ptr(dk), _ptr(dv), _ptr(dgate), _ptr(self.bwd_ws), self.bwd_ws.numel(),
-                                       _stream()), "nsa_sel_bwd_gated")
+        expect_attention_args(s, self.device, q=q, k=k, v=v, cu=cu, o=o, lse=lse, do=do_out, gate=gate)
+        if self.bwd_ws is None:
+            raise NsaSelError("this SelAttention was created with bwd=False")
+        with torch.cuda.device(self.device):
+            _check(lib().nsa_sel_bwd_gated(C.byref(s), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do_out),
+                                           _ptr(gate), _ptr(cu), _ptr(self.index_ws), _nbytes(self.index_ws), _ptr(dq),
+                                           _ptr(dk), _ptr(dv), _ptr(dgate), _ptr(self.bwd_ws), _nbytes(self.bwd_ws),
+                                           _stream(self.device)), "nsa_sel_bwd_gated")
         return dq, dk, dv, dgate
 
     def index_arrays(self):

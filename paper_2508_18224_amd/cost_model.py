@@ -32,3 +32,15 @@ def effective_flops(total_tokens: int, hq: int, topk: int, d: int = 128, block: 
     padded slots and the masked part of the diagonal block are counted."""
     f = fsa_selected_flops(total_tokens, hq, d, block, topk)
     return f, 2.5 * f
+
+
+def compulsory_bytes(total_tokens: int, hq: int, hkv: int, topk: int, d: int = 128):
+    """(forward, backward) bytes the method itself must move through HBM, each tensor once: forward reads Q, K, V and
+    idx and writes O and LSE; backward reads Q, K, V, O, dO, LSE, delta and idx and writes dQ, dK, dV (bf16 tensors,
+    fp32 row statistics, int32 idx).  Partial buffers and gathers re-reading Q / dO are not in it: they are what the
+    measured traffic is compared against."""
+    T = total_tokens
+    stats, idx = 4.0 * T * hq, 4.0 * T * hkv * topk
+    fwd = 2.0 * T * d * (2 * hq + 2 * hkv) + stats + idx
+    bwd = 2.0 * T * d * (4 * hq + 4 * hkv) + 2 * stats + idx
+    return fwd, bwd

@@ -217,7 +217,9 @@ int nsa_sel_fwd_gated(const nsa_sel_shape* shape, const void* Q, const void* K, 
                       const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
                       float* LSE, const float* gate, const void* O_acc, void* O_out, void* ws, size_t ws_bytes,
                       void* stream) {
-  if (!gate || !O_out || !aligned16(O_out) || (O_acc && !aligned16(O_acc)) || ((uintptr_t)gate & 3) || O_out == O)
+  // O_out == O would overwrite the ungated result the backward needs; O_acc == O would be read after O is written
+  if (!gate || !O_out || !aligned16(O_out) || (O_acc && !aligned16(O_acc)) || ((uintptr_t)gate & 3) || O_out == O ||
+      (O_acc && O_acc == O))
     return NSA_SEL_EINVAL;
   return fwd_impl(shape, Q, K, V, idx, cu_seqlens, rebuild_index, index_ws, index_bytes, O, LSE,
                   GateArgs{gate, O_acc, O_out, nullptr}, ws, ws_bytes, stream);

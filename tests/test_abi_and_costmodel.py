@@ -81,3 +81,63 @@ def test_product_path_does_not_import_the_oracle():
             if fn.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text, fn
+
+
+def test_binding_validates_tensors_on_the_host():
+    """dtype, shape, device and contiguity of every tensor are checked before an address reaches the library."""
+    import torch
+    nsa, _ = _lib()
+    from paper_2508_18224_amd import binding as B
+    s = nsa.Shape(256, 2, 8, 2, 128, 64, 4, 1, 0.0, 0)
+    bf, f32, i32 = torch.bfloat16, torch.float32, torch.int32
+    good = dict(q=torch.zeros(256, 8, 128, dtype=bf), k=torch.zeros(256, 2, 128, dtype=bf),
+                v=torch.zeros(256, 2, 128, dtype=bf), idx=torch.zeros(256, 2, 4, dtype=i32),
+                cu=torch.tensor([0, 100, 256], dtype=i32), o=torch.zeros(256, 8, 128, dtype=bf),
+                lse=torch.zeros(256, 8, dtype=f32), do=torch.zeros(256, 8, 128, dtype=bf),
+                gate=torch.zeros(256, 8, dtype=f32))
+    B.expect_attention_args(s, "cpu", need_idx=True, **good)                 # all consistent: passes
+    bad = {
+        "q": [good["q"].float(), good["q"].half(), good["q"][:255], good["q"].transpose(0, 1).contiguous()],
+        "k": [good["k"].float(), torch.zeros(256, 8, 128, dtype=bf)],
+        "idx": [good["idx"].long(), torch.zeros(256, 2, 16, dtype=i32), None],
+        "cu": [good["cu"].long(), torch.tensor([0, 256], dtype=i32), None],
+        "lse": [good["lse"].double(), torch.zeros(256, 2, dtype=f32)],
+        "gate": [good["gate"].double(), torch.zeros(256, dtype=f32)],
+        "do": [good["do"].float(), torch.zeros(128, 8, 128, dtype=bf)],
+    }
+    for name, cases in bad.items():
+        for t in cases:
+            with pytest.raises(nsa.NsaSelError):
+                B.expect_attention_args(s, "cpu", need_idx=True, **{**good, name: t})
+    with pytest.raises(nsa.NsaSelError):                                  # a strided view
+        B.expect_attention_args(s, "cpu", **{**good, "q": torch.zeros(256, 8, 256, dtype=bf)[:, :, ::2]})
+    with pytest.raises(nsa.NsaSelError):                                  # wrong device
+        B.expect_attention_args(s, "cuda:0", **good)
+    with pytest.raises(nsa.NsaSelError):                                  # the gated sum may not alias O
+        B.expect_attention_args(s, "cpu", **{**good, "o_acc": good["o"]})
+    with pytest.raises(nsa.NsaSelError):
+        B.expect_attention_args(s, "cpu", **{**good, "o_out": good["o"]})
+    with pytest.raises(nsa.NsaSelError):                                  # gradients: dk with query-head count
+        B.expect_attention_args(s, "cpu", grads=(good["q"], good["q"], good["k"]), **good)
+    # workspaces are sized in bytes whatever the element type of the tensor that holds them
+    need = nsa.workspace_bytes_min(s)[0]
+    B.expect_workspace("ws", torch.zeros((need + 3) // 4, dtype=torch.float32), need, "cpu")
+    with pytest.raises(nsa.NsaSelError):
+        B.expect_workspace("ws", torch.zeros(need // 4 - 1, dtype=torch.float32), need, "cpu")
+    with pytest.raises(nsa.NsaSelError):
+        B.expect_workspace("ws", torch.zeros(need, dtype=torch.uint8), need, "cuda:0")
+    # the entry points run these checks before they touch the library: a CPU tensor never reaches a kernel
+    ws = torch.zeros(16, dtype=torch.uint8)
+    with pytest.raises(nsa.NsaSelError):
+        nsa.nsa_sel_fwd(s, good["q"], good["k"], good["v"], good["idx"], good["cu"], True, ws, good["o"], good["lse"], ws)
+
+
+def test_gated_forward_rejects_aliasing_of_the_ungated_output():
+    nsa, L = _lib()
+    ok = nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 1, 0.0, 0)
+    vp = ctypes.c_void_p
+    a, b, c = vp(4096), vp(8192), vp(16384)
+    big = 1 << 40
+    # O_out == O and O_acc == O are argument errors, found on the host before any launch
+    assert L.nsa_sel_fwd_gated(ctypes.byref(ok), a, a, a, a, None, 0, a, big, b, a, a, None, b, a, big, None) == -1
+    assert L.nsa_sel_fwd_gated(ctypes.byref(ok), a, a, a, a, None, 0, a, big, b, a, a, b, c, a, big, None) == -1

@@ -1,20 +1,56 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-The oracle cannot run these shapes whole, so each case checks (a) sampled query rows (O, LSE, dQ) and sampled KV
-blocks (dK, dV; every token that selects the block is revisited by the oracle) element by element, and (b)
-properties that hold at any size: LSE of zero queries is the log of an exactly countable number of visible
-keys, and the column sums of dV equal the summed dO of each head group (softmax rows sum to one)."""
-import math
+The oracle cannot run these shapes whole, so each case checks (a) >= 256 sampled query rows (O, LSE, dQ) and >= 8
+sampled KV blocks including the last one (dK, dV; every token that selects the block is revisited by the oracle)
+element by element - at the headline, the varlen and the 128-token-block shapes also a block whose query list is split
+over several work units, which exercises the fixed-order dK/dV reduction - and (b) properties that hold at any size:
+LSE of zero queries is the log of an exactly countable number of visible keys, and the column sums of dV equal the
+summed dO of each head group (softmax rows sum to one).
+
+The oracle runs as a separate process (oracle/sample_cli.py: nsa_sel_oracle as it stands, token ranges spread over
+the host's cores) that regenerates the same seeded inputs and never touches the GPU; it is started before the GPU
+work of the case and joined afterwards."""
+import os
+import subprocess
+import sys
+import tempfile
 
 import numpy as np
 import pytest
 import torch
 
 import workloads as wl
-from oracle import nsa_sel_oracle as orc
-from gpu_util import BitsF64, Case, TOL_GRAD, TOL_O, TOL_LSE, assert_close, to_f64
+from gpu_util import Case, TOL_GRAD, TOL_O, TOL_LSE, assert_close, assert_dgate_close, dev_bf16, to_f64
 
 pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+class OracleRun:
+    """The oracle on `tokens` / `blocks` of a named workload, in a child process."""
+
+    def __init__(self, name, tokens, blocks, window=0, gated=False, forward_only=False):
+        self.tokens, self.blocks = list(tokens), list(blocks)
+        self.path = tempfile.mktemp(suffix=".npz", prefix="nsa_ref_")
+        cmd = [sys.executable, "-m", "oracle.sample_cli", "--workload", name, "--out", self.path,
+               "--tokens", ",".join(str(t) for t in self.tokens),
+               "--blocks", ",".join(":".join(str(x) for x in b) for b in self.blocks)]
+        if window:
+            cmd += ["--window", str(window)]
+        if gated:
+            cmd.append("--gated")
+        if forward_only:
+            cmd.append("--forward-only")
+        self.proc = subprocess.Popen(cmd, cwd=ROOT, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+
+    def result(self):
+        out, _ = self.proc.communicate(timeout=900)
+        assert self.proc.returncode == 0, out
+        print("  oracle:", out.strip().splitlines()[-1], flush=True)
+        ref = dict(np.load(self.path))
+        os.unlink(self.path)
+        assert [int(t) for t in ref["tokens"]] == self.tokens
+        return ref
 
 
 def _visible_counts(w):
@@ -37,8 +73,56 @@ def _visible_counts(w):
     return full + diag
 
 
-def _run_case(name, n_tokens, blocks, window=0):
+def _sample_tokens(T, n, seed=99):
+    rng = np.random.default_rng(seed)
+    return sorted({0, 63, 64, T - 1, *[int(x) for x in rng.integers(0, T, n)]})
+
+
+def _sample_blocks(w0, n, extra=(), seed=7):
+    """n (kv head, sequence, block) triples spread over heads and positions, always with the last block of the last
+    sequence, plus `extra`."""
+    rng = np.random.default_rng(seed)
+    nseq = len(w0.seqlens)
+    out = list(extra)
+    last_s = nseq - 1
+    out.append((w0.hkv - 1, last_s, -(-w0.seqlens[last_s] // w0.block) - 1))
+    while len(out) < n + len(extra):
+        s = int(rng.integers(0, nseq))
+        nb = -(-w0.seqlens[s] // w0.block)
+        cand = (int(rng.integers(0, w0.hkv)), s, int(rng.integers(1, nb)))
+        if cand not in out:
+            out.append(cand)
+    return out
+
+
+def _check_rows(ref, tokens, o, lse, dq):
+    sel = torch.tensor(tokens, device="cuda")
+    assert_close("O", to_f64(o[sel]), ref["O"], TOL_O)
+    got, want = to_f64(lse[sel]), ref["LSE"]
+    assert np.array_equal(np.isneginf(got), np.isneginf(want))
+    fin = np.isfinite(want)
+    assert np.abs(got[fin] - want[fin]).max() <= TOL_LSE
+    if dq is not None:
+        assert_close("dQ", to_f64(dq[sel]), ref["dQ"], TOL_GRAD)
+    print(f"  {len(tokens)} sampled rows ok", flush=True)
+
+
+def _check_blocks(ref, w, blocks, dk, dv):
+    for n, (j, s, x) in enumerate(blocks):
+        dKb, dVb = ref[f"dK{n}"], ref[f"dV{n}"]
+        lo = int(w.cu_seqlens[s]) + x * w.block
+        hi = lo + dKb.shape[0]
+        assert_close(f"dK block {(j, s, x)}", to_f64(dk[lo:hi, j]), dKb, TOL_GRAD)
+        assert_close(f"dV block {(j, s, x)}", to_f64(dv[lo:hi, j]), dVb, TOL_GRAD)
+    print(f"  {len(blocks)} sampled kv blocks ok", flush=True)
+
+
+def _run_case(name, n_tokens=256, n_blocks=8, extra_blocks=(), window=0, closed_forms=True):
     print("full-size case", name, "window", window, flush=True)
+    w0 = wl.named(name)
+    tokens = _sample_tokens(w0.total_tokens, n_tokens)
+    blocks = _sample_blocks(w0, n_blocks, extra_blocks)
+    oracle = OracleRun(name, tokens, blocks, window=window)
     w = wl.realise(wl.named(name))
     if window:                                               # the sliding-window branch at the same shape
         w.idx = wl.window_block_indices(w.seqlens, w.hkv, window, w.block)
@@ -48,23 +132,16 @@ def _run_case(name, n_tokens, blocks, window=0):
     o, lse = c.forward()
     dq, dk, dv = c.backward(o, lse)
     print("  gpu done", flush=True)
-    Q, K, V, dO = (BitsF64(x) for x in (w.q, w.k, w.v, w.do))
-    rng = np.random.default_rng(99)
-    tokens = sorted({0, 63, 64, T - 1, *[int(x) for x in rng.integers(0, T, n_tokens)]})
-    O_ref, LSE_ref = orc.forward(Q, K, V, w.idx, w.cu_seqlens, block=w.block, tokens=tokens, window=window)
-    dQ_ref, _, _ = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, block=w.block, tokens=tokens, window=window)
-    sel = torch.tensor(tokens, device="cuda")
-    assert_close("O", to_f64(o[sel]), O_ref[tokens], TOL_O)
-    assert np.abs(to_f64(lse[sel]) - LSE_ref[tokens]).max() <= TOL_LSE
-    assert_close("dQ", to_f64(dq[sel]), dQ_ref[tokens], TOL_GRAD)
-    print("  sampled rows ok", flush=True)
-    ref = orc.backward_kv_blocks(Q, K, V, dO, w.idx, w.cu_seqlens, blocks, block=w.block, window=window)
-    for (j, s, x), (dKb, dVb) in zip(blocks, ref):
-        lo = int(w.cu_seqlens[s]) + x * w.block
-        hi = lo + dKb.shape[0]
-        assert_close(f"dK block {(j, s, x)}", to_f64(dk[lo:hi, j]), dKb, TOL_GRAD)
-        assert_close(f"dV block {(j, s, x)}", to_f64(dv[lo:hi, j]), dVb, TOL_GRAD)
-    print("  sampled kv blocks ok", flush=True)
+    if extra_blocks:                                         # these lists must really be split over work units
+        cnt, _, _, _, _, _ = c.attn.index_arrays()
+        for (j, s, x) in extra_blocks:
+            gb = sum(-(-L // w.block) for L in w.seqlens[:s]) + x
+            assert cnt[j, gb] > 2048, (j, s, x, int(cnt[j, gb]))
+    ref = oracle.result()
+    _check_rows(ref, tokens, o, lse, dq)
+    _check_blocks(ref, w, blocks, dk, dv)
+    if not closed_forms:
+        return
     # softmax rows sum to one: sum_u dV[u, j, :] == sum over tokens and the group's heads of dO
     want = c.do.double().view(T, w.hkv, g, 128).sum(dim=(0, 2))
     got = dv.double().sum(dim=0)
@@ -85,30 +162,86 @@ def _run_case(name, n_tokens, blocks, window=0):
 
 
 def test_headline_64k_g4():
-    _run_case("headline", 12, [(0, 0, 0), (3, 0, 517), (7, 0, 1023)])
+    _run_case("headline", extra_blocks=[(0, 0, 0)])           # the sink block's list: 32 work units
 
 
 def test_headline_shape_sliding_window_512():
-    _run_case("headline", 10, [(0, 0, 0), (4, 0, 600), (7, 0, 1023)], window=512)
+    _run_case("headline", window=512)
 
 
 def test_llama8b_32k_g4():
-    _run_case("llama8b_32k", 8, [(2, 0, 100), (5, 0, 511)])
+    _run_case("llama8b_32k")
 
 
 def test_headline_128_token_blocks():
-    _run_case("headline_b128", 8, [(1, 0, 300), (6, 0, 511)])
+    _run_case("headline_b128", extra_blocks=[(5, 0, 0)])
 
 
 def test_qwen_g7_64k():
-    _run_case("qwen_g7", 8, [(1, 0, 300), (3, 0, 1000)])
+    _run_case("qwen_g7")
 
 
 def test_varlen_g1():
     w = wl.named("varlen_g1")
-    last = len(w.seqlens) - 1
-    _run_case("varlen_g1", 8, [(5, 2, 10), (15, last, 3)])
+    shortest = int(np.argmin(w.seqlens))
+    _run_case("varlen_g1", extra_blocks=[(9, shortest, 0)])   # first block of the shortest sequence: > 1 work unit
 
 
 def test_llama70b_128k_g8():
-    _run_case("llama70b_128k", 6, [(2, 0, 1500), (7, 0, 2047)])
+    _run_case("llama70b_128k")
+
+
+@pytest.mark.parametrize("name", ["grid_g1_b128_n64", "grid_g8_b128_n64"])
+def test_128_token_blocks_at_g1_and_g8(name):
+    _run_case(name, n_tokens=128, n_blocks=4, closed_forms=False)
+
+
+def test_ultra_long_256k_tokens_64_heads():
+    """The largest shape of the paper's grid (App. F): 256K tokens, 64 query heads (g = 8), (B_K, T) = (64, 16)."""
+    _run_case("grid_g8_b64_n256_h64", n_tokens=64, n_blocks=4)
+
+
+def test_headline_gated_entry_points():
+    """nsa_sel_fwd_gated / nsa_sel_bwd_gated at the headline shape: O_out, dQ, dgate on sampled rows, dK/dV on sampled
+    blocks (the oracle's gated backward is its backward on gate * dO_out)."""
+    name = "headline"
+    print("full-size case gated", name, flush=True)
+    w0 = wl.named(name)
+    tokens = _sample_tokens(w0.total_tokens, 256, seed=5)
+    blocks = _sample_blocks(w0, 4, seed=11)
+    oracle = OracleRun(name, tokens, blocks, gated=True)
+    w = wl.realise(wl.named(name))
+    T = w.total_tokens
+    c = Case(w)
+    gate = wl.draw_gates(w.seed, T, w.hq)
+    acc_bits = wl.draw_other_branches(w.seed, T, w.hq)
+    gate_d, acc_d = torch.from_numpy(gate).cuda(), dev_bf16(acc_bits)
+    o_out, o, lse = c.attn.forward_gated(c.q, c.k, c.v, c.idx, gate_d, acc_d, c.cu)
+    dq, dk, dv, dgate = c.attn.backward_gated(c.q, c.k, c.v, o, lse, c.do, gate_d, c.cu)
+    torch.cuda.synchronize()
+    print("  gpu done", flush=True)
+    ref = oracle.result()
+    _check_rows(ref, tokens, o, lse, dq)
+    _check_blocks(ref, w, blocks, dk, dv)
+    from oracle import nsa_sel_oracle as orc
+    sel = torch.tensor(tokens, device="cuda")
+    rO = ref["O"]                                            # the ungated output (the gate only scales dO)
+    g64 = gate.astype(np.float64)[tokens]
+    assert_close("O_out", to_f64(o_out[sel]), orc.gated_forward(rO, g64, wl.bf16_bits_to_f64(acc_bits[tokens])), TOL_O)
+    assert_dgate_close("dgate", to_f64(dgate[sel]), wl.bf16_bits_to_f64(w.do[tokens]), rO)
+    off = torch.from_numpy(gate == 0.0).cuda()
+    assert bool(off.any()) and not bool(dq[off].any())        # a closed gate passes no gradient
+
+
+def test_headline_query_outer_forward():
+    """nsa_sel_fwd_query_outer at the headline shape on sampled rows."""
+    name = "headline"
+    print("full-size case query-outer", name, flush=True)
+    w0 = wl.named(name)
+    tokens = _sample_tokens(w0.total_tokens, 256, seed=3)
+    oracle = OracleRun(name, tokens, [], forward_only=True)
+    w = wl.realise(wl.named(name))
+    c = Case(w, bwd=False)
+    o, lse = c.attn.forward_query_outer(c.q, c.k, c.v, c.idx, c.cu)
+    torch.cuda.synchronize()
+    _check_rows(oracle.result(), tokens, o, lse, None)

@@ -1,0 +1,90 @@
+"""A bounded, seeded sweep over random shapes, selections, windows, gates and unit sizes: every entry point of the path
+against the oracles on the same inputs.  It stops at the first failing case and names its seed.  (The dgate bound of
+gpu_util.assert_dgate_close is exercised here on every gated case.)"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2508_18224_amd as nsa
+import workloads as wl
+from oracle import nsa_sel_oracle as orc
+from oracle import topk_select_oracle as tko
+from gpu_util import (Case, TOL_GRAD, TOL_O, assert_close, assert_dgate_close, assert_lse_close, dev_bf16, to_f64)
+
+pytestmark = pytest.mark.gpu
+N_CASES = 40
+
+
+def _one(seed):
+    rng = np.random.default_rng(50000 + seed)
+    nseq = int(rng.integers(1, 5))
+    seqlens = [int(x) for x in rng.integers(0, 420, size=nseq)]
+    if sum(seqlens) == 0:
+        seqlens[0] = 5
+    hkv, g = int(rng.integers(1, 4)), int(rng.integers(1, 9))
+    block = int(rng.choice([64, 128]))
+    topk = int(rng.integers(1, 13))
+    causal = bool(rng.integers(0, 4) > 0)
+    window = int(rng.choice([0, 0, 1, 50, 64, 129, 300])) if causal else 0
+    mode = int(rng.integers(0, 3))   # 0: the workload recipe, 1: adversarial ids, 2: idx from nsa_sel_select_blocks
+    gated = bool(rng.integers(0, 2))
+    unit = int(rng.choice([0, 256, 512, 1024, 2048]))
+    cap = 1 if rng.integers(0, 2) else None
+    info = dict(seed=seed, seqlens=seqlens, hkv=hkv, g=g, block=block, topk=topk, causal=causal, window=window,
+                mode=mode, gated=gated, unit=unit, cap=cap)
+    print("sweep case", info, flush=True)
+    w = wl.Workload(f"s{seed}", seqlens, hq=hkv * g, hkv=hkv, topk=topk, causal=causal,
+                    sink=bool(rng.integers(0, 2)) and topk >= 2, block=block, seed=seed)
+    wl.realise(w)
+    T = w.total_tokens
+    if mode == 1:
+        w.idx = wl.draw_adversarial_indices(rng, seqlens, hkv, topk, block=block)
+    elif mode == 2:
+        kind = str(rng.choice(["heavy", "ties", "wild"]))
+        x = wl.draw_block_scores(seed, seqlens, hkv, block, kind=kind, trap_future=causal)
+        ns, nl = int(rng.integers(0, 3)), int(rng.integers(0, 4))
+        ref_idx = tko.select_blocks(x, w.cu_seqlens, topk, block=block, causal=causal, n_sink=ns, n_local=nl)
+        got = nsa.select_blocks(torch.from_numpy(x).cuda(), torch.from_numpy(w.cu_seqlens).cuda(), topk, block=block,
+                                causal=causal, n_sink=ns, n_local=nl)
+        assert np.array_equal(got.cpu().numpy(), ref_idx), "select_blocks"
+        w.idx = ref_idx
+    c = Case(w, window=window)
+    c.attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(seqlens), causal=causal, block=block, window=window,
+                              unit=unit, ws_cap_bytes=cap)
+    Q, K, V, dO = c.host_f64()
+    kw = dict(causal=causal, block=block, window=window)
+    rO, rL = orc.forward(Q, K, V, w.idx, w.cu_seqlens, **kw)
+    if gated:
+        gate = wl.draw_gates(seed, T, w.hq)
+        acc = wl.draw_other_branches(seed, T, w.hq)
+        gd = torch.from_numpy(gate).cuda()
+        out, o, lse = c.attn.forward_gated(c.q, c.k, c.v, c.idx, gd, dev_bf16(acc), c.cu)
+        dq, dk, dv, dg = c.attn.backward_gated(c.q, c.k, c.v, o, lse, c.do, gd, c.cu)
+        torch.cuda.synchronize()
+        assert_close("O_out", to_f64(out), orc.gated_forward(rO, gate.astype(np.float64), wl.bf16_bits_to_f64(acc)),
+                     TOL_O)
+        rq, rk, rv = orc.backward(Q, K, V, gate.astype(np.float64)[:, :, None] * dO, w.idx, w.cu_seqlens, **kw)
+        assert_dgate_close("dgate", to_f64(dg), dO, rO)
+    else:
+        o, lse = c.forward()
+        dq, dk, dv = c.backward(o, lse)
+        rq, rk, rv = orc.backward(Q, K, V, dO, w.idx, w.cu_seqlens, **kw)
+    assert_close("O", to_f64(o), rO, TOL_O)
+    assert_lse_close(to_f64(lse), rL)
+    if block == 64 and window == 0:
+        qo, ql = c.attn.forward_query_outer(c.q, c.k, c.v, c.idx, c.cu)
+        torch.cuda.synchronize()
+        assert_close("O query-outer", to_f64(qo), rO, TOL_O)
+        assert_lse_close(to_f64(ql), rL)
+    assert_close("dQ", to_f64(dq), rq, TOL_GRAD)
+    assert_close("dK", to_f64(dk), rk, TOL_GRAD)
+    assert_close("dV", to_f64(dv), rv, TOL_GRAD)
+    cnt, off, qlist, qslot, vmask, bcap = c.attn.index_arrays()
+    rc, ro, rl, rs, rvm = orc.invert_index(w.idx, w.cu_seqlens, block=block, causal=causal, window=window)
+    assert np.array_equal(cnt[:, :rc.shape[1]], rc) and np.array_equal(qlist, rl) and np.array_equal(qslot, rs)
+    assert np.array_equal(vmask, rvm)
+
+
+def test_random_sweep_of_every_entry_point():
+    for seed in range(N_CASES):
+        _one(seed)                      # the first failure ends the sweep; its seed is in the printed case line

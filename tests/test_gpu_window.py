@@ -8,9 +8,21 @@ import torch
 import paper_2508_18224_amd as nsa
 import workloads as wl
 from oracle import nsa_sel_oracle as orc
+from oracle import topk_select_oracle as tko
 from gpu_util import Case, TOL_GRAD, TOL_O, assert_close, assert_lse_close, to_f64
 
 pytestmark = pytest.mark.gpu
+
+
+def _oracle_window_table(seqlens, hkv, window, block=64):
+    """The blocks a causal window of `window` tokens can touch, from the selection oracle: no sink, the
+    R + 1 = ceil((window - 1) / block) + 1 most recent blocks forced, which leaves no free pick (scores are never read
+    for a decision, so zeros serve)."""
+    topk = -(-(window - 1) // block) + 1
+    cu = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int64)
+    nb = max(-(-L // block) for L in seqlens)
+    scores = np.zeros((sum(seqlens), hkv, max(nb, 1)), dtype=np.float32)
+    return tko.select_blocks(scores, cu, topk, block=block, causal=True, n_sink=0, n_local=topk)
 
 
 @pytest.mark.parametrize("seqlens,hkv,window,block", [([2000], 2, 512, 64), ([700, 64, 1, 333, 1029], 3, 100, 64),
@@ -21,7 +33,9 @@ def test_window_block_table_is_exact(seqlens, hkv, window, block):
     cu = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int32)
     got = nsa.window_blocks(sum(seqlens), hkv, window, torch.from_numpy(cu).cuda(), block=block)
     torch.cuda.synchronize()
-    assert np.array_equal(got.cpu().numpy(), wl.window_block_indices(seqlens, hkv, window, block))
+    ref = _oracle_window_table(seqlens, hkv, window, block)
+    assert np.array_equal(got.cpu().numpy(), ref)
+    assert np.array_equal(wl.window_block_indices(seqlens, hkv, window, block), ref)   # the input generator agrees
 
 
 def _run(w, window, idx=None, check_index=False):
@@ -79,5 +93,5 @@ def test_window_table_from_the_device_feeds_the_path():
     idx_d = nsa.window_blocks(w.total_tokens, w.hkv, window, cu_d)
     w.idx = idx_d.cpu().numpy()
     w.topk = w.idx.shape[2]
-    assert np.array_equal(w.idx, wl.window_block_indices(w.seqlens, w.hkv, window))
+    assert np.array_equal(w.idx, _oracle_window_table(w.seqlens, w.hkv, window))
     _run(w, window)
