@@ -42,6 +42,11 @@ extern "C" {
 #define NSA_SEL_EUNSUPPORTED -2   /* d != 128, block not 64 or 128, topk outside [1,32], too many tokens      */
 #define NSA_SEL_EWORKSPACE   -3   /* index workspace too small, or ws below nsa_sel_workspace_bytes_min       */
 #define NSA_SEL_EHIP         -4   /* the HIP runtime refused a launch or attribute                            */
+#define NSA_SEL_ESTATIC      -5   /* nsa_sel_fwd_static: shape beyond the library's built-in scratch array    */
+
+/* Size of the device array nsa_sel_fwd_static keeps its partial results in (each GPU the library runs on holds one
+ * copy until the process ends). */
+#define NSA_SEL_STATIC_WS_BYTES (64u << 20)
 
 typedef struct {
   int32_t total_tokens;   /* sum of sequence lengths (N when nseq == 1)                                      */
@@ -110,6 +115,21 @@ int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
 int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const void* O,
                 const float* LSE, const void* dO, const int32_t* cu_seqlens, const void* index_ws,
                 size_t index_bytes, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
+
+/* nsa_sel_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as nsa_sel_fwd (bit for bit)
+ * minus ws / ws_bytes: the partial outputs and log-sum-exps live in a file-scope device array of the library of
+ * NSA_SEL_STATIC_WS_BYTES (64 MiB).  The call allocates and frees nothing.  The partial results of ONE KV head,
+ * total_tokens * (hq / hkv) * topk * 260 bytes (+ up to 512 bytes of alignment), must fit the array - e.g. 4032 tokens
+ * at g = 4, topk = 16 - otherwise NSA_SEL_ESTATIC is returned and nothing is enqueued; when several KV heads fit they
+ * share a pass, as with a capped ws.  The index workspace is still the caller's (it is an output the backward reads).
+ * Every call on a GPU uses that GPU's one array and leaves its partial rows behind; nothing needs clearing between
+ * calls, but two calls in flight on the same GPU at once (two streams, two threads) race on it and give wrong
+ * results: serialise them.  The first call on a device looks up the array's address (hipGetSymbolAddress) and must
+ * therefore be made outside graph capture; later calls only launch kernels. */
+int nsa_sel_fwd_static(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                       const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
+                       float* LSE, void* stream);
 
 /* The same forward in QUERY-OUTER loop order, the order of the original NSA kernel (Sec. 2.2, 3.1; App. C): one
  * wavefront per (token, KV head) walks the row's selected blocks with an online softmax, re-loading a K/V block for

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libnsa_sel.so")
 _lib = None
 
-SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_workspace_bytes_min", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd", "nsa_sel_fwd_query_outer", "nsa_sel_fwd_gated", "nsa_sel_bwd_gated", "nsa_sel_select_blocks",
+SYMBOLS = ["nsa_sel_workspace_bytes", "nsa_sel_workspace_bytes_min", "nsa_sel_build_index", "nsa_sel_index_view", "nsa_sel_fwd", "nsa_sel_bwd", "nsa_sel_fwd_static", "nsa_sel_fwd_query_outer", "nsa_sel_fwd_gated", "nsa_sel_bwd_gated", "nsa_sel_select_blocks",
            "nsa_sel_profile_enable", "nsa_sel_profile_select", "nsa_sel_profile_collect", "nsa_sel_calibration_copy", "nsa_sel_mfma_probe", "nsa_sel_strerror"]
 
 
@@ -39,6 +39,7 @@ def lib():
         L.nsa_sel_index_view.argtypes = [C.POINTER(Shape), vp] + [C.POINTER(vp)] * 4 + [C.POINTER(C.c_int32)]
         L.nsa_sel_fwd.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, sz, vp]
         L.nsa_sel_bwd.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, sz, vp]
+        L.nsa_sel_fwd_static.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp]
         L.nsa_sel_fwd_query_outer.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, vp, vp, vp]
         L.nsa_sel_fwd_gated.argtypes = [C.POINTER(Shape), vp, vp, vp, i32p, i32p, C.c_int, vp, sz, vp, vp, vp, vp, vp, vp, sz, vp]
         L.nsa_sel_bwd_gated.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, vp, i32p, vp, sz, vp, vp, vp, vp, vp, sz, vp]
@@ -177,6 +178,17 @@ def nsa_sel_fwd(shape, q, k, v, idx, cu, rebuild_index, index_ws, o, lse, ws):
         _check(lib().nsa_sel_fwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu), int(rebuild_index),
                                  _ptr(index_ws), _nbytes(index_ws), _ptr(o), _ptr(lse), _ptr(ws), _nbytes(ws),
                                  _stream(dev)), "nsa_sel_fwd")
+
+
+def nsa_sel_fwd_static(shape, q, k, v, idx, cu, rebuild_index, index_ws, o, lse):
+    """nsa_sel_fwd with the partial buffers in the library's own device array (no workspace argument)."""
+    dev = index_ws.device
+    expect_attention_args(shape, dev, q=q, k=k, v=v, idx=idx, cu=cu, o=o, lse=lse, need_idx=bool(rebuild_index))
+    expect_workspace("index_ws", index_ws, workspace_bytes(shape)[2], dev)
+    with torch.cuda.device(dev):
+        _check(lib().nsa_sel_fwd_static(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(idx), _ptr(cu),
+                                        int(rebuild_index), _ptr(index_ws), _nbytes(index_ws), _ptr(o), _ptr(lse),
+                                        _stream(dev)), "nsa_sel_fwd_static")
 
 
 def nsa_sel_bwd(shape, q, k, v, o, lse, do, cu, index_ws, dq, dk, dv, ws):
@@ -324,6 +336,15 @@ class SelAttention:
         o = torch.empty(s.total_tokens, s.hq, 128, dtype=torch.bfloat16, device=self.device) if out is None else out
         l = torch.empty(s.total_tokens, s.hq, dtype=torch.float32, device=self.device) if lse is None else lse
         nsa_sel_fwd(s, q, k, v, idx, cu, rebuild_index, self.index_ws, o, l, self.fwd_ws)
+        return o, l
+
+    def forward_static(self, q, k, v, idx, cu=None, rebuild_index=True, out=None, lse=None):
+        """(O, LSE) by nsa_sel_fwd_static: the forward that keeps its partial results in the library's own device
+        array instead of this object's workspace (small shapes only)."""
+        s = self.shape
+        o = torch.empty(s.total_tokens, s.hq, 128, dtype=torch.bfloat16, device=self.device) if out is None else out
+        l = torch.empty(s.total_tokens, s.hq, dtype=torch.float32, device=self.device) if lse is None else lse
+        nsa_sel_fwd_static(s, q, k, v, idx, cu, rebuild_index, self.index_ws, o, l)
         return o, l
 
     def backward(self, q, k, v, o, lse, do, cu=None, out=None):

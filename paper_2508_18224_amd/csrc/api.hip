@@ -166,17 +166,26 @@ int nsa_sel_index_view(const nsa_sel_shape* shape, const void* index_ws, const i
   return NSA_SEL_OK;
 }
 
+// Pointer checks of the forward entry points (everything but the workspace).
+static int check_fwd_pointers(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V,
+                              const int32_t* idx, const int32_t* cu_seqlens, int rebuild_index, const void* index_ws,
+                              const void* O, const float* LSE) {
+  if (!Q || !K || !V || !index_ws || !O || !LSE) return NSA_SEL_EINVAL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(index_ws)) return NSA_SEL_EINVAL;
+  if (rebuild_index && !idx) return NSA_SEL_EINVAL;
+  if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
+  return NSA_SEL_OK;
+}
+
 static int fwd_impl(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
                     const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
                     float* LSE, const GateArgs& G, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (shape->total_tokens == 0) return NSA_SEL_OK;  // nothing to do: zero-sized tensors may have no address
-  if (!Q || !K || !V || !index_ws || !O || !LSE || !ws) return NSA_SEL_EINVAL;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(ws) || !aligned16(index_ws))
-    return NSA_SEL_EINVAL;
-  if (rebuild_index && !idx) return NSA_SEL_EINVAL;
-  if (!cu_seqlens && shape->nseq != 1) return NSA_SEL_EINVAL;
+  rc = check_fwd_pointers(shape, Q, K, V, idx, cu_seqlens, rebuild_index, index_ws, O, LSE);
+  if (rc) return rc;
+  if (!ws || !aligned16(ws)) return NSA_SEL_EINVAL;
   IndexLayout L = make_layout(shape);
   const int hpp = heads_that_fit(shape->hkv, ws_bytes, [&](int nj) { return fwd_ws_bytes(shape, nj); });
   if (index_bytes < L.total || hpp < 1) return NSA_SEL_EWORKSPACE;
@@ -196,6 +205,46 @@ int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
                 void* ws, size_t ws_bytes, void* stream) {
   return fwd_impl(shape, Q, K, V, idx, cu_seqlens, rebuild_index, index_ws, index_bytes, O, LSE,
                   GateArgs{nullptr, nullptr, nullptr, nullptr}, ws, ws_bytes, stream);
+}
+
+// ---- nsa_sel_fwd_static: the forward with its partial buffers in a device array of the library -------------------
+// In host code the array's name is only a stand-in for the symbol: the address kernels can use comes from
+// hipGetSymbolAddress, once per device (every GPU holds its own copy of the array at its own address).
+static __device__ __align__(256) unsigned char scratch[NSA_SEL_STATIC_WS_BYTES];
+static constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return NSA_SEL_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return NSA_SEL_EUNSUPPORTED;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return NSA_SEL_EHIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return NSA_SEL_OK;
+}
+
+int nsa_sel_fwd_static(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
+                       const int32_t* cu_seqlens, int rebuild_index, void* index_ws, size_t index_bytes, void* O,
+                       float* LSE, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (shape->total_tokens == 0) return NSA_SEL_OK;
+  // sizes first: a shape whose partial results of one KV head exceed the array is refused before anything else
+  if (fwd_ws_bytes(shape, 1) > (size_t)NSA_SEL_STATIC_WS_BYTES) return NSA_SEL_ESTATIC;
+  rc = check_fwd_pointers(shape, Q, K, V, idx, cu_seqlens, rebuild_index, index_ws, O, LSE);
+  if (rc) return rc;
+  if (index_bytes < make_layout(shape).total) return NSA_SEL_EWORKSPACE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  // Nothing in the array has to start at zero: the merge reads exactly the partial rows the main kernel of the same
+  // call wrote (those of kept selections), whatever an earlier call left behind.
+  return fwd_impl(shape, Q, K, V, idx, cu_seqlens, rebuild_index, index_ws, index_bytes, O, LSE,
+                  GateArgs{nullptr, nullptr, nullptr, nullptr}, ws, (size_t)NSA_SEL_STATIC_WS_BYTES, stream);
 }
 
 int nsa_sel_fwd_query_outer(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
@@ -276,6 +325,9 @@ const char* nsa_sel_strerror(int code) {
     case NSA_SEL_EUNSUPPORTED: return "unsupported shape (d must be 128, block 64 or 128, topk 1..32, size limits)";
     case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes / nsa_sel_workspace_bytes_min)";
     case NSA_SEL_EHIP: return "HIP runtime error at launch";
+    case NSA_SEL_ESTATIC:
+      return "shape too large for nsa_sel_fwd_static: the partial results of one KV head (total_tokens * g * topk * "
+             "260 bytes) exceed NSA_SEL_STATIC_WS_BYTES; use nsa_sel_fwd with a caller-owned workspace";
     default: return "unknown nsa_sel error code";
   }
 }

@@ -141,3 +141,16 @@ def test_gated_forward_rejects_aliasing_of_the_ungated_output():
     # O_out == O and O_acc == O are argument errors, found on the host before any launch
     assert L.nsa_sel_fwd_gated(ctypes.byref(ok), a, a, a, a, None, 0, a, big, b, a, a, None, b, a, big, None) == -1
     assert L.nsa_sel_fwd_gated(ctypes.byref(ok), a, a, a, a, None, 0, a, big, b, a, a, b, c, a, big, None) == -1
+
+
+def test_static_forward_refuses_large_shapes_before_any_gpu_call():
+    nsa, L = _lib()
+    vp = ctypes.c_void_p
+    a = vp(4096)
+    fits = nsa.Shape(4032, 1, 32, 8, 128, 64, 16, 1, 0.0, 0)       # one KV head: 4032 * 4 * 16 * 260 B < 64 MiB
+    big = nsa.Shape(4096, 1, 32, 8, 128, 64, 16, 1, 0.0, 0)
+    assert nsa.workspace_bytes_min(fits)[0] <= 64 << 20 < nsa.workspace_bytes_min(big)[0]
+    assert L.nsa_sel_fwd_static(ctypes.byref(big), a, a, a, a, None, 1, a, 1 << 40, a, a, None) == -5
+    assert b"nsa_sel_fwd_static" in L.nsa_sel_strerror(-5)
+    assert L.nsa_sel_fwd_static(ctypes.byref(fits), None, a, a, a, None, 1, a, 1 << 40, a, a, None) == -1
+    assert L.nsa_sel_fwd_static(ctypes.byref(fits), a, a, a, a, None, 1, a, 16, a, a, None) == -3
