@@ -303,7 +303,7 @@ def main():
     f, b = effective_flops(T, w.hq, w.topk, block=w.block)
     for name, avg in sorted(per_kernel.items(), key=lambda kv: -kv[1]):
         print(f"[bench] {name:16s} {avg:9.3f} ms/launch", file=sys.stderr)
-    fwd_ms = sum(per_kernel.get(n, 0.0) for n in ("fwd_main", "fwd_merge"))
+    fwd_ms = sum(per_kernel.get(n, 0.0) for n in ("fwd_main", "fwd_dense", "fwd_merge"))
     bwd_ms = sum(per_kernel.get(n, 0.0) for n in ("bwd_delta", "bwd_main", "bwd_dq_reduce", "bwd_dkv_reduce"))
     idx_ms = sum(vv for n, vv in per_kernel.items() if n.startswith("index_"))
     # algorithmic work of the dominant kernel: the MFMA contractions it performs (forward main: QK^T and PV,
@@ -346,7 +346,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: N={T}, hq={w.hq}, hkv={w.hkv}, g={w.g}, topk={w.topk}, block={w.block}, "
                                f"d=128, causal, seed {w.seed}",
-                   "step": "index inversion + forward (main, merge) + backward (delta, main, dQ reduce, dK/dV reduce)",
+                   "step": "index inversion + forward (main, dense, merge) + backward (delta, main, dQ reduce, dK/dV reduce)",
                    "workspace_GB": {"fwd": attn.fwd_ws.numel() / 1e9, "bwd": attn.bwd_ws.numel() / 1e9,
                                     "index": attn.index_ws.numel() / 1e9}},
         "frac_of_bf16_mfma_peak": (f + b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

@@ -22,7 +22,8 @@ class NsaSelError(RuntimeError):
 class Shape(C.Structure):
     _fields_ = [("total_tokens", C.c_int32), ("nseq", C.c_int32), ("hq", C.c_int32), ("hkv", C.c_int32),
                 ("d", C.c_int32), ("block", C.c_int32), ("topk", C.c_int32), ("causal", C.c_int32),
-                ("scale", C.c_float), ("max_seqlen", C.c_int32), ("window", C.c_int32), ("unit", C.c_int32)]
+                ("scale", C.c_float), ("max_seqlen", C.c_int32), ("window", C.c_int32), ("unit", C.c_int32),
+                ("dense", C.c_int32)]
 
 
 def lib():
@@ -289,10 +290,11 @@ class SelAttention:
     """Owns the workspaces for one shape and calls the library (buffers are torch uint8 tensors)."""
 
     def __init__(self, total_tokens, hq, hkv, topk, *, nseq=1, causal=True, scale=0.0, device="cuda:0", bwd=True,
-                 block=64, ws_cap_bytes=None, window=0, unit=0):
+                 block=64, ws_cap_bytes=None, window=0, unit=0, dense=True):
         """ws_cap_bytes caps each of the forward / backward workspaces (never below the library's minimum);
         the library then works through the KV heads in as many passes as needed."""
-        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0, int(window), int(unit))
+        self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0, int(window),
+                           int(unit), 0 if dense else -1)
         fb, bb, ib = workspace_bytes(self.shape)
         if ws_cap_bytes is not None:
             fmin, bmin = workspace_bytes_min(self.shape)
@@ -401,6 +403,16 @@ class SelAttention:
                                            _stream(self.device)), "nsa_sel_bwd_gated")
         return dq, dk, dv, dgate
 
+    def dense_entries(self):
+        """Boolean host array over the list entries (in list order): True where the forward routes the entry's
+        (query tile, KV block) pair through the dense path (the sign bit of the entry's column)."""
+        (o_cnt, o_off, o_qe, o_vm), bcap = index_view(self.shape, self.index_ws)
+        nl = self.shape.hkv * bcap
+        raw = self.index_ws
+        npairs = int(raw[o_off + 4 * nl:o_off + 4 * nl + 4].view(torch.int32).item())
+        qent = raw[o_qe:o_qe + 8 * npairs].view(torch.int32).cpu().numpy().reshape(npairs, 2)
+        return qent[:, 1] < 0
+
     def index_arrays(self):
         """Host copies of (cnt [hkv, b_cap], off, qlist, qslot, vmask [T, hkv]) for inspection."""
         (o_cnt, o_off, o_qe, o_vm), bcap = index_view(self.shape, self.index_ws)
@@ -413,5 +425,7 @@ class SelAttention:
         off = ints(o_off, nl + 1)
         npairs = int(off[-1])
         qent = ints(o_qe, 2 * npairs).reshape(npairs, 2)
-        return cnt, off, qent[:, 0].copy(), qent[:, 1].copy(), ints(o_vm, s.total_tokens * s.hkv).reshape(
+        # the sign bit of an entry's column flags a dense (tile, block) pair (the forward's routing, not part of the
+        # inversion result)
+        return cnt, off, qent[:, 0].copy(), (qent[:, 1] & 0x7FFFFFFF).copy(), ints(o_vm, s.total_tokens * s.hkv).reshape(
             s.total_tokens, s.hkv).view("uint32"), bcap

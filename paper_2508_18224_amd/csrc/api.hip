@@ -17,6 +17,7 @@ static int check_shape(const nsa_sel_shape* s) {
   if (g < 1 || g > 8) return NSA_SEL_EINVAL;
   if (s->window < 0 || (s->window > 0 && !s->causal)) return NSA_SEL_EINVAL;
   if (s->unit != 0 && (s->unit < kMinUnit || s->unit > kMaxUnit || (s->unit & (s->unit - 1)) != 0)) return NSA_SEL_EINVAL;
+  if (s->dense != 0 && s->dense != -1) return NSA_SEL_EINVAL;
   if (s->d != kD || (s->block != kBlock && s->block != 2 * kBlock)) return NSA_SEL_EUNSUPPORTED;
   if (s->topk < 1 || s->topk > kMaxTopk) return NSA_SEL_EUNSUPPORTED;
   if (s->nseq > (1 << 20)) return NSA_SEL_EUNSUPPORTED;
@@ -48,6 +49,8 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.p_max = (int64_t)s->total_tokens * s->hkv * L.topk;
   L.unit = s->unit != 0 ? s->unit : work_unit_entries(L.p_max);
   L.units_max = (int32_t)units_bound(L.hkv, L.b_cap, L.T, L.topk, L.unit);
+  L.dense = s->dense == 0 ? 1 : 0;
+  L.t_cap = s->total_tokens / kTileTokens + s->nseq;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };
   L.hdr = take(64);
@@ -64,6 +67,13 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   L.u_list = take(4 * (size_t)(L.units_max + 1));
   L.u_start = take(4 * (size_t)(L.units_max + 1));
   L.scan_tmp = take(4 * (size_t)index_scan_tmp_ints(L.n_lists));
+  L.tile_base = take(4 * (size_t)(L.nseq + 1));
+  L.tile_tok0 = take(4 * (size_t)L.t_cap);
+  L.tile_len = take(4 * (size_t)L.t_cap);
+  L.dmask = take(4 * ((size_t)L.T * L.hkv + 1));
+  L.d_cnt = take(4 * (size_t)L.t_cap * L.hkv);
+  L.d_piece = take(8 * (size_t)L.t_cap * L.hkv * kDenseMax);
+  L.d_mask = take(8 * (size_t)L.t_cap * L.hkv * kDenseMax);
   L.total = o;
   return L;
 }
@@ -81,6 +91,8 @@ static Problem make_problem(const nsa_sel_shape* s, const IndexLayout& L) {
   P.b_cap = L.b_cap;
   P.bk = L.bk;
   P.unit = L.unit;
+  P.dense = L.dense;
+  P.t_cap = L.t_cap;
   P.g_magic = P.g == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint64_t)P.g + 1);
   P.j0 = 0;
   P.nj = s->hkv;
@@ -94,9 +106,14 @@ static size_t partial_rows(const nsa_sel_shape* s, int nj) {
 }
 
 // Workspaces that hold the partial results of nj KV heads at once (nj = hkv: everything in one pass).
+// One more row per (token, head of the pass): the dense path's partial output and log-sum-exp.
+static size_t dense_rows(const nsa_sel_shape* s, int nj) {
+  return s->dense == 0 ? (size_t)s->total_tokens * nj * (s->hq / s->hkv) : 0;
+}
+
 static size_t fwd_ws_bytes(const nsa_sel_shape* s, int nj) {
-  const size_t rows = partial_rows(s, nj);
-  return align256(rows * kD * 2) + align256(rows * 4);
+  const size_t rows = partial_rows(s, nj), drows = dense_rows(s, nj);
+  return align256(rows * kD * 2) + align256(rows * 4) + align256(drows * kD * 2) + align256(drows * 4);
 }
 
 static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L, int nj) {
@@ -194,10 +211,15 @@ static int fwd_impl(const nsa_sel_shape* shape, const void* Q, const void* K, co
   if (rebuild_index && launch_build_index(L, idx, cu_seqlens, index_ws, st) != hipSuccess) return NSA_SEL_EHIP;
   Problem P = make_problem(shape, L);
   const size_t rows = partial_rows(shape, hpp);
-  void* opart = ws;
-  float* lse_part = (float*)((char*)ws + align256(rows * kD * 2));
-  return launch_fwd(P, L, hpp, Q, K, V, index_ws, opart, lse_part, O, LSE, G, st) == hipSuccess ? NSA_SEL_OK
-                                                                                                 : NSA_SEL_EHIP;
+  const size_t drows = dense_rows(shape, hpp);
+  char* w = (char*)ws;
+  void* opart = w;
+  float* lse_part = (float*)(w + align256(rows * kD * 2));
+  void* odense = (char*)lse_part + align256(rows * 4);
+  float* lse_dense = (float*)((char*)odense + align256(drows * kD * 2));
+  return launch_fwd(P, L, hpp, Q, K, V, index_ws, opart, lse_part, odense, lse_dense, O, LSE, G, st) == hipSuccess
+             ? NSA_SEL_OK
+             : NSA_SEL_EHIP;
 }
 
 int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
@@ -326,8 +348,8 @@ const char* nsa_sel_strerror(int code) {
     case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes / nsa_sel_workspace_bytes_min)";
     case NSA_SEL_EHIP: return "HIP runtime error at launch";
     case NSA_SEL_ESTATIC:
-      return "shape too large for nsa_sel_fwd_static: the partial results of one KV head (total_tokens * g * topk * "
-             "260 bytes) exceed NSA_SEL_STATIC_WS_BYTES; use nsa_sel_fwd with a caller-owned workspace";
+      return "shape too large for nsa_sel_fwd_static: the partial results of one KV head (total_tokens * g * "
+             "(topk + 1) * 260 bytes) exceed NSA_SEL_STATIC_WS_BYTES; use nsa_sel_fwd with a caller-owned workspace";
     default: return "unknown nsa_sel error code";
   }
 }

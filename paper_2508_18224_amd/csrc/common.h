@@ -18,6 +18,9 @@ constexpr int kMaxUnit = 2048;     // most list entries of one work unit (the si
 constexpr int kMinUnit = 256;
 constexpr int kMaxTopk = 32;
 constexpr int kSlotBatch = 4;      // slots of a row the two reduction kernels gather at a time
+constexpr int kTileTokens = 64;    // query tokens of a tile of the dense forward path (whatever B_K is)
+constexpr int kDenseMax = 32;      // most 64-key pieces one (query tile, kv head) routes through the dense path
+constexpr int kDenseHash = 1024;   // per-wavefront counters of the detection pass (block id modulo this)
 
 // Host-computed description of the index workspace (byte offsets from its base, all 256-aligned).
 struct IndexLayout {
@@ -31,13 +34,16 @@ struct IndexLayout {
   int64_t p_max;        // T * hkv * topk
   int32_t unit;         // list entries per work unit of the attention kernels (see work_unit_entries)
   int32_t units_max;    // upper bound of the number of work units
+  int32_t dense;        // 1: (query tile, KV block) pairs most of the tile's tokens keep go through the dense path
+  int32_t t_cap;        // query tiles of kTileTokens tokens: T / kTileTokens + nseq (>= real number of tiles)
   size_t hdr, blk_base, blk_tok0, blk_len, chunk_off, cnt, off, qent, vmask, slotpos;
   size_t u_nu, u_list, u_start, scan_tmp;
+  size_t tile_base, tile_tok0, tile_len, dmask, d_cnt, d_piece, d_mask;
   size_t total;
 };
 
 // hdr words
-enum { HDR_BTOT = 0, HDR_NPAIRS = 1, HDR_UNITS = 2 };
+enum { HDR_BTOT = 0, HDR_NPAIRS = 1, HDR_UNITS = 2, HDR_NTILES = 3 };
 
 struct IndexPtrs {
   int32_t* hdr;
@@ -53,6 +59,14 @@ struct IndexPtrs {
   // work units (shared by forward and backward): scanned units per list, and per unit its list and first entry
   int32_t *u_nu, *u_list, *u_start;
   int32_t* scan_tmp;
+  // dense forward path: query tiles (kTileTokens consecutive tokens of one sequence) and, per (tile, kv head), the
+  // 64-key pieces of the KV blocks at least half of the tile's tokens keep, each with the 64-bit mask of the tokens
+  // that keep its block
+  int32_t *tile_base, *tile_tok0, *tile_len;
+  uint32_t* dmask;     // [T, hkv]: columns of idx the dense path takes over (a subset of vmask)
+  int32_t* d_cnt;      // [t_cap, hkv]
+  int2* d_piece;       // [t_cap, hkv, kDenseMax] (first key token, number of keys <= 64)
+  unsigned long long* d_mask;  // [t_cap, hkv, kDenseMax]
 };
 
 inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
@@ -72,6 +86,13 @@ inline IndexPtrs index_ptrs(const IndexLayout& L, void* base) {
   r.u_list = (int32_t*)(p + L.u_list);
   r.u_start = (int32_t*)(p + L.u_start);
   r.scan_tmp = (int32_t*)(p + L.scan_tmp);
+  r.tile_base = (int32_t*)(p + L.tile_base);
+  r.tile_tok0 = (int32_t*)(p + L.tile_tok0);
+  r.tile_len = (int32_t*)(p + L.tile_len);
+  r.dmask = (uint32_t*)(p + L.dmask);
+  r.d_cnt = (int32_t*)(p + L.d_cnt);
+  r.d_piece = (int2*)(p + L.d_piece);
+  r.d_mask = (unsigned long long*)(p + L.d_mask);
   return r;
 }
 
@@ -81,6 +102,8 @@ struct Problem {
   int32_t window;    // 0, or: key u is visible to token t only if u > t - window
   uint32_t g_magic;  // floor(2^32 / g) + 1, or 0 when g == 1: row / g as one multiply-high (see div_g)
   int32_t unit;    // list entries per work unit
+  int32_t dense;   // 1: the dense forward path is on (the index carries dense flags and tables)
+  int32_t t_cap;   // stride of the per-(tile, kv head) dense tables
   int32_t j0, nj;  // KV heads [j0, j0 + nj) handled by this launch (all of them unless the workspace is capped)
   float scale;
 };
@@ -104,7 +127,7 @@ inline int64_t units_bound(int nj, int b_cap, int T, int topk, int unit) {
 enum KernelId {
   KID_INDEX_PREP = 0, KID_INDEX_CHUNK_PREFIX, KID_INDEX_HIST, KID_INDEX_SCAN, KID_INDEX_SCATTER, KID_INDEX_FINALIZE,
   KID_INDEX_UNITS, KID_FWD_MAIN, KID_FWD_MERGE, KID_BWD_DELTA, KID_BWD_MAIN, KID_BWD_DQ_REDUCE, KID_BWD_DKV_REDUCE,
-  KID_SELECT_BLOCKS, KID_FWD_QUERY_OUTER, KID_COUNT
+  KID_SELECT_BLOCKS, KID_FWD_QUERY_OUTER, KID_INDEX_DENSE, KID_FWD_DENSE, KID_COUNT
 };
 // Records a HIP event on `st` at construction and destruction when profiling is on; does nothing otherwise.
 struct ProfScope {
@@ -139,9 +162,10 @@ struct GateArgs {
 hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
                               hipStream_t st);
 // heads_per_pass: KV heads whose partial results the workspace can hold at once (1 .. hkv)
+// odense / lse_dense: one partial row per (token, head of the pass) from the dense path (unused when it is off)
 hipError_t launch_fwd(const Problem& P, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
-                      const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
-                      const GateArgs& G, hipStream_t st);
+                      const void* V, const void* index_ws, void* opart, float* lse_part, void* odense,
+                      float* lse_dense, void* O, float* LSE, const GateArgs& G, hipStream_t st);
 // the same forward in query-outer loop order (no workspaces, no index): see qouter.hip
 hipError_t launch_fwd_query_outer(const Problem& P, const void* Q, const void* K, const void* V, const int32_t* idx,
                                   const int32_t* cu, void* O, float* LSE, hipStream_t st);

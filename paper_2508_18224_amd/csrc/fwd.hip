@@ -42,15 +42,70 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+
+// Tokens of a work unit's list entries that take the gather route, compacted into `ent`, with each one's index
+// inside the unit in `epos` (its partial rows live at the entry's list position, dense entries leave holes there).
+// Entries of dense (tile, block) pairs carry the sign bit in their column (see k_scatter) and are skipped.  Block-wide:
+// every thread takes entries i0 + tid of up to kMaxUnit / kThreads rounds, a round's survivors of a wavefront are
+// ranked by ballot, and the (round, wavefront) counts are prefix-summed through `cnts`.  Returns the number of
+// entries kept; ends with a barrier.
+template <int kThreads>
+__device__ __forceinline__ int load_sparse_entries(const int2* __restrict__ qent, int e0, int ne, int32_t* ent,
+                                                   uint16_t* epos, int32_t* cnts) {
+  constexpr int kRounds = kMaxUnit / kThreads, kWaves = kThreads / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int tok[kRounds];
+  unsigned long long keep[kRounds];
+#pragma unroll
+  for (int r = 0; r < kRounds; ++r) {
+    const int i = r * kThreads + tid;
+    int2 e = make_int2(0, -1);
+    if (i < ne) e = qent[e0 + i];
+    tok[r] = e.x;
+    keep[r] = __builtin_amdgcn_ballot_w64(e.y >= 0);
+    if (lane == 0) cnts[r * kWaves + wave] = __popcll(keep[r]);
+  }
+  __syncthreads();
+  int run = 0;
+#pragma unroll
+  for (int r = 0; r < kRounds; ++r) {
+    int before = 0;  // survivors of earlier rounds and of the lower wavefronts of this round
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      if (w == wave) before = run;
+      run += cnts[r * kWaves + w];
+    }
+    if ((keep[r] >> lane) & 1ull) {
+      const int pos = before + __popcll(keep[r] & ((1ull << lane) - 1ull));
+      ent[pos] = tok[r];
+      epos[pos] = (uint16_t)(r * kThreads + tid);
+    }
+  }
+  __syncthreads();
+  return run;
+}
+
+// LDS of k_fwd_main (dynamic: 66 KB, two workgroups per CU)
+constexpr int kF64Vt = 0;
+constexpr int kF64Tiles = kF64Vt + kD * kVtStride * 2;
+constexpr int kF64Ent = kF64Tiles + 4 * 32 * kTileStride * 2;
+constexpr int kF64Epos = kF64Ent + kMaxUnit * 4;
+constexpr int kF64Cnts = kF64Epos + kMaxUnit * 2;
+constexpr int kF64Rowpos = kF64Cnts + (kMaxUnit / 64) * 4;
+constexpr int kF64Bytes = kF64Rowpos + 4 * 32 * 8;
+static_assert(2 * kF64Bytes <= 160 * 1024, "two workgroups of the 64-key forward must fit one CU's LDS");
+
 __global__ void __launch_bounds__(256, 2)  // two workgroups per CU: 256 registers per wavefront
 k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
            const int32_t* __restrict__ nu_scan, const int32_t* __restrict__ u_list, const int32_t* __restrict__ u_start,
            const int32_t* __restrict__ off, const int32_t* __restrict__ blk_tok0, const int32_t* __restrict__ blk_len,
            const int2* __restrict__ qent, bf16_t* __restrict__ opart,
            float* __restrict__ lse_part) {
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[kD * kVtStride];
-  __shared__ __attribute__((aligned(16))) bf16_t tiles[4][32 * kTileStride];
-  __shared__ int32_t ent[kMaxUnit];  // tokens of the unit's list entries
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* Vt = reinterpret_cast<bf16_t*>(smem + kF64Vt);
+  int32_t* ent = reinterpret_cast<int32_t*>(smem + kF64Ent);     // tokens of the unit's list entries that take this route
+  uint16_t* epos = reinterpret_cast<uint16_t*>(smem + kF64Epos);  // and their index inside the unit
+  int32_t* cnts = reinterpret_cast<int32_t*>(smem + kF64Cnts);
   // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
   const int u = nu_scan[P.j0 * P.b_cap] + blockIdx.x;
   if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
@@ -59,11 +114,14 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int gb = L - j * P.b_cap;
   const int e0 = u_start[u];
   const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
-  const int ne = min(P.unit, off[L + 1] - e0);
+  const int ne_all = min(P.unit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
   const int crow = lane >> 4, cchunk = (lane & 15) * 8;  // coalesced layout: 16 lanes per row, 4 rows per access
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  // entries of dense (tile, block) pairs are the dense kernel's: a unit made of them only (the sink block's) ends here
+  const int ne = load_sparse_entries<256>(qent, e0, ne_all, ent, epos, cnts);
+  if (ne == 0) return;
 
   {  // V_i -> LDS, transposed and key-permuted
     const int key = tid >> 2, d0 = (tid & 3) * 32, pos = key_pos(key);
@@ -83,7 +141,6 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
     for (int s = 0; s < 8; ++s) kf[mb][s] = key < blen ? *reinterpret_cast<const bf16x8*>(src + 16 * s) : zero8;
   }
-  for (int i = tid; i < ne; i += 256) ent[i] = qent[e0 + i].x;
   __syncthreads();
   const bf16_t* vbase = &Vt[col * kVtStride + 8 * qh];  // this lane's V^T fragments: + 32 db rows, + 16 sp keys
 
@@ -91,7 +148,9 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int n_tiles = (rows_total + 31) >> 5;
   if (wave >= n_tiles) return;  // no block-wide barrier below this point
   const float c2 = P.scale * 1.4426950408889634f;  // scores in the log2 domain
-  bf16_t* tile_lds = tiles[wave];
+  bf16_t* tile_lds = reinterpret_cast<bf16_t*>(smem + kF64Tiles) + wave * 32 * kTileStride;
+  // per wavefront: the partial-buffer row of each of the tile's 32 rows
+  int64_t* rowpos = reinterpret_cast<int64_t*>(smem + kF64Rowpos) + 32 * wave;
   const int hbase = j * P.g;
 
   // gather the 32 rows of Q of a tile in coalesced form (a row = 16 lanes x 16 bytes, 4 rows per access)
@@ -133,7 +192,8 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     // keys [0, lim) of the block are visible to this row
     const int r = tile * 32 + col;
     const bool valid = r < rows_total;
-    const int t = valid ? ent[div_g(r, P.g, P.g_magic)] : -1;
+    const int ecol = div_g(min(r, rows_total - 1), P.g, P.g_magic);
+    const int t = valid ? ent[ecol] : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
     const int lo = P.window > 0 ? t - P.window + 1 - tok0 : 0;  // with a window, keys before lo are hidden (<= 0: none)
@@ -200,17 +260,20 @@ k_fwd_main(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
         *reinterpret_cast<uint2*>(&tile_lds[col * kTileStride + 32 * db + 8 * a + 4 * qh]) = w;
       }
+    // this row's place in the partial buffers, published for the lanes that store it
+    const int64_t prow = (int64_t)(e0 - pos0 + epos[ecol]) * P.g + (r - ecol * P.g);
+    if (qh == 0) rowpos[col] = prow;
     wave_sync();
-    // partial rows live at the list position of their entry: a tile's 32 rows are one contiguous 8 KB run
-    const size_t prow0 = (size_t)(e0 - pos0) * P.g + (size_t)tile * 32;
+    // partial rows live at the list position of their entry (row = position * g + head): consecutive entries of the
+    // unit give one contiguous run, broken only where a dense pair's entries were left out
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = 4 * i + crow;
       if (tile * 32 + row < rows_total)
-        store_streaming(opart + (prow0 + row) * kD + cchunk,
+        store_streaming(opart + (size_t)rowpos[row] * kD + cchunk,
                         *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]));
     }
-    if (valid && qh == 0) lse_part[prow0 + col] = (mc + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    if (valid && qh == 0) lse_part[prow] = (mc + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
     wave_sync();
   };
 
@@ -230,7 +293,10 @@ constexpr int kF128K = 0;
 constexpr int kF128V = kF128K + 128 * kPitch128 * 2;
 constexpr int kF128Tiles = kF128V + 128 * kPitch128 * 2;
 constexpr int kF128Ent = kF128Tiles + kWaves128 * 32 * kTileStride * 2;
-constexpr int kF128Bytes = kF128Ent + kMaxUnit * 4;
+constexpr int kF128Epos = kF128Ent + kMaxUnit * 4;
+constexpr int kF128Cnts = kF128Epos + kMaxUnit * 2;
+constexpr int kF128Rowpos = kF128Cnts + (kMaxUnit / 64) * 4;
+constexpr int kF128Bytes = kF128Rowpos + kWaves128 * 32 * 8;
 static_assert(kF128Bytes <= 160 * 1024, "forward 128-key tile set must fit the CU's LDS");
 
 // ds_read_b64_tr_b16: every lane passes the address of 8 bytes (four 16-bit elements); within each group of 16
@@ -253,6 +319,9 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kF128K);
   bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kF128V);
   int32_t* ent = reinterpret_cast<int32_t*>(smem + kF128Ent);
+  uint16_t* epos = reinterpret_cast<uint16_t*>(smem + kF128Epos);
+  int32_t* cnts = reinterpret_cast<int32_t*>(smem + kF128Cnts);
+  int64_t* rowpos = reinterpret_cast<int64_t*>(smem + kF128Rowpos) + 32 * (threadIdx.x >> 6);
   // units of this pass's KV heads [j0, j0 + nj); nu_scan is the exclusive scan of units per list
   const int u = nu_scan[P.j0 * P.b_cap] + blockIdx.x;
   if (u >= nu_scan[(P.j0 + P.nj) * P.b_cap]) return;
@@ -261,13 +330,16 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
   const int gb = L - j * P.b_cap;
   const int e0 = u_start[u];
   const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
-  const int ne = min(P.unit, off[L + 1] - e0);
+  const int ne_all = min(P.unit, off[L + 1] - e0);
   const int tok0 = blk_tok0[gb], blen = blk_len[gb];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int col = lane & 31, qh = lane >> 5;                 // not const: see the top of the tile loop
   int crow = lane >> 4, cchunk = (lane & 15) * 8;
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   bf16_t* tile_lds = reinterpret_cast<bf16_t*>(smem + kF128Tiles) + wave * 32 * kTileStride;
+  // entries of dense (tile, block) pairs belong to the dense kernel (see load_sparse_entries)
+  const int ne = load_sparse_entries<64 * kWaves128>(qent, e0, ne_all, ent, epos, cnts);
+  if (ne == 0) return;
 
   {  // K_i, V_i -> LDS, row-major (rows past the end of a ragged block are zero)
     const int key = tid >> 2, d0 = (tid & 3) * 32;
@@ -280,7 +352,6 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
           key < blen ? *reinterpret_cast<const bf16x8*>(V + o + 8 * i) : zero8;
     }
   }
-  for (int i = tid; i < ne; i += 64 * kWaves128) ent[i] = qent[e0 + i].x;
   __syncthreads();
 
   const int rows_total = ne * P.g;
@@ -335,7 +406,8 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
 
     const int r = tile * 32 + col;
     const bool valid = r < rows_total;
-    const int t = valid ? ent[div_g(r, P.g, P.g_magic)] : -1;
+    const int ecol = div_g(min(r, rows_total - 1), P.g, P.g_magic);
+    const int t = valid ? ent[ecol] : -1;
     int lim = P.causal ? min(blen, t - tok0 + 1) : blen;
     if (!valid) lim = 0;
     const int lo = P.window > 0 ? t - P.window + 1 - tok0 : 0;  // with a window, keys before lo are hidden
@@ -399,17 +471,241 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
         w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
         *reinterpret_cast<uint2*>(&tile_lds[col * kTileStride + 32 * db + 8 * a + 4 * qh]) = w;
       }
+    // this row's place in the partial buffers, published for the lanes that store it
+    const int64_t prow = (int64_t)(e0 - pos0 + epos[ecol]) * P.g + (r - ecol * P.g);
+    if (qh == 0) rowpos[col] = prow;
     wave_sync();
-    const size_t prow0 = (size_t)(e0 - pos0) * P.g + (size_t)tile * 32;
+    // partial rows live at the list position of their entry (see k_fwd_main)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = 4 * i + crow;
       if (tile * 32 + row < rows_total)
-        store_streaming(opart + (prow0 + row) * kD + cchunk,
+        store_streaming(opart + (size_t)rowpos[row] * kD + cchunk,
                         *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]));
     }
-    if (valid && qh == 0) lse_part[prow0 + col] = (mc + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    if (valid && qh == 0) lse_part[prow] = (mc + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
     wave_sync();
+  }
+}
+
+
+// ---- dense (query-tile-outer) forward ------------------------------------------------------------------------------
+// The (query tile, KV block) pairs the index marked dense - blocks that at least half of the tile's 64 tokens keep:
+// the attention-sink block and the tokens' own and neighbouring blocks (App. E, the paragraph on the attention sink;
+// the whole band of the sliding-window term of Eq. (2)) - are contiguous token ranges on both sides, so they need no
+// gather and no partial row per slot: one workgroup takes 128 rows (row = (token of the tile, head of the group)) of
+// one (tile, kv head), keeps their Q fragments in registers and walks the tile's dense blocks, 64 keys at a time
+// (the index lists them as pieces) through LDS, with a running (max, sum) per row and the output accumulated in registers across the blocks.  What
+// leaves the kernel is ONE normalised partial row and log-sum-exp per (token, head), which the merge combines with
+// the rows of the gather route.  The 64-bit mask of a pair says which tokens of the tile keep the block; the others
+// see none of its keys.  S^T = K Q^T and O^T = V^T P^T as in the kernels above (K fragments are 16-byte LDS reads,
+// V^T fragments LDS transpose reads); the next 64 keys are fetched into registers while the current ones compute.
+constexpr int kDnPitch = 152;                                  // bf16 per LDS row of the K / V tiles
+constexpr int kDnK = 0;
+constexpr int kDnV = kDnK + 64 * kDnPitch * 2;
+constexpr int kDnTiles = kDnV + 64 * kDnPitch * 2;
+constexpr int kDnBytes = kDnTiles + 4 * 32 * kTileStride * 2;  // 73728: two workgroups per CU
+static_assert(2 * kDnBytes <= 160 * 1024, "two workgroups of the dense forward must fit one CU's LDS");
+
+__global__ void __launch_bounds__(256, 2)
+k_fwd_dense(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+            const int32_t* __restrict__ tile_tok0, const int32_t* __restrict__ tile_len,
+            const int32_t* __restrict__ d_cnt, const int2* __restrict__ d_piece,
+            const unsigned long long* __restrict__ d_mask, bf16_t* __restrict__ odense,
+            float* __restrict__ lse_dense) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kDnK);
+  bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kDnV);
+  const int chunks = (kTileTokens * P.g + 127) >> 7;  // 128-row chunks of a tile's rows
+  // Workgroups are handed to the chip's 8 XCDs (each with its own L2) round-robin by their index; the work is
+  // ordered kv head -> tile -> chunk, and every XCD takes one contiguous eighth of that order, so that the
+  // workgroups running side by side on an XCD share K / V pieces (neighbouring tiles of one head, the sink block).
+  const int total = P.nj * P.t_cap * chunks, per = (total + 7) >> 3;
+  const int lid = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (lid >= total) return;
+  const int chunk = lid % chunks, qt = (lid / chunks) % P.t_cap;
+  const int j = P.j0 + lid / (chunks * P.t_cap);
+  const size_t slot = (size_t)qt * P.hkv + j;
+  const int nd = d_cnt[slot];
+  const int tlen = tile_len[qt];
+  const int rows_total = tlen * P.g;
+  if (nd == 0 || chunk * 128 >= rows_total) return;  // nothing dense here: no row of this tile reads the dense buffers
+  const int ttok0 = tile_tok0[qt];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
+  const int crow = lane >> 4, cchunk = (lane & 15) * 8;
+  bf16_t* tile_lds = reinterpret_cast<bf16_t*>(smem + kDnTiles) + wave * 32 * kTileStride;
+  const int row0 = chunk * 128 + wave * 32;        // first row of this wavefront
+  const bool wave_on = row0 < rows_total;          // idle wavefronts still help to stage K / V
+  const int hbase = j * P.g;
+  const float c2 = P.scale * 1.4426950408889634f;
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+  // this wavefront's 32 rows of Q: coalesced loads -> wave tile -> B-operand fragments, kept for the whole tile
+  bf16x8 qf[8];
+  if (wave_on) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = min(row0 + 4 * i + crow, rows_total - 1);
+      const int e = div_g(r, P.g, P.g_magic);
+      const uint32_t grow = (uint32_t)(ttok0 + e) * (uint32_t)P.hq + (uint32_t)(hbase + (r - e * P.g));
+      *reinterpret_cast<u32x4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) =
+          *reinterpret_cast<const u32x4*>(Q + ((size_t)grow * kD + cchunk));
+    }
+    wave_sync();
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kTileStride + 16 * s + 8 * qh]);
+  }
+  const int r = row0 + col;                        // this lane's row
+  const bool valid = r < rows_total;
+  const int e_row = div_g(min(r, rows_total - 1), P.g, P.g_magic);
+  const int t = ttok0 + e_row;
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;            // running maximum (raw scores) and sum of the row
+
+  // staging of 64 keys: thread = (key, 32 channels), four 16-byte pieces of K and of V
+  const int skey = tid >> 2, sd0 = (tid & 3) * 32;
+  const int steps = nd;                            // one 64-key piece per step
+  u32x4 kreg[4], vreg[4];
+  auto fetch = [&](int step) {
+    const int2 piece = d_piece[slot * kDenseMax + step];  // (first key, number of keys)
+    const bool on = skey < piece.y;
+    const size_t o = ((size_t)(piece.x + (on ? skey : 0)) * P.hkv + j) * kD + sd0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      kreg[i] = *reinterpret_cast<const u32x4*>(K + o + 8 * i);
+      vreg[i] = *reinterpret_cast<const u32x4*>(V + o + 8 * i);
+      if (!on) {  // rows past the end of a ragged block are zero
+        kreg[i] = u32x4{0, 0, 0, 0};
+        vreg[i] = u32x4{0, 0, 0, 0};
+      }
+    }
+  };
+  const int grp = lane >> 4, sl = lane & 15;
+  const int tr_v = ((sl >> 2) + 4 * (grp >> 1)) * kDnPitch + 16 * (grp & 1) + 4 * (sl & 3);
+
+  fetch(0);
+  for (int step = 0; step < steps; ++step) {
+    __syncthreads();  // the previous piece is no longer read
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *reinterpret_cast<u32x4*>(&Ks[skey * kDnPitch + sd0 + 8 * i]) = kreg[i];
+      *reinterpret_cast<u32x4*>(&Vs[skey * kDnPitch + sd0 + 8 * i]) = vreg[i];
+    }
+    const int2 piece = d_piece[slot * kDenseMax + step];
+    const unsigned long long members = d_mask[slot * kDenseMax + step];
+    const int ktok0 = piece.x, klen = piece.y;                // first key of the piece and its number of keys
+    if (step + 1 < steps) fetch(step + 1);                    // flies during the compute
+    __syncthreads();  // K, V of the piece staged
+    if (!wave_on) continue;
+
+    f32x16 sacc[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sacc[mb][v] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Ks[(32 * mb + col) * kDnPitch + 16 * s + 8 * qh]);
+        sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[mb], 0, 0, 0);
+      }
+    // keys [lo, lim) of the piece are visible to this row: none if the token does not keep the block
+    int lim = P.causal ? min(klen, t - ktok0 + 1) : klen;
+    if (!valid || !((members >> e_row) & 1ull)) lim = 0;
+    const int lo = P.window > 0 ? t - P.window + 1 - ktok0 : 0;
+    float m = -INFINITY;
+    if (__builtin_amdgcn_ballot_w64(lim < 64 || lo > 0) == 0) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m = fmaxf(m, sacc[mb][v]);
+    } else {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
+          const float x = (key < lim && key >= lo) ? sacc[mb][v] : -INFINITY;
+          sacc[mb][v] = x;
+          m = fmaxf(m, x);
+        }
+    }
+    m = fmaxf(m, __shfl_xor(m, 32));
+    // online softmax: new running maximum, rescale of what has been accumulated
+    const float m_new = fmaxf(m_run, m);
+    const float mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
+    const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c2, -mc));  // exp2(-inf) = 0 on the first visible piece
+    m_run = m_new;
+    float l = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][v], c2, -mc));
+        sacc[mb][v] = p;
+        l += p;
+      }
+    l += __shfl_xor(l, 32);
+    l_run = l_run * alpha + l;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+
+    bf16x8 pf[4];
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp)
+#pragma unroll
+      for (int e2 = 0; e2 < 8; ++e2) pf[sp][e2] = (bf16_t)sacc[sp >> 1][8 * (sp & 1) + e2];
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const bf16x4 a0 = lds_read_tr_f(&Vs[16 * sp * kDnPitch + tr_v + 32 * db]);
+        const bf16x4 a1 = lds_read_tr_f(&Vs[(16 * sp + 8) * kDnPitch + tr_v + 32 * db]);
+        const bf16x8 vf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], oacc[db], 0, 0, 0);
+      }
+  }
+  if (!wave_on) return;
+
+  // one normalised partial row per (token, head) -> wave tile -> coalesced 256-byte row stores.  Rows are indexed
+  // (token, head within the pass's heads); a row no dense block of which the token keeps gets log-sum-exp -inf.
+  const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      uint2 w;
+      w.x = pack_bf16x2(oacc[db][4 * a + 0] * inv, oacc[db][4 * a + 1] * inv);
+      w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
+      *reinterpret_cast<uint2*>(&tile_lds[col * kTileStride + 32 * db + 8 * a + 4 * qh]) = w;
+    }
+  wave_sync();
+  const int hp = P.nj * P.g;                        // heads of the pass
+  const int hoff = (j - P.j0) * P.g;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = 4 * i + crow;
+    const int rr = row0 + row;
+    if (rr < rows_total) {
+      const int e = div_g(rr, P.g, P.g_magic);
+      const size_t drow = (size_t)(ttok0 + e) * hp + (size_t)(hoff + rr - e * P.g);
+      *reinterpret_cast<uint4*>(odense + drow * kD + cchunk) =
+          *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]);
+    }
+  }
+  if (valid && qh == 0) {
+    const float mcf = (m_run == -INFINITY) ? 0.f : m_run * c2;
+    lse_dense[(size_t)t * hp + (size_t)(hoff + r - e_row * P.g)] =
+        l_run > 0.f ? (mcf + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f : -INFINITY;
   }
 }
 
@@ -419,8 +715,9 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
 // result hide the gather latency better than long batches did (16 -> 4: 1.87 -> 1.80 ms at the headline shape).
 __global__ void __launch_bounds__(256)
 k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict__ lse_part,
-            const uint32_t* __restrict__ vmask, const int32_t* __restrict__ slotpos,
-            const int32_t* __restrict__ off, bf16_t* __restrict__ O,
+            const uint32_t* __restrict__ vmask, const uint32_t* __restrict__ dmask,
+            const int32_t* __restrict__ slotpos, const int32_t* __restrict__ off,
+            const bf16_t* __restrict__ odense, const float* __restrict__ lse_dense, bf16_t* __restrict__ O,
             float* __restrict__ LSE, const float* __restrict__ gate, const bf16_t* Oacc, bf16_t* Oout) {
   // rows of the pass: (token, head of the KV heads [j0, j0 + nj))
   const int hp = P.nj * P.g;
@@ -432,9 +729,12 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
   const int64_t row = (int64_t)t * P.hq + h;
   const int j = h / P.g, hh = h - j * P.g;
   const int pos0 = off[P.j0 * P.b_cap];
-  const uint32_t vm = vmask[(size_t)t * P.hkv + j];
+  const uint32_t vm_all = vmask[(size_t)t * P.hkv + j];
+  // columns the dense path took over have no partial row of their own: they arrive as one row per (token, head)
+  const uint32_t dm = P.dense ? dmask[(size_t)t * P.hkv + j] : 0u;
+  const uint32_t vm = vm_all & ~dm;
   bf16_t* orow = O + row * kD + 8 * sub;
-  if (vm == 0u) {
+  if (vm_all == 0u) {
     *reinterpret_cast<uint4*>(orow) = make_uint4(0, 0, 0, 0);
     if (sub == 0) LSE[row] = -INFINITY;
     if (gate != nullptr)  // nothing to add: the gated sum is what the other branches gave
@@ -445,6 +745,17 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
   const int32_t* sp = slotpos + ((size_t)t * P.hkv + j) * P.topk;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   float M = -INFINITY, Ls = 0.f;
+  if (dm != 0u) {  // the dense path's row starts the sum (its log-sum-exp is -inf if the token keeps none of the blocks)
+    const size_t drow = (size_t)t * hp + (size_t)(h - P.j0 * P.g);
+    const uint4 x = *reinterpret_cast<const uint4*>(odense + drow * kD + 8 * sub);
+    const float ls = lse_dense[drow];
+    if (ls > -INFINITY) {
+      M = ls;
+      Ls = 1.f;
+      acc[0] = bf16_lo(x.x); acc[1] = bf16_hi(x.x); acc[2] = bf16_lo(x.y); acc[3] = bf16_hi(x.y);
+      acc[4] = bf16_lo(x.z); acc[5] = bf16_hi(x.z); acc[6] = bf16_lo(x.w); acc[7] = bf16_hi(x.w);
+    }
+  }
   for (int m0 = 0; m0 < P.topk; m0 += kSlotBatch) {
     size_t pr[kSlotBatch];
     uint4 x[kSlotBatch];
@@ -504,12 +815,18 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
 }
 
 hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
-                      const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
-                      const GateArgs& G, hipStream_t st) {
+                      const void* V, const void* index_ws, void* opart, float* lse_part, void* odense,
+                      float* lse_dense, void* O, float* LSE, const GateArgs& G, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
-  if (P0.bk == 128) {
-    static std::atomic<uint64_t> ready;
-    hipError_t e = allow_dynamic_lds((const void*)k_fwd_main128, kF128Bytes, ready);
+  if (P0.dense) {
+    static std::atomic<uint64_t> ready_dense;
+    hipError_t e = allow_dynamic_lds((const void*)k_fwd_dense, kDnBytes, ready_dense);
+    if (e != hipSuccess) return e;
+  }
+  {
+    static std::atomic<uint64_t> ready[2];
+    hipError_t e = P0.bk == 128 ? allow_dynamic_lds((const void*)k_fwd_main128, kF128Bytes, ready[1])
+                                : allow_dynamic_lds((const void*)k_fwd_main, kF64Bytes, ready[0]);
     if (e != hipSuccess) return e;
   }
   // KV heads are processed heads_per_pass at a time; every pass reuses the same partial buffers (the lists of
@@ -527,15 +844,23 @@ hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
                          p.blk_len, p.qent, (bf16_t*)opart, lse_part);
     } else {
       ProfScope ps(KID_FWD_MAIN, st);
-      hipLaunchKernelGGL(k_fwd_main, dim3(units_max), dim3(256), 0, st, P, (const bf16_t*)Q, (const bf16_t*)K,
+      hipLaunchKernelGGL(k_fwd_main, dim3(units_max), dim3(256), kF64Bytes, st, P, (const bf16_t*)Q, (const bf16_t*)K,
                          (const bf16_t*)V, p.u_nu, p.u_list, p.u_start, p.off, p.blk_tok0, p.blk_len, p.qent,
                          (bf16_t*)opart, lse_part);
+    }
+    if (P.dense) {
+      const int chunks = (kTileTokens * P.g + 127) / 128;
+      ProfScope ps(KID_FWD_DENSE, st);
+      const int per = (P.nj * P.t_cap * chunks + 7) / 8;
+      hipLaunchKernelGGL(k_fwd_dense, dim3((unsigned)(8 * per)), dim3(256), kDnBytes, st, P,
+                         (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, p.tile_tok0, p.tile_len, p.d_cnt,
+                         p.d_piece, p.d_mask, (bf16_t*)odense, lse_dense);
     }
     const int64_t rows = (int64_t)P.T * P.nj * P.g;
     ProfScope ps(KID_FWD_MERGE, st);
     hipLaunchKernelGGL(k_fwd_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P, (const bf16_t*)opart,
-                       (const float*)lse_part, p.vmask, p.slotpos, p.off, (bf16_t*)O, LSE, G.gate,
-                       (const bf16_t*)G.o_acc, (bf16_t*)G.o_out);
+                       (const float*)lse_part, p.vmask, p.dmask, p.slotpos, p.off, (const bf16_t*)odense,
+                       (const float*)lse_dense, (bf16_t*)O, LSE, G.gate, (const bf16_t*)G.o_acc, (bf16_t*)G.o_out);
   }
   return hipGetLastError();
 }

@@ -21,7 +21,7 @@ constexpr int kScanTile = kScanThreads * kScanItems;  // 4096
 // key count.
 __global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int bk, int b_cap,
                        int32_t* __restrict__ blk_base,
-                       int32_t* __restrict__ blk_tok0, int32_t* __restrict__ blk_len, int32_t* __restrict__ hdr) {
+                       int32_t* __restrict__ blk_tok0, int32_t* __restrict__ blk_len, int32_t* __restrict__ hdr_slot) {
   __shared__ int s_btot;
   if (threadIdx.x == 0) {
     int acc = 0;
@@ -32,7 +32,7 @@ __global__ void k_prep(const int32_t* __restrict__ cu, int nseq, int T, int bk, 
     }
     blk_base[nseq] = acc;
     s_btot = acc;
-    hdr[HDR_BTOT] = acc;
+    *hdr_slot = acc;
   }
   __threadfence_block();
   __syncthreads();
@@ -178,6 +178,125 @@ __global__ void __launch_bounds__(256) k_chunk_prefix(int32_t* __restrict__ coun
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) len_scan[n_lists] = 0;
 }
 
+// ------------------------------------------------------------------------------------------------ dense detection
+// Dense forward path: which (query tile, KV block) pairs skip the gather route.  A query tile is kTileTokens
+// consecutive tokens of one sequence.  One wavefront per (tile, kv head), lane = token: a KV block that at least
+// `need` = half of the tile's tokens keep (the attention-sink block, the tokens' own block and the blocks next to it
+// are kept by all of them) becomes a dense pair: the forward computes it for the whole tile with the query tile read
+// once and the output accumulated on chip, a 64-bit mask saying which tokens really keep it.  The tokens' columns
+// that hold such a block are recorded in dmask; the scatter flags their list entries, and the gather route of the
+// forward skips them.  Nothing here is assumed about the selection: pairs come from counting, and any pair may take
+// either route.  Candidates are the kept blocks of three tokens of the tile (first, middle, last); a block that
+// qualifies but is kept by none of the three simply stays on the gather route.  A per-wavefront table of counters
+// (block id modulo kDenseHash, LDS atomics: counts are order-free) tells which candidates can reach `need`: lane m
+// looks up column m of the proposing token, so only the few that pass get the exact count (a ballot).
+// The dense table lists 64-key pieces (a 128-token block gives two) by first key and key count, in the order found;
+// pieces no token of the tile can see (wholly in the future, or wholly before every token's window) are left out.
+// grid (ceil(t_cap / 4), hkv), 256 threads.  Dynamic LDS: 4 * (kDenseHash + 64 * (k + 1)) ints.
+__global__ void __launch_bounds__(256) k_dense_detect(const int32_t* __restrict__ idx, const int32_t* __restrict__ cu,
+                                                      const int32_t* __restrict__ tile_tok0,
+                                                      const int32_t* __restrict__ tile_len, int nseq, int T, int hkv,
+                                                      int k, int bk, int causal, int window, int t_cap, int on,
+                                                      const uint32_t* __restrict__ vmask,
+                                                      uint32_t* __restrict__ dmask, int32_t* __restrict__ d_cnt,
+                                                      int2* __restrict__ d_piece,
+                                                      unsigned long long* __restrict__ d_mask) {
+  extern __shared__ int32_t lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, j = blockIdx.y;
+  const int qt = blockIdx.x * 4 + wave;
+  if (qt >= t_cap) return;  // no block-wide barrier below
+  int32_t* hash = lds + wave * (kDenseHash + 64 * (k + 1));
+  int32_t* rows = hash + kDenseHash;
+  const int tlen = tile_len[qt], ttok0 = tile_tok0[qt];
+  const size_t slot = (size_t)qt * hkv + j;
+  if (tlen == 0 || !on) {
+    if (lane == 0) d_cnt[slot] = 0;
+    if (lane < tlen) dmask[(size_t)(ttok0 + lane) * hkv + j] = 0u;
+    return;
+  }
+  const int t = ttok0 + lane;
+  const bool live = lane < tlen;
+  int s, c0, c1;
+  seq_bounds(cu, nseq, T, ttok0, s, c0, c1);  // a tile lies in one sequence
+  for (int i = lane; i < kDenseHash; i += 64) hash[i] = 0;
+  int32_t* row = rows + lane * (k + 1);
+  const uint32_t vm = live ? vmask[(size_t)t * hkv + j] : 0u;
+  if ((k & 3) == 0 && (reinterpret_cast<uintptr_t>(idx) & 15) == 0) {
+    // the tile's rows of idx, 16 bytes per lane: k / 4 lanes cover a row, 256 / k rows per access
+    const int lpr = k >> 2, rpa = 64 / lpr;
+    const int sub = lane % lpr, r0 = lane / lpr;
+    for (int rr = r0; rr < tlen; rr += rpa) {
+      const int4 x = *reinterpret_cast<const int4*>(idx + ((size_t)(ttok0 + rr) * hkv + j) * k + 4 * sub);
+      int32_t* dst = rows + rr * (k + 1) + 4 * sub;
+      dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+    }
+  } else if (live) {
+    const int32_t* src = idx + ((size_t)t * hkv + j) * k;
+    for (int m = 0; m < k; ++m) row[m] = src[m];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  for (int m = 0; m < k; ++m)
+    if ((vm >> m) & 1u) atomicAdd(&hash[row[m] & (kDenseHash - 1)], 1);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  // this token's kept block ids in registers (-1 where the column is not kept: no candidate matches it)
+  int kept[kMaxTopk];
+#pragma unroll
+  for (int m = 0; m < kMaxTopk; ++m) kept[m] = (m < k && ((vm >> m) & 1u)) ? row[m] : -1;
+  const int need = (tlen + 1) >> 1;
+  const int prop[3] = {0, tlen >> 1, tlen - 1};
+  int nd = 0;
+  uint32_t dm = 0;
+  for (int pi = 0; pi < 3; ++pi) {
+    const int p = prop[pi];
+    if ((pi == 1 && p == prop[0]) || (pi == 2 && (p == prop[0] || p == prop[1]))) continue;
+    const uint32_t pvm = (uint32_t)__builtin_amdgcn_readlane((int)vm, p);
+    // lane m: could column m of token p's row reach `need`?
+    const bool mine = lane < k && ((pvm >> lane) & 1u);
+    const int cand_blk = mine ? rows[p * (k + 1) + lane] : 0;
+    const int cand_cnt = mine ? hash[cand_blk & (kDenseHash - 1)] : 0;
+    unsigned long long cand = __builtin_amdgcn_ballot_w64(cand_cnt >= need);
+    while (cand != 0ull) {
+      const int m = __builtin_ctzll(cand);
+      cand &= cand - 1ull;
+      const int c = __builtin_amdgcn_readlane(cand_blk, m);
+      int mycol = -1;
+#pragma unroll
+      for (int mm = kMaxTopk - 1; mm >= 0; --mm) mycol = kept[mm] == c ? mm : mycol;
+      const unsigned long long members = __builtin_amdgcn_ballot_w64(mycol >= 0);
+      // an earlier proposer that keeps c has already dealt with it
+      bool seen = false;
+      for (int pj = 0; pj < pi; ++pj) seen |= ((members >> prop[pj]) & 1ull) != 0ull;
+      if (seen || __popcll(members) < need) continue;
+      // the block's 64-key pieces some token of the tile can see
+      const int btok0 = c0 + c * bk, blen = min(bk, c1 - btok0);
+      int np = 0, ptok[2], plen[2];
+      for (int sub = 0; sub < (bk >> 6); ++sub) {
+        const int pt = btok0 + 64 * sub, pl = min(64, blen - 64 * sub);
+        if (pl <= 0) continue;
+        if (causal && pt > ttok0 + tlen - 1) continue;
+        if (window > 0 && pt + pl - 1 < ttok0 - window + 1) continue;
+        ptok[np] = pt;
+        plen[np] = pl;
+        ++np;
+      }
+      if (nd + np > kDenseMax) continue;
+      if (lane == 0)
+        for (int q = 0; q < np; ++q) {
+          d_piece[slot * kDenseMax + nd + q] = make_int2(ptok[q], plen[q]);
+          d_mask[slot * kDenseMax + nd + q] = members;
+        }
+      if (mycol >= 0) dm |= 1u << mycol;  // also when no piece is visible: the pair then contributes nothing
+      nd += np;
+    }
+  }
+  if (lane == 0) d_cnt[slot] = nd;
+  if (live) dmask[(size_t)t * hkv + j] = dm;
+}
+
 // ------------------------------------------------------------------------------------------------ scan
 __global__ void __launch_bounds__(kScanThreads) k_scan_reduce(const int32_t* __restrict__ a, int64_t n,
                                                               int32_t* __restrict__ sums) {
@@ -253,7 +372,8 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
                                                 int bk, int causal, int b_cap, int n_chunks,
                                                 const int32_t* __restrict__ chunk_off,
                                                 const int32_t* __restrict__ off, int2* __restrict__ qent,
-                                                const uint32_t* __restrict__ vmask, int32_t* __restrict__ slotpos) {
+                                                const uint32_t* __restrict__ vmask,
+                                                const uint32_t* __restrict__ dmask, int32_t* __restrict__ slotpos) {
   extern __shared__ int32_t lds[];
   unsigned long long* mask = reinterpret_cast<unsigned long long*>(lds);
   int32_t* cursor = lds + 2 * b_cap;
@@ -275,7 +395,7 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
   const bool vec4 = (k & 3) == 0 && ((reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(slotpos)) & 15) == 0;
   for (int r0 = t0; r0 < t1; r0 += 64) {
     const int t = r0 + lane;
-    uint32_t vm = 0;
+    uint32_t vm = 0, dm = 0;
     int base = 0;
     if (t < t1) {
       int s, c0, c1;
@@ -290,6 +410,7 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
         for (int m = 0; m < k; ++m) row[m] = src[m];
       }
       vm = vmask[(size_t)t * hkv + j];  // kept columns, decided by the histogram pass
+      dm = dmask[(size_t)t * hkv + j];  // those of them the dense forward path takes over
       base = blk_base[s] - gb_lo;
     }
     // A: mark membership of this round's tokens in every block they keep
@@ -315,7 +436,9 @@ __global__ void __launch_bounds__(64) k_scatter(const int32_t* __restrict__ idx,
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int pos = on[u] ? c[u] + __popcll(mk[u] & below) : -1;
-        if (on[u]) qent[pos] = make_int2(t, m0 + u);
+        // the sign bit of the column flags an entry of a dense (tile, block) pair: the forward's gather route skips
+        // it, the backward (which walks whole lists) ignores the flag
+        if (on[u]) qent[pos] = make_int2(t, (m0 + u) | (int)(((dm >> (m0 + u)) & 1u) << 31));
         if (m0 + u < k) prow[m0 + u] = pos;
       }
     }
@@ -392,7 +515,10 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
   }
   { ProfScope ps(KID_INDEX_PREP, st);
   hipLaunchKernelGGL(k_prep, dim3(1), dim3(256), 0, st, cu, L.nseq, L.T, L.bk, L.b_cap, p.blk_base, p.blk_tok0, p.blk_len,
-                     p.hdr); }
+                     p.hdr + HDR_BTOT);
+  // the query tiles of the dense forward path: the same table for blocks of kTileTokens tokens
+  hipLaunchKernelGGL(k_prep, dim3(1), dim3(256), 0, st, cu, L.nseq, L.T, kTileTokens, L.t_cap, p.tile_base, p.tile_tok0,
+                     p.tile_len, p.hdr + HDR_NTILES); }
   { ProfScope ps(KID_INDEX_HIST, st);
   hipLaunchKernelGGL(k_hist, dim3(L.n_chunks, L.hkv), dim3(256), lds_hist, st, idx, cu, p.blk_base, L.nseq, L.T, L.hkv,
                      L.topk, L.bk, L.causal, L.window, L.b_cap, L.n_chunks, p.chunk_off, p.vmask); }
@@ -402,9 +528,16 @@ hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const in
                      L.n_lists, p.cnt, p.off); }
   { ProfScope ps(KID_INDEX_SCAN, st);
   scan_exclusive(p.off, nl1, p.scan_tmp, st); }
+  { ProfScope ps(KID_INDEX_DENSE, st);
+  const size_t lds_dense = 4 * (size_t)(kDenseHash + 64 * (L.topk + 1)) * 4;
+  hipLaunchKernelGGL(k_dense_detect, dim3((L.t_cap + 3) / 4, L.hkv), dim3(256), lds_dense, st, idx, cu, p.tile_tok0,
+                     p.tile_len, L.nseq, L.T, L.hkv, L.topk, L.bk, L.causal, L.window, L.t_cap,
+                     L.dense, p.vmask,
+                     p.dmask, p.d_cnt, p.d_piece, p.d_mask); }
   { ProfScope ps(KID_INDEX_SCATTER, st);
   hipLaunchKernelGGL(k_scatter, dim3(L.n_chunks, L.hkv), dim3(64), lds_scat, st, idx, cu, p.blk_base, L.nseq, L.T,
-                     L.hkv, L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.off, p.qent, p.vmask, p.slotpos); }
+                     L.hkv, L.topk, L.bk, L.causal, L.b_cap, L.n_chunks, p.chunk_off, p.off, p.qent, p.vmask, p.dmask,
+                     p.slotpos); }
   { ProfScope ps(KID_INDEX_FINALIZE, st);
   hipLaunchKernelGGL(k_finalize, dim3((nl1 + 255) / 256), dim3(256), 0, st, p.cnt, p.off, L.n_lists, L.unit, p.u_nu,
                      p.hdr); }

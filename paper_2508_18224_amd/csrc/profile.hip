@@ -15,7 +15,8 @@ bool g_on = false;
 unsigned g_mask = ~0u;  // kernel kinds that are recorded (bit = index in kNames)
 const char* const kNames[KID_COUNT] = {"index_prep", "index_chunk_prefix", "index_hist", "index_scan", "index_scatter",
                                        "index_finalize", "index_units", "fwd_main", "fwd_merge", "bwd_delta",
-                                       "bwd_main", "bwd_dq_reduce", "bwd_dkv_reduce", "select_blocks", "fwd_query_outer"};
+                                       "bwd_main", "bwd_dq_reduce", "bwd_dkv_reduce", "select_blocks", "fwd_query_outer",
+                                       "index_dense", "fwd_dense"};
 }  // namespace
 
 ProfScope::ProfScope(int kid, hipStream_t stream) : slot(-1), st(stream) {

@@ -22,13 +22,13 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
 class Case:
     """A realised workload on the device plus the library object that owns its workspaces."""
 
-    def __init__(self, w: wl.Workload, bwd: bool = True, scale: float = 0.0, window: int = 0):
+    def __init__(self, w: wl.Workload, bwd: bool = True, scale: float = 0.0, window: int = 0, dense: bool = True):
         self.w = w
         self.q, self.k, self.v, self.do = (dev_bf16(x) for x in (w.q, w.k, w.v, w.do))
         self.idx = torch.from_numpy(w.idx).cuda()
         self.cu = torch.from_numpy(w.cu_seqlens).cuda()
         self.attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal,
-                                     scale=scale, bwd=bwd, block=w.block, window=window)
+                                     scale=scale, bwd=bwd, block=w.block, window=window, dense=dense)
 
     def host_f64(self):
         w = self.w
