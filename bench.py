@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # kernel kinds of nsa_sel_profile_collect -> kernel names in the rocprofv3 summaries under profiles/
 KERNEL_NAMES = {
     "fwd_main": ("nsa::k_fwd_main", "nsa::k_fwd_main128"), "fwd_merge": ("nsa::k_fwd_merge",),
-    "fwd_dense": ("nsa::k_fwd_dense",),
+    "fwd_dense": ("nsa::k_fwd_dense_merge",),
     "bwd_main": ("nsa::k_bwd_tiled<2>", "nsa::k_bwd_tiled<4>"), "bwd_delta": ("nsa::k_bwd_delta",),
     "bwd_dq_reduce": ("nsa::k_bwd_dq_reduce",), "bwd_dkv_reduce": ("nsa::k_bwd_dkv_reduce",),
 }

@@ -70,9 +70,9 @@ typedef struct {
                              the workspace sizes, not results (dK/dV only in their fp32 summation order)      */
   int32_t dense;          /* 0: the forward routes (query tile of 64 tokens, KV block) pairs that at least half of
                              the tile's tokens keep - found by counting, e.g. the attention-sink block (App. E) and
-                             the tokens' own and neighbouring blocks - through a query-tile-outer kernel that needs
-                             no gather and one partial row per (token, head) instead of one per slot.  -1: every
-                             pair takes the gather route.  Same results up to rounding; the index workspace built
+                             the tokens' own and neighbouring blocks - through a query-tile-outer kernel, fused
+                             with the reduction step, that needs no gather and no partial row.  -1: every pair
+                             takes the gather route.  Same results up to rounding; the index workspace built
                              for one setting must not be used with the other                                   */
 } nsa_sel_shape;
 
@@ -127,8 +127,8 @@ int nsa_sel_bwd(const nsa_sel_shape* shape, const void* Q, const void* K, const 
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as nsa_sel_fwd (bit for bit)
  * minus ws / ws_bytes: the partial outputs and log-sum-exps live in a file-scope device array of the library of
  * NSA_SEL_STATIC_WS_BYTES (64 MiB).  The call allocates and frees nothing.  The partial results of ONE KV head,
- * total_tokens * (hq / hkv) * (topk + 1) * 260 bytes (+ up to 1 KB of alignment; topk instead of topk + 1 with
- * shape->dense = -1), must fit the array - e.g. 3776 tokens at g = 4, topk = 16 - otherwise NSA_SEL_ESTATIC is returned and nothing is enqueued; when several KV heads fit they
+ * total_tokens * (hq / hkv) * topk * 260 bytes (+ up to 512 bytes of alignment), must fit the array - e.g. 4032 tokens
+ * at g = 4, topk = 16 - otherwise NSA_SEL_ESTATIC is returned and nothing is enqueued; when several KV heads fit they
  * share a pass, as with a capped ws.  The index workspace is still the caller's (it is an output the backward reads).
  * Every call on a GPU uses that GPU's one array and leaves its partial rows behind; nothing needs clearing between
  * calls, but two calls in flight on the same GPU at once (two streams, two threads) race on it and give wrong

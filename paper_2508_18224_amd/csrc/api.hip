@@ -106,14 +106,9 @@ static size_t partial_rows(const nsa_sel_shape* s, int nj) {
 }
 
 // Workspaces that hold the partial results of nj KV heads at once (nj = hkv: everything in one pass).
-// One more row per (token, head of the pass): the dense path's partial output and log-sum-exp.
-static size_t dense_rows(const nsa_sel_shape* s, int nj) {
-  return s->dense == 0 ? (size_t)s->total_tokens * nj * (s->hq / s->hkv) : 0;
-}
-
 static size_t fwd_ws_bytes(const nsa_sel_shape* s, int nj) {
-  const size_t rows = partial_rows(s, nj), drows = dense_rows(s, nj);
-  return align256(rows * kD * 2) + align256(rows * 4) + align256(drows * kD * 2) + align256(drows * 4);
+  const size_t rows = partial_rows(s, nj);
+  return align256(rows * kD * 2) + align256(rows * 4);
 }
 
 static size_t bwd_ws_bytes(const nsa_sel_shape* s, const IndexLayout& L, int nj) {
@@ -211,15 +206,10 @@ static int fwd_impl(const nsa_sel_shape* shape, const void* Q, const void* K, co
   if (rebuild_index && launch_build_index(L, idx, cu_seqlens, index_ws, st) != hipSuccess) return NSA_SEL_EHIP;
   Problem P = make_problem(shape, L);
   const size_t rows = partial_rows(shape, hpp);
-  const size_t drows = dense_rows(shape, hpp);
-  char* w = (char*)ws;
-  void* opart = w;
-  float* lse_part = (float*)(w + align256(rows * kD * 2));
-  void* odense = (char*)lse_part + align256(rows * 4);
-  float* lse_dense = (float*)((char*)odense + align256(drows * kD * 2));
-  return launch_fwd(P, L, hpp, Q, K, V, index_ws, opart, lse_part, odense, lse_dense, O, LSE, G, st) == hipSuccess
-             ? NSA_SEL_OK
-             : NSA_SEL_EHIP;
+  void* opart = ws;
+  float* lse_part = (float*)((char*)ws + align256(rows * kD * 2));
+  return launch_fwd(P, L, hpp, Q, K, V, index_ws, opart, lse_part, O, LSE, G, st) == hipSuccess ? NSA_SEL_OK
+                                                                                                 : NSA_SEL_EHIP;
 }
 
 int nsa_sel_fwd(const nsa_sel_shape* shape, const void* Q, const void* K, const void* V, const int32_t* idx,
@@ -348,8 +338,8 @@ const char* nsa_sel_strerror(int code) {
     case NSA_SEL_EWORKSPACE: return "workspace too small (see nsa_sel_workspace_bytes / nsa_sel_workspace_bytes_min)";
     case NSA_SEL_EHIP: return "HIP runtime error at launch";
     case NSA_SEL_ESTATIC:
-      return "shape too large for nsa_sel_fwd_static: the partial results of one KV head (total_tokens * g * "
-             "(topk + 1) * 260 bytes) exceed NSA_SEL_STATIC_WS_BYTES; use nsa_sel_fwd with a caller-owned workspace";
+      return "shape too large for nsa_sel_fwd_static: the partial results of one KV head (total_tokens * g * topk * "
+             "260 bytes) exceed NSA_SEL_STATIC_WS_BYTES; use nsa_sel_fwd with a caller-owned workspace";
     default: return "unknown nsa_sel error code";
   }
 }

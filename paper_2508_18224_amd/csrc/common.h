@@ -162,10 +162,9 @@ struct GateArgs {
 hipError_t launch_build_index(const IndexLayout& L, const int32_t* idx, const int32_t* cu, void* index_ws,
                               hipStream_t st);
 // heads_per_pass: KV heads whose partial results the workspace can hold at once (1 .. hkv)
-// odense / lse_dense: one partial row per (token, head of the pass) from the dense path (unused when it is off)
 hipError_t launch_fwd(const Problem& P, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
-                      const void* V, const void* index_ws, void* opart, float* lse_part, void* odense,
-                      float* lse_dense, void* O, float* LSE, const GateArgs& G, hipStream_t st);
+                      const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
+                      const GateArgs& G, hipStream_t st);
 // the same forward in query-outer loop order (no workspaces, no index): see qouter.hip
 hipError_t launch_fwd_query_outer(const Problem& P, const void* Q, const void* K, const void* V, const int32_t* idx,
                                   const int32_t* cu, void* O, float* LSE, hipStream_t st);

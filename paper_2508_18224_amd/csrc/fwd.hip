@@ -489,30 +489,46 @@ k_fwd_main128(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict_
 }
 
 
-// ---- dense (query-tile-outer) forward ------------------------------------------------------------------------------
+// ---- dense (query-tile-outer) forward, fused with the merge ---------------------------------------------------------
 // The (query tile, KV block) pairs the index marked dense - blocks that at least half of the tile's 64 tokens keep:
 // the attention-sink block and the tokens' own and neighbouring blocks (App. E, the paragraph on the attention sink;
 // the whole band of the sliding-window term of Eq. (2)) - are contiguous token ranges on both sides, so they need no
-// gather and no partial row per slot: one workgroup takes 128 rows (row = (token of the tile, head of the group)) of
-// one (tile, kv head), keeps their Q fragments in registers and walks the tile's dense blocks, 64 keys at a time
-// (the index lists them as pieces) through LDS, with a running (max, sum) per row and the output accumulated in registers across the blocks.  What
-// leaves the kernel is ONE normalised partial row and log-sum-exp per (token, head), which the merge combines with
-// the rows of the gather route.  The 64-bit mask of a pair says which tokens of the tile keep the block; the others
-// see none of its keys.  S^T = K Q^T and O^T = V^T P^T as in the kernels above (K fragments are 16-byte LDS reads,
-// V^T fragments LDS transpose reads); the next 64 keys are fetched into registers while the current ones compute.
+// gather and no partial row in memory at all.  One workgroup takes 128 rows (row = (token of the tile, head of the
+// group)) of one (tile, kv head):
+//   phase 1  keeps the rows' Q fragments in registers and walks the tile's dense blocks, 64 keys at a time (the index
+//            lists them as pieces) through LDS, with a running (max, sum) per row and the output accumulated in
+//            registers across the pieces.  The 64-bit mask of a piece says which tokens of the tile keep its block;
+//            the others see none of its keys.  S^T = K Q^T and O^T = V^T P^T as in the kernels above (K fragments
+//            are 16-byte LDS reads, V^T fragments LDS transpose reads); the next piece is fetched into registers while
+//            the current one computes.  The result, normalised, goes to a wave-private LDS tile with its log-sum-exp.
+//   phase 2  is the reduction step of Sec. 3.2 for the same rows: 16 lanes per row gather the partial rows the gather
+//            route left for the row's other kept columns (two rows and eight columns at a time per lane: the few
+//            wavefronts of this kernel need that many loads in flight) and combine them, together with the row of
+//            phase 1, by their log-sum-exps; O, LSE and the optional gated sum of Eq. (2) are written once.  The
+//            rows' kept-column masks and slot positions are fetched at the very start of the kernel and parked in
+//            the wave's LDS tile (free between the Q staging and the end), so that phase 2 starts with its addresses
+//            known and the only memory latency left in it is that of the gathers themselves.
+// Tiles without a dense piece skip phase 1, so with the dense route on this kernel is the merge of every row.
 constexpr int kDnPitch = 152;                                  // bf16 per LDS row of the K / V tiles
 constexpr int kDnK = 0;
 constexpr int kDnV = kDnK + 64 * kDnPitch * 2;
 constexpr int kDnTiles = kDnV + 64 * kDnPitch * 2;
-constexpr int kDnBytes = kDnTiles + 4 * 32 * kTileStride * 2;  // 73728: two workgroups per CU
+constexpr int kDnLse = kDnTiles + 4 * 32 * kTileStride * 2;
+constexpr int kDnBytes = kDnLse + 4 * 32 * 4;                  // 74240: two workgroups per CU
+static_assert(4 * 32 * kTileStride * 2 <= kDnTiles, "phase 1's result must fit the K / V area");
+static_assert((kMaxTopk + 2) * 32 * 4 <= 32 * kTileStride * 2, "a wavefront's index data must fit its LDS tile");
+constexpr int kMergeBatch = 8;                                 // columns of a row gathered at a time in phase 2
 static_assert(2 * kDnBytes <= 160 * 1024, "two workgroups of the dense forward must fit one CU's LDS");
 
 __global__ void __launch_bounds__(256, 2)
-k_fwd_dense(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-            const int32_t* __restrict__ tile_tok0, const int32_t* __restrict__ tile_len,
-            const int32_t* __restrict__ d_cnt, const int2* __restrict__ d_piece,
-            const unsigned long long* __restrict__ d_mask, bf16_t* __restrict__ odense,
-            float* __restrict__ lse_dense) {
+k_fwd_dense_merge(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+                  const int32_t* __restrict__ tile_tok0, const int32_t* __restrict__ tile_len,
+                  const int32_t* __restrict__ d_cnt, const int2* __restrict__ d_piece,
+                  const unsigned long long* __restrict__ d_mask, const bf16_t* __restrict__ opart,
+                  const float* __restrict__ lse_part, const uint32_t* __restrict__ vmask,
+                  const uint32_t* __restrict__ dmask, const int32_t* __restrict__ slotpos,
+                  const int32_t* __restrict__ off, bf16_t* __restrict__ O, float* __restrict__ LSE,
+                  const float* __restrict__ gate, const bf16_t* Oacc, bf16_t* Oout) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + kDnK);
   bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + kDnV);
@@ -526,186 +542,320 @@ k_fwd_dense(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
   const int chunk = lid % chunks, qt = (lid / chunks) % P.t_cap;
   const int j = P.j0 + lid / (chunks * P.t_cap);
   const size_t slot = (size_t)qt * P.hkv + j;
+  // everything the prologue needs from the tables is requested at once (the first piece's slot exists even when the
+  // tile has no dense piece)
   const int nd = d_cnt[slot];
   const int tlen = tile_len[qt];
-  const int rows_total = tlen * P.g;
-  if (nd == 0 || chunk * 128 >= rows_total) return;  // nothing dense here: no row of this tile reads the dense buffers
   const int ttok0 = tile_tok0[qt];
+  const int2 piece0 = d_piece[slot * kDenseMax];
+  const int rows_total = tlen * P.g;
+  if (chunk * 128 >= rows_total) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
   const int crow = lane >> 4, cchunk = (lane & 15) * 8;
   bf16_t* tile_lds = reinterpret_cast<bf16_t*>(smem + kDnTiles) + wave * 32 * kTileStride;
+  float* lse_lds = reinterpret_cast<float*>(smem + kDnLse) + wave * 32;
+  bf16_t* od_lds = Ks + wave * 32 * kTileStride;   // phase 1's result for phase 2 (the K / V area after the last piece)
   const int row0 = chunk * 128 + wave * 32;        // first row of this wavefront
   const bool wave_on = row0 < rows_total;          // idle wavefronts still help to stage K / V
   const int hbase = j * P.g;
-  const float c2 = P.scale * 1.4426950408889634f;
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-  // this wavefront's 32 rows of Q: coalesced loads -> wave tile -> B-operand fragments, kept for the whole tile
-  bf16x8 qf[8];
-  if (wave_on) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = min(row0 + 4 * i + crow, rows_total - 1);
-      const int e = div_g(r, P.g, P.g_magic);
-      const uint32_t grow = (uint32_t)(ttok0 + e) * (uint32_t)P.hq + (uint32_t)(hbase + (r - e * P.g));
-      *reinterpret_cast<u32x4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) =
-          *reinterpret_cast<const u32x4*>(Q + ((size_t)grow * kD + cchunk));
-    }
-    wave_sync();
-#pragma unroll
-    for (int s = 0; s < 8; ++s)
-      qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kTileStride + 16 * s + 8 * qh]);
-  }
-  const int r = row0 + col;                        // this lane's row
-  const bool valid = r < rows_total;
-  const int e_row = div_g(min(r, rows_total - 1), P.g, P.g_magic);
-  const int t = ttok0 + e_row;
-
-  f32x16 oacc[4];
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;            // running maximum (raw scores) and sum of the row
-
-  // staging of 64 keys: thread = (key, 32 channels), four 16-byte pieces of K and of V
-  const int skey = tid >> 2, sd0 = (tid & 3) * 32;
-  const int steps = nd;                            // one 64-key piece per step
-  u32x4 kreg[4], vreg[4];
-  auto fetch = [&](int step) {
-    const int2 piece = d_piece[slot * kDenseMax + step];  // (first key, number of keys)
-    const bool on = skey < piece.y;
-    const size_t o = ((size_t)(piece.x + (on ? skey : 0)) * P.hkv + j) * kD + sd0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      kreg[i] = *reinterpret_cast<const u32x4*>(K + o + 8 * i);
-      vreg[i] = *reinterpret_cast<const u32x4*>(V + o + 8 * i);
-      if (!on) {  // rows past the end of a ragged block are zero
-        kreg[i] = u32x4{0, 0, 0, 0};
-        vreg[i] = u32x4{0, 0, 0, 0};
-      }
-    }
+  // Phase 2's index data for this wavefront's tokens: per token (kept columns, dense columns, slot positions).
+  // Requested now (up to 4 words per lane in registers, the rest - many tokens per wave, long rows - later), stored to
+  // the wave's LDS tile once the Q fragments have left it.
+  const int e_lo = div_g(min(row0, rows_total - 1), P.g, P.g_magic);
+  const int e_hi = div_g(min(row0 + 31, rows_total - 1), P.g, P.g_magic);
+  const int mstride = P.topk + 2;
+  const int mwords = wave_on ? (e_hi - e_lo + 1) * mstride : 0;
+  int32_t* meta = reinterpret_cast<int32_t*>(tile_lds);
+  auto meta_word = [&](int i) -> int32_t {
+    const int tk = i / mstride, c = i - tk * mstride;
+    const size_t tj = (size_t)(ttok0 + e_lo + tk) * P.hkv + j;
+    return c == 0 ? (int32_t)vmask[tj] : c == 1 ? (int32_t)dmask[tj] : slotpos[tj * P.topk + (c - 2)];
   };
-  const int grp = lane >> 4, sl = lane & 15;
-  const int tr_v = ((sl >> 2) + 4 * (grp >> 1)) * kDnPitch + 16 * (grp & 1) + 4 * (sl & 3);
+  int32_t mreg[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) mreg[q] = lane + 64 * q < mwords ? meta_word(lane + 64 * q) : 0;
+  auto park_meta = [&]() {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (lane + 64 * q < mwords) meta[lane + 64 * q] = mreg[q];
+    for (int i = lane + 256; i < mwords; i += 64) meta[i] = meta_word(i);
+    wave_sync();
+  };
 
-  fetch(0);
-  for (int step = 0; step < steps; ++step) {
-    __syncthreads();  // the previous piece is no longer read
+  if (nd > 0) {  // ---------------------------------------------------------------------------------- phase 1
+    const float c2 = P.scale * 1.4426950408889634f;
+    // staging of 64 keys: thread = (key, 32 channels), four 16-byte pieces of K and of V
+    const int skey = tid >> 2, sd0 = (tid & 3) * 32;
+    u32x4 kreg[4], vreg[4];
+    auto fetch = [&](int2 piece) {  // (first key, number of keys)
+      const bool on = skey < piece.y;
+      const size_t o = ((size_t)(piece.x + (on ? skey : 0)) * P.hkv + j) * kD + sd0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<u32x4*>(&Ks[skey * kDnPitch + sd0 + 8 * i]) = kreg[i];
-      *reinterpret_cast<u32x4*>(&Vs[skey * kDnPitch + sd0 + 8 * i]) = vreg[i];
-    }
-    const int2 piece = d_piece[slot * kDenseMax + step];
-    const unsigned long long members = d_mask[slot * kDenseMax + step];
-    const int ktok0 = piece.x, klen = piece.y;                // first key of the piece and its number of keys
-    if (step + 1 < steps) fetch(step + 1);                    // flies during the compute
-    __syncthreads();  // K, V of the piece staged
-    if (!wave_on) continue;
-
-    f32x16 sacc[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[mb][v] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 8; ++s)
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Ks[(32 * mb + col) * kDnPitch + 16 * s + 8 * qh]);
-        sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[mb], 0, 0, 0);
+      for (int i = 0; i < 4; ++i) {
+        kreg[i] = *reinterpret_cast<const u32x4*>(K + o + 8 * i);
+        vreg[i] = *reinterpret_cast<const u32x4*>(V + o + 8 * i);
+        if (!on) {  // rows past the end of a ragged block are zero
+          kreg[i] = u32x4{0, 0, 0, 0};
+          vreg[i] = u32x4{0, 0, 0, 0};
+        }
       }
-    // keys [lo, lim) of the piece are visible to this row: none if the token does not keep the block
-    int lim = P.causal ? min(klen, t - ktok0 + 1) : klen;
-    if (!valid || !((members >> e_row) & 1ull)) lim = 0;
-    const int lo = P.window > 0 ? t - P.window + 1 - ktok0 : 0;
-    float m = -INFINITY;
-    if (__builtin_amdgcn_ballot_w64(lim < 64 || lo > 0) == 0) {
+    };
+    // this wavefront's 32 rows of Q (coalesced loads) and the first piece are requested together
+    u32x4 qc[8];
+    if (wave_on) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int r = min(row0 + 4 * i + crow, rows_total - 1);
+        const int e = div_g(r, P.g, P.g_magic);
+        const uint32_t grow = (uint32_t)(ttok0 + e) * (uint32_t)P.hq + (uint32_t)(hbase + (r - e * P.g));
+        qc[i] = *reinterpret_cast<const u32x4*>(Q + ((size_t)grow * kD + cchunk));
+      }
+    }
+    fetch(piece0);
+    // Q rows -> wave tile -> B-operand fragments, kept for the whole tile
+    bf16x8 qf[8];
+    if (wave_on) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(&tile_lds[(4 * i + crow) * kTileStride + cchunk]) = qc[i];
+      wave_sync();
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        qf[s] = *reinterpret_cast<const bf16x8*>(&tile_lds[col * kTileStride + 16 * s + 8 * qh]);
+      wave_sync();
+      park_meta();  // the tile is free until phase 2
+    }
+    const int r = row0 + col;                        // this lane's row
+    const bool valid = r < rows_total;
+    const int e_row = div_g(min(r, rows_total - 1), P.g, P.g_magic);
+    const int t = ttok0 + e_row;
+
+    f32x16 oacc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;            // running maximum (raw scores) and sum of the row
+    const int grp = lane >> 4, sl = lane & 15;
+    const int tr_v = ((sl >> 2) + 4 * (grp >> 1)) * kDnPitch + 16 * (grp & 1) + 4 * (sl & 3);
+
+    for (int step = 0; step < nd; ++step) {
+      __syncthreads();  // the previous piece is no longer read
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        *reinterpret_cast<u32x4*>(&Ks[skey * kDnPitch + sd0 + 8 * i]) = kreg[i];
+        *reinterpret_cast<u32x4*>(&Vs[skey * kDnPitch + sd0 + 8 * i]) = vreg[i];
+      }
+      const int2 piece = d_piece[slot * kDenseMax + step];
+      const unsigned long long members = d_mask[slot * kDenseMax + step];
+      const int ktok0 = piece.x, klen = piece.y;                // first key of the piece and its number of keys
+      if (step + 1 < nd) fetch(d_piece[slot * kDenseMax + step + 1]);  // flies during the compute
+      __syncthreads();  // K, V of the piece staged
+      if (!wave_on) continue;
+
+      f32x16 sacc[2];
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) m = fmaxf(m, sacc[mb][v]);
-    } else {
+        for (int v = 0; v < 16; ++v) sacc[mb][v] = 0.f;
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Ks[(32 * mb + col) * kDnPitch + 16 * s + 8 * qh]);
+          sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[mb], 0, 0, 0);
+        }
+      // keys [lo, lim) of the piece are visible to this row: none if the token does not keep the block
+      int lim = P.causal ? min(klen, t - ktok0 + 1) : klen;
+      if (!valid || !((members >> e_row) & 1ull)) lim = 0;
+      const int lo = P.window > 0 ? t - P.window + 1 - ktok0 : 0;
+      float m = -INFINITY;
+      if (__builtin_amdgcn_ballot_w64(lim < 64 || lo > 0) == 0) {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) m = fmaxf(m, sacc[mb][v]);
+      } else {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
+            const float x = (key < lim && key >= lo) ? sacc[mb][v] : -INFINITY;
+            sacc[mb][v] = x;
+            m = fmaxf(m, x);
+          }
+      }
+      m = fmaxf(m, __shfl_xor(m, 32));
+      // online softmax: new running maximum, rescale of what has been accumulated
+      const float m_new = fmaxf(m_run, m);
+      const float mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
+      const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c2, -mc));  // exp2(-inf) = 0 on the first visible piece
+      m_run = m_new;
+      float l = 0.f;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int key = 32 * mb + 8 * (v >> 2) + 4 * qh + (v & 3);
-          const float x = (key < lim && key >= lo) ? sacc[mb][v] : -INFINITY;
-          sacc[mb][v] = x;
-          m = fmaxf(m, x);
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][v], c2, -mc));
+          sacc[mb][v] = p;
+          l += p;
+        }
+      l += __shfl_xor(l, 32);
+      l_run = l_run * alpha + l;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+
+      bf16x8 pf[4];
+#pragma unroll
+      for (int sp = 0; sp < 4; ++sp)
+#pragma unroll
+        for (int e2 = 0; e2 < 8; ++e2) pf[sp][e2] = (bf16_t)sacc[sp >> 1][8 * (sp & 1) + e2];
+#pragma unroll
+      for (int sp = 0; sp < 4; ++sp)
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const bf16x4 a0 = lds_read_tr_f(&Vs[16 * sp * kDnPitch + tr_v + 32 * db]);
+          const bf16x4 a1 = lds_read_tr_f(&Vs[(16 * sp + 8) * kDnPitch + tr_v + 32 * db]);
+          const bf16x8 vf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], oacc[db], 0, 0, 0);
         }
     }
-    m = fmaxf(m, __shfl_xor(m, 32));
-    // online softmax: new running maximum, rescale of what has been accumulated
-    const float m_new = fmaxf(m_run, m);
-    const float mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
-    const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c2, -mc));  // exp2(-inf) = 0 on the first visible piece
-    m_run = m_new;
-    float l = 0.f;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][v], c2, -mc));
-        sacc[mb][v] = p;
-        l += p;
-      }
-    l += __shfl_xor(l, 32);
-    l_run = l_run * alpha + l;
+    __syncthreads();  // every wavefront is done with the last piece: the K / V area is free
+    if (!wave_on) return;
+    // the rows' dense result, normalised, and its log-sum-exp (natural log; -inf for a row that keeps none of the
+    // tile's dense blocks) -> this wavefront's quarter of the K / V area, where phase 2 picks them up in its own
+    // lane layout
+    const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
-
-    bf16x8 pf[4];
-#pragma unroll
-    for (int sp = 0; sp < 4; ++sp)
-#pragma unroll
-      for (int e2 = 0; e2 < 8; ++e2) pf[sp][e2] = (bf16_t)sacc[sp >> 1][8 * (sp & 1) + e2];
-#pragma unroll
-    for (int sp = 0; sp < 4; ++sp)
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const bf16x4 a0 = lds_read_tr_f(&Vs[16 * sp * kDnPitch + tr_v + 32 * db]);
-        const bf16x4 a1 = lds_read_tr_f(&Vs[(16 * sp + 8) * kDnPitch + tr_v + 32 * db]);
-        const bf16x8 vf = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sp], oacc[db], 0, 0, 0);
+      for (int a = 0; a < 4; ++a) {
+        uint2 w;
+        w.x = pack_bf16x2(oacc[db][4 * a + 0] * inv, oacc[db][4 * a + 1] * inv);
+        w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
+        *reinterpret_cast<uint2*>(&od_lds[col * kTileStride + 32 * db + 8 * a + 4 * qh]) = w;
       }
+    if (qh == 0) {
+      const float mcf = (m_run == -INFINITY) ? 0.f : m_run * c2;
+      lse_lds[col] = l_run > 0.f ? (mcf + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f : -INFINITY;
+    }
+    wave_sync();
   }
   if (!wave_on) return;
 
-  // one normalised partial row per (token, head) -> wave tile -> coalesced 256-byte row stores.  Rows are indexed
-  // (token, head within the pass's heads); a row no dense block of which the token keeps gets log-sum-exp -inf.
-  const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+  // ------------------------------------------------------------------------------------------------ phase 2
+  if (nd == 0) park_meta();
+  const int sub = lane & 15;
+  const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
+  for (int pass = 0; pass < 4; ++pass) {
+    // two rows per lane group: wave rows 4 pass + crow and 16 more
+    bool ok[2];
+    int hh[2];
+    int64_t grow[2];
+    uint32_t vm_all[2], vm[2];
+    const int32_t* sp[2];  // the row's slot positions (LDS)
+    float acc[2][8], M[2], Ls[2];
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
+    for (int x = 0; x < 2; ++x) {
+      const int wrow = 4 * pass + crow + 16 * x;
+      const int rr = row0 + wrow;
+      ok[x] = rr < rows_total;
+      const int rc = min(rr, rows_total - 1);
+      const int e = div_g(rc, P.g, P.g_magic);
+      hh[x] = rc - e * P.g;
+      grow[x] = (int64_t)(ttok0 + e) * P.hq + hbase + hh[x];
+      const int32_t* mrow = meta + (e - e_lo) * mstride;
+      vm_all[x] = ok[x] ? (uint32_t)mrow[0] : 0u;
+      const uint32_t dm = ok[x] ? (uint32_t)mrow[1] : 0u;
+      vm[x] = vm_all[x] & ~dm;
+      sp[x] = mrow + 2;
+      M[x] = -INFINITY;
+      Ls[x] = 0.f;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      uint2 w;
-      w.x = pack_bf16x2(oacc[db][4 * a + 0] * inv, oacc[db][4 * a + 1] * inv);
-      w.y = pack_bf16x2(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
-      *reinterpret_cast<uint2*>(&tile_lds[col * kTileStride + 32 * db + 8 * a + 4 * qh]) = w;
+      for (int c = 0; c < 8; ++c) acc[x][c] = 0.f;
+      if (dm != 0u && nd > 0) {  // the row of phase 1 starts the sum
+        const float ls = lse_lds[wrow];
+        if (ls > -INFINITY) {
+          const uint4 v = *reinterpret_cast<const uint4*>(&od_lds[wrow * kTileStride + 8 * sub]);
+          M[x] = ls;
+          Ls[x] = 1.f;
+          acc[x][0] = bf16_lo(v.x); acc[x][1] = bf16_hi(v.x); acc[x][2] = bf16_lo(v.y); acc[x][3] = bf16_hi(v.y);
+          acc[x][4] = bf16_lo(v.z); acc[x][5] = bf16_hi(v.z); acc[x][6] = bf16_lo(v.w); acc[x][7] = bf16_hi(v.w);
+        }
+      }
     }
-  wave_sync();
-  const int hp = P.nj * P.g;                        // heads of the pass
-  const int hoff = (j - P.j0) * P.g;
+    for (int m0 = 0; m0 < P.topk; m0 += kMergeBatch) {
+      if (((vm[0] | vm[1]) >> m0) == 0u) break;  // no kept column left in either row
+      uint4 xv[2][kMergeBatch];
+      float ls[2][kMergeBatch];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = 4 * i + crow;
-    const int rr = row0 + row;
-    if (rr < rows_total) {
-      const int e = div_g(rr, P.g, P.g_magic);
-      const size_t drow = (size_t)(ttok0 + e) * hp + (size_t)(hoff + rr - e * P.g);
-      *reinterpret_cast<uint4*>(odense + drow * kD + cchunk) =
-          *reinterpret_cast<const uint4*>(&tile_lds[row * kTileStride + cchunk]);
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int i = 0; i < kMergeBatch; ++i) {
+          const int m = m0 + i;
+          const bool on = m < P.topk && ((vm[x] >> m) & 1u);
+          const size_t pr = on ? (size_t)(sp[x][m] - pos0) * P.g + hh[x] : (size_t)0;
+          xv[x][i] = on ? *reinterpret_cast<const uint4*>(opart + pr * kD + 8 * sub) : make_uint4(0, 0, 0, 0);
+          ls[x][i] = on ? lse_part[pr] : -INFINITY;
+        }
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        float Mb = M[x];
+#pragma unroll
+        for (int i = 0; i < kMergeBatch; ++i) Mb = fmaxf(Mb, ls[x][i]);
+        if (Mb == -INFINITY) continue;  // no kept column in this batch or before it
+        const float rescale = __expf(M[x] - Mb);  // 0 on the first non-empty batch
+        Ls[x] *= rescale;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[x][c] *= rescale;
+        M[x] = Mb;
+#pragma unroll
+        for (int i = 0; i < kMergeBatch; ++i) {
+          const float w = __expf(ls[x][i] - Mb);  // exp(-inf) = 0 for columns that are off
+          Ls[x] += w;
+          acc[x][0] += w * bf16_lo(xv[x][i].x); acc[x][1] += w * bf16_hi(xv[x][i].x);
+          acc[x][2] += w * bf16_lo(xv[x][i].y); acc[x][3] += w * bf16_hi(xv[x][i].y);
+          acc[x][4] += w * bf16_lo(xv[x][i].z); acc[x][5] += w * bf16_hi(xv[x][i].z);
+          acc[x][6] += w * bf16_lo(xv[x][i].w); acc[x][7] += w * bf16_hi(xv[x][i].w);
+        }
+      }
     }
-  }
-  if (valid && qh == 0) {
-    const float mcf = (m_run == -INFINITY) ? 0.f : m_run * c2;
-    lse_dense[(size_t)t * hp + (size_t)(hoff + r - e_row * P.g)] =
-        l_run > 0.f ? (mcf + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f : -INFINITY;
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      if (!ok[x]) continue;
+      bf16_t* orow = O + grow[x] * kD + 8 * sub;
+      if (vm_all[x] == 0u) {  // nothing visible: O = 0, LSE = -inf, and the gated sum is what the other branches gave
+        *reinterpret_cast<uint4*>(orow) = make_uint4(0, 0, 0, 0);
+        if (sub == 0) LSE[grow[x]] = -INFINITY;
+        if (gate != nullptr)
+          *reinterpret_cast<uint4*>(Oout + grow[x] * kD + 8 * sub) =
+              Oacc != nullptr ? *reinterpret_cast<const uint4*>(Oacc + grow[x] * kD + 8 * sub) : make_uint4(0, 0, 0, 0);
+        continue;
+      }
+      const float inv = 1.f / Ls[x];
+      uint4 o;
+      o.x = pack_bf16x2(acc[x][0] * inv, acc[x][1] * inv);
+      o.y = pack_bf16x2(acc[x][2] * inv, acc[x][3] * inv);
+      o.z = pack_bf16x2(acc[x][4] * inv, acc[x][5] * inv);
+      o.w = pack_bf16x2(acc[x][6] * inv, acc[x][7] * inv);
+      *reinterpret_cast<uint4*>(orow) = o;
+      if (sub == 0) LSE[grow[x]] = M[x] + __logf(Ls[x]);
+      if (gate != nullptr) {
+        // Eq. (2): O_out = O_acc + gate * O, from the fp32 result (Oout may be the buffer Oacc points to: every lane
+        // reads its own 16 bytes before it writes them)
+        const float tau = gate[grow[x]] * inv;
+        uint4 a = make_uint4(0, 0, 0, 0);
+        if (Oacc != nullptr) a = *reinterpret_cast<const uint4*>(Oacc + grow[x] * kD + 8 * sub);
+        o.x = pack_bf16x2(bf16_lo(a.x) + tau * acc[x][0], bf16_hi(a.x) + tau * acc[x][1]);
+        o.y = pack_bf16x2(bf16_lo(a.y) + tau * acc[x][2], bf16_hi(a.y) + tau * acc[x][3]);
+        o.z = pack_bf16x2(bf16_lo(a.z) + tau * acc[x][4], bf16_hi(a.z) + tau * acc[x][5]);
+        o.w = pack_bf16x2(bf16_lo(a.w) + tau * acc[x][6], bf16_hi(a.w) + tau * acc[x][7]);
+        *reinterpret_cast<uint4*>(Oout + grow[x] * kD + 8 * sub) = o;
+      }
+    }
   }
 }
 
@@ -715,9 +865,8 @@ k_fwd_dense(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
 // result hide the gather latency better than long batches did (16 -> 4: 1.87 -> 1.80 ms at the headline shape).
 __global__ void __launch_bounds__(256)
 k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict__ lse_part,
-            const uint32_t* __restrict__ vmask, const uint32_t* __restrict__ dmask,
-            const int32_t* __restrict__ slotpos, const int32_t* __restrict__ off,
-            const bf16_t* __restrict__ odense, const float* __restrict__ lse_dense, bf16_t* __restrict__ O,
+            const uint32_t* __restrict__ vmask, const int32_t* __restrict__ slotpos,
+            const int32_t* __restrict__ off, bf16_t* __restrict__ O,
             float* __restrict__ LSE, const float* __restrict__ gate, const bf16_t* Oacc, bf16_t* Oout) {
   // rows of the pass: (token, head of the KV heads [j0, j0 + nj))
   const int hp = P.nj * P.g;
@@ -729,12 +878,9 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
   const int64_t row = (int64_t)t * P.hq + h;
   const int j = h / P.g, hh = h - j * P.g;
   const int pos0 = off[P.j0 * P.b_cap];
-  const uint32_t vm_all = vmask[(size_t)t * P.hkv + j];
-  // columns the dense path took over have no partial row of their own: they arrive as one row per (token, head)
-  const uint32_t dm = P.dense ? dmask[(size_t)t * P.hkv + j] : 0u;
-  const uint32_t vm = vm_all & ~dm;
+  const uint32_t vm = vmask[(size_t)t * P.hkv + j];
   bf16_t* orow = O + row * kD + 8 * sub;
-  if (vm_all == 0u) {
+  if (vm == 0u) {
     *reinterpret_cast<uint4*>(orow) = make_uint4(0, 0, 0, 0);
     if (sub == 0) LSE[row] = -INFINITY;
     if (gate != nullptr)  // nothing to add: the gated sum is what the other branches gave
@@ -745,17 +891,6 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
   const int32_t* sp = slotpos + ((size_t)t * P.hkv + j) * P.topk;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   float M = -INFINITY, Ls = 0.f;
-  if (dm != 0u) {  // the dense path's row starts the sum (its log-sum-exp is -inf if the token keeps none of the blocks)
-    const size_t drow = (size_t)t * hp + (size_t)(h - P.j0 * P.g);
-    const uint4 x = *reinterpret_cast<const uint4*>(odense + drow * kD + 8 * sub);
-    const float ls = lse_dense[drow];
-    if (ls > -INFINITY) {
-      M = ls;
-      Ls = 1.f;
-      acc[0] = bf16_lo(x.x); acc[1] = bf16_hi(x.x); acc[2] = bf16_lo(x.y); acc[3] = bf16_hi(x.y);
-      acc[4] = bf16_lo(x.z); acc[5] = bf16_hi(x.z); acc[6] = bf16_lo(x.w); acc[7] = bf16_hi(x.w);
-    }
-  }
   for (int m0 = 0; m0 < P.topk; m0 += kSlotBatch) {
     size_t pr[kSlotBatch];
     uint4 x[kSlotBatch];
@@ -815,12 +950,12 @@ k_fwd_merge(Problem P, const bf16_t* __restrict__ opart, const float* __restrict
 }
 
 hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pass, const void* Q, const void* K,
-                      const void* V, const void* index_ws, void* opart, float* lse_part, void* odense,
-                      float* lse_dense, void* O, float* LSE, const GateArgs& G, hipStream_t st) {
+                      const void* V, const void* index_ws, void* opart, float* lse_part, void* O, float* LSE,
+                      const GateArgs& G, hipStream_t st) {
   IndexPtrs p = index_ptrs(L, const_cast<void*>(index_ws));
   if (P0.dense) {
     static std::atomic<uint64_t> ready_dense;
-    hipError_t e = allow_dynamic_lds((const void*)k_fwd_dense, kDnBytes, ready_dense);
+    hipError_t e = allow_dynamic_lds((const void*)k_fwd_dense_merge, kDnBytes, ready_dense);
     if (e != hipSuccess) return e;
   }
   {
@@ -849,18 +984,21 @@ hipError_t launch_fwd(const Problem& P0, const IndexLayout& L, int heads_per_pas
                          (bf16_t*)opart, lse_part);
     }
     if (P.dense) {
+      // dense pairs and the reduction step in one kernel (every row of the pass's heads)
       const int chunks = (kTileTokens * P.g + 127) / 128;
-      ProfScope ps(KID_FWD_DENSE, st);
       const int per = (P.nj * P.t_cap * chunks + 7) / 8;
-      hipLaunchKernelGGL(k_fwd_dense, dim3((unsigned)(8 * per)), dim3(256), kDnBytes, st, P,
-                         (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, p.tile_tok0, p.tile_len, p.d_cnt,
-                         p.d_piece, p.d_mask, (bf16_t*)odense, lse_dense);
+      ProfScope ps(KID_FWD_DENSE, st);
+      hipLaunchKernelGGL(k_fwd_dense_merge, dim3((unsigned)(8 * per)), dim3(256), kDnBytes, st, P, (const bf16_t*)Q,
+                         (const bf16_t*)K, (const bf16_t*)V, p.tile_tok0, p.tile_len, p.d_cnt, p.d_piece, p.d_mask,
+                         (const bf16_t*)opart, (const float*)lse_part, p.vmask, p.dmask, p.slotpos, p.off, (bf16_t*)O,
+                         LSE, G.gate, (const bf16_t*)G.o_acc, (bf16_t*)G.o_out);
+    } else {
+      const int64_t rows = (int64_t)P.T * P.nj * P.g;
+      ProfScope ps(KID_FWD_MERGE, st);
+      hipLaunchKernelGGL(k_fwd_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P, (const bf16_t*)opart,
+                         (const float*)lse_part, p.vmask, p.slotpos, p.off, (bf16_t*)O, LSE, G.gate,
+                         (const bf16_t*)G.o_acc, (bf16_t*)G.o_out);
     }
-    const int64_t rows = (int64_t)P.T * P.nj * P.g;
-    ProfScope ps(KID_FWD_MERGE, st);
-    hipLaunchKernelGGL(k_fwd_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, P, (const bf16_t*)opart,
-                       (const float*)lse_part, p.vmask, p.dmask, p.slotpos, p.off, (const bf16_t*)odense,
-                       (const float*)lse_dense, (bf16_t*)O, LSE, G.gate, (const bf16_t*)G.o_acc, (bf16_t*)G.o_out);
   }
   return hipGetLastError();
 }

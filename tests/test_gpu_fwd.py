@@ -52,7 +52,7 @@ def test_profile_records_only_selected_kernels():
     nsa.profile_select(None)
     c.forward()
     every = {n for n, v in nsa.profile_collect().items() if v[1]}
-    assert {"fwd_main", "fwd_merge", "index_scatter", "index_scan"} <= every
+    assert {"fwd_main", "fwd_dense", "index_dense", "index_scatter", "index_scan"} <= every   # fwd_dense: dense pairs + merge
     nsa.profile_enable(0)
     c.forward()
     assert not any(v[1] for v in nsa.profile_collect().values())
