@@ -196,6 +196,8 @@ def main():
                     help="list entries per work unit (0: the library's choice; a power of two in 256..2048)")
     ap.add_argument("--ws-cap-gb", type=float, default=0.0,
                     help="cap each workspace at this many GB: the library then reuses it over groups of KV heads")
+    ap.add_argument("--dense", choices=["auto", "on", "off"], default="auto",
+                    help="routing of the forward (shape.dense): the library's choice, or the dense route forced on / off")
     ap.add_argument("--no-select", action="store_true",
                     help="skip the separate measurement of the selection step (block scores -> idx) in front of the path")
     ap.add_argument("--extras", action="store_true",
@@ -232,7 +234,7 @@ def main():
     idx = torch.from_numpy(w.idx).cuda()
     cu = torch.from_numpy(w.cu_seqlens).cuda()
     attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, block=w.block, unit=args.unit,
-                            ws_cap_bytes=int(args.ws_cap_gb * 1e9) if args.ws_cap_gb > 0 else None)
+                            dense={'auto': None, 'on': True, 'off': False}[args.dense], ws_cap_bytes=int(args.ws_cap_gb * 1e9) if args.ws_cap_gb > 0 else None)
     o = torch.empty_like(q)
     lse = torch.empty(T, w.hq, dtype=torch.float32, device="cuda")
     grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))

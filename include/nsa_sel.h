@@ -39,7 +39,7 @@ extern "C" {
 #define NSA_SEL_OK            0
 #define NSA_SEL_EINVAL       -1   /* null/misaligned pointer, g not in [1,8], hq % hkv != 0, nseq < 1, negative size,
                                      window < 0 or window without causal, unit not 0 or a power of two in range,
-                                     dense not 0 or -1 */
+                                     dense outside [-1, 1] */
 #define NSA_SEL_EUNSUPPORTED -2   /* d != 128, block not 64 or 128, topk outside [1,32], too many tokens      */
 #define NSA_SEL_EWORKSPACE   -3   /* index workspace too small, or ws below nsa_sel_workspace_bytes_min       */
 #define NSA_SEL_EHIP         -4   /* the HIP runtime refused a launch or attribute                            */
@@ -68,12 +68,13 @@ typedef struct {
                              unit; the knob that corresponds to the paper's query batch size B_Q, App. E, which
                              it picks by online profiling): a power of two in [256, 2048].  It changes speed and
                              the workspace sizes, not results (dK/dV only in their fp32 summation order)      */
-  int32_t dense;          /* 0: the forward routes (query tile of 64 tokens, KV block) pairs that at least half of
-                             the tile's tokens keep - found by counting, e.g. the attention-sink block (App. E) and
-                             the tokens' own and neighbouring blocks - through a query-tile-outer kernel, fused
+  int32_t dense;          /* Routing of the forward.  1: (query tile of 64 tokens, KV block) pairs that at least half
+                             of the tile's tokens keep - found by counting, e.g. the attention-sink block (App. E) and
+                             the tokens' own and neighbouring blocks - go through a query-tile-outer kernel, fused
                              with the reduction step, that needs no gather and no partial row.  -1: every pair
-                             takes the gather route.  Same results up to rounding; the index workspace built
-                             for one setting must not be used with the other                                   */
+                             takes the gather route.  0: the library picks (the dense route when hq / hkv >= 2 or a
+                             window is set).  Same results up to rounding; an index workspace built for one
+                             routing must not be used with the other                                           */
 } nsa_sel_shape;
 
 /* Bytes of the three caller-owned workspaces for `shape` (any of the outputs may be NULL).

@@ -290,11 +290,12 @@ class SelAttention:
     """Owns the workspaces for one shape and calls the library (buffers are torch uint8 tensors)."""
 
     def __init__(self, total_tokens, hq, hkv, topk, *, nseq=1, causal=True, scale=0.0, device="cuda:0", bwd=True,
-                 block=64, ws_cap_bytes=None, window=0, unit=0, dense=True):
+                 block=64, ws_cap_bytes=None, window=0, unit=0, dense=None):
         """ws_cap_bytes caps each of the forward / backward workspaces (never below the library's minimum);
-        the library then works through the KV heads in as many passes as needed."""
+        the library then works through the KV heads in as many passes as needed.  dense: None lets the library
+        route the forward (shape.dense = 0), True / False force the dense route on / off."""
         self.shape = Shape(total_tokens, nseq, hq, hkv, 128, block, topk, int(causal), float(scale), 0, int(window),
-                           int(unit), 0 if dense else -1)
+                           int(unit), 0 if dense is None else (1 if dense else -1))
         fb, bb, ib = workspace_bytes(self.shape)
         if ws_cap_bytes is not None:
             fmin, bmin = workspace_bytes_min(self.shape)

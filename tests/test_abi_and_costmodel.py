@@ -46,7 +46,7 @@ def test_shape_validation_happens_on_the_host():
         (nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 0, 0.0, 0, 512), -1),  # window without causal
         (nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 1, 0.0, 0, 0, 300), -1),   # unit not a power of two
         (nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 1, 0.0, 0, 0, 4096), -1),  # unit too large
-        (nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 1, 0.0, 0, 0, 0, 2), -1),     # dense neither 0 nor -1
+        (nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 1, 0.0, 0, 0, 0, 2), -1),     # dense outside [-1, 1]
     ]
     sz = ctypes.c_size_t()
     for shape, code in bad:

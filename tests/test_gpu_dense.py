@@ -116,3 +116,16 @@ def test_dense_route_with_capped_workspace_is_bit_identical():
                               block=w.block, ws_cap_bytes=1, bwd=False)
     o2, lse2 = c.forward()
     assert torch.equal(o, o2) and torch.equal(lse, lse2)
+
+
+def test_default_routing_policy():
+    """shape.dense = 0: the dense route where it pays (g >= 2, or a window), the gather route at g = 1."""
+    print("case dense policy", flush=True)
+    import paper_2508_18224_amd as nsa
+    for name, window, expect in (("g4", 0, True), ("g1_varlen", 0, False), ("g1_varlen", 100, True)):
+        w = wl.realise(wl.small(name))
+        c = Case(w, bwd=False, window=window)
+        c.attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal,
+                                  block=w.block, window=window, bwd=False)        # dense=None: the library picks
+        c.forward()
+        assert bool(c.attn.dense_entries().any()) == expect, (name, window)
