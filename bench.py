@@ -169,6 +169,31 @@ def bench_extras(nsa, wl, w, q, k, v, do, cu, steps):
         res["loop_order_forward"] = {"kv_outer_ms": a["step_with_events"], "query_outer_ms": b["step_with_events"],
                                      "ratio": b["step_with_events"] / a["step_with_events"],
                                      "note": "kv_outer includes index inversion, main and merge"}
+        # What a query-outer kernel that shares blocks between the tokens of a 64-token query tile could reach at
+        # best: only the forced blocks (sink, own, recent) are shared by a tile's tokens, and for those the
+        # query-tile-outer order is this library's dense route; the other picks differ from token to token and cost
+        # a K/V block load per (token, block) in any query-outer cut.  So: the query-outer kernel on the free picks
+        # alone plus the dense route on the forced blocks alone.
+        tok = np.arange(T)
+        seq = np.searchsorted(w.cu_seqlens, tok, side="right") - 1
+        cur = ((tok - w.cu_seqlens[seq]) // w.block)[:, None, None]
+        forced = np.zeros(w.idx.shape, dtype=bool)
+        if w.sink:
+            forced |= w.idx == 0
+        for r in range(w.recent):
+            forced |= w.idx == cur - r
+        idx_free = torch.from_numpy(np.where(forced, -1, w.idx).astype(np.int32)).cuda()
+        idx_forced = torch.from_numpy(np.where(forced, w.idx, -1).astype(np.int32)).cuda()
+        dense_attn = nsa.SelAttention(T, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal, block=w.block,
+                                      bwd=False, dense=True)
+        c = per_kernel(lambda: attn.forward_query_outer(q, k, v, idx_free, cu))
+        d = per_kernel(lambda: dense_attn.forward(q, k, v, idx_forced, cu))
+        res["loop_order_forward"].update({
+            "query_outer_free_picks_only_ms": c["step_with_events"],
+            "query_tile_outer_forced_blocks_only_ms": d["step_with_events"],
+            "query_outer_with_sharing_estimate_ms": c["step_with_events"] + d["step_with_events"],
+            "forced_share_of_pairs": float(forced.sum()) / float((w.idx >= 0).sum())})
+        del idx_free, idx_forced, dense_attn
     del attn, idx
     if w.causal:
         for window, blk in ((512, 64), (512, 128)):

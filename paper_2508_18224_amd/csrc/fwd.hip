@@ -550,7 +550,8 @@ k_fwd_dense_merge(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restr
   const int2 piece0 = d_piece[slot * kDenseMax];
   const int rows_total = tlen * P.g;
   if (chunk * 128 >= rows_total) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, qh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, qh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: what derives from it stays out of the VGPRs
   const int crow = lane >> 4, cchunk = (lane & 15) * 8;
   bf16_t* tile_lds = reinterpret_cast<bf16_t*>(smem + kDnTiles) + wave * 32 * kTileStride;
   float* lse_lds = reinterpret_cast<float*>(smem + kDnLse) + wave * 32;
@@ -748,7 +749,10 @@ k_fwd_dense_merge(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restr
 
   // ------------------------------------------------------------------------------------------------ phase 2
   if (nd == 0) park_meta();
-  const int sub = lane & 15;
+  // lane-derived indices of this phase, recomputed here so that they do not occupy registers during phase 1
+  int lane_b = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane_b));
+  const int sub = lane_b & 15, crow_b = lane_b >> 4;
   const int pos0 = off[P.j0 * P.b_cap];  // first list position of the pass: partial rows are relative to it
   for (int pass = 0; pass < 4; ++pass) {
     // two rows per lane group: wave rows 4 pass + crow and 16 more
@@ -760,7 +764,7 @@ k_fwd_dense_merge(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restr
     float acc[2][8], M[2], Ls[2];
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
-      const int wrow = 4 * pass + crow + 16 * x;
+      const int wrow = 4 * pass + crow_b + 16 * x;
       const int rr = row0 + wrow;
       ok[x] = rr < rows_total;
       const int rc = min(rr, rows_total - 1);
