@@ -73,8 +73,9 @@ typedef struct {
                              the tokens' own and neighbouring blocks - go through a query-tile-outer kernel, fused
                              with the reduction step, that needs no gather and no partial row.  -1: every pair
                              takes the gather route.  0: the library picks (the dense route when hq / hkv >= 2 or a
-                             window is set).  Same results up to rounding; an index workspace built for one
-                             routing must not be used with the other                                           */
+                             window is set, and total_tokens * hkv * topk >= 2^18).  Same results up to
+                             rounding; an index workspace built for one routing must not be used with the
+                             other                                                                             */
 } nsa_sel_shape;
 
 /* Bytes of the three caller-owned workspaces for `shape` (any of the outputs may be NULL).

@@ -52,7 +52,8 @@ static IndexLayout make_layout(const nsa_sel_shape* s) {
   // dense route: on request, or by default where it pays: with g = 1 a (tile, kv head) has only 64 rows to share a
   // K / V piece, which costs more than the gather route saves (measured: +4 % per step at g = 1, -1 % .. -8 % at
   // g = 4 .. 8), unless the call is the sliding-window branch, where every pair is dense
-  L.dense = s->dense == 1 || (s->dense == 0 && (s->hq / s->hkv >= 2 || s->window > 0)) ? 1 : 0;
+  // (and not for inputs so small that the step is a few launch latencies: below 2^18 (token, kv head, column) triples)
+  L.dense = s->dense == 1 || (s->dense == 0 && L.p_max >= (1 << 18) && (s->hq / s->hkv >= 2 || s->window > 0)) ? 1 : 0;
   L.t_cap = s->total_tokens / kTileTokens + s->nseq;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };

@@ -122,8 +122,10 @@ def test_default_routing_policy():
     """shape.dense = 0: the dense route where it pays (g >= 2, or a window), the gather route at g = 1."""
     print("case dense policy", flush=True)
     import paper_2508_18224_amd as nsa
-    for name, window, expect in (("g4", 0, True), ("g1_varlen", 0, False), ("g1_varlen", 100, True)):
-        w = wl.realise(wl.small(name))
+    big = wl.Workload("policy_g2", [9000], hq=4, hkv=2, topk=16, sink=True, seed=41)      # 288K triples
+    big1 = wl.Workload("policy_g1", [9000, 300], hq=2, hkv=2, topk=16, seed=42)
+    for name, window, expect in ((big, 0, True), (big1, 0, False), (big1, 100, True), ("g4", 0, False)):
+        w = wl.realise(wl.small(name) if isinstance(name, str) else name)
         c = Case(w, bwd=False, window=window)
         c.attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal,
                                   block=w.block, window=window, bwd=False)        # dense=None: the library picks
