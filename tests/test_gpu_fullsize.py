@@ -117,8 +117,9 @@ def _check_blocks(ref, w, blocks, dk, dv):
     print(f"  {len(blocks)} sampled kv blocks ok", flush=True)
 
 
-def _run_case(name, n_tokens=256, n_blocks=8, extra_blocks=(), window=0, closed_forms=True):
-    print("full-size case", name, "window", window, flush=True)
+def _run_case(name, n_tokens=256, n_blocks=8, extra_blocks=(), window=0, closed_forms=True, dense=None):
+    """dense=None: the forward routing the library picks for the shape, i.e. what bench.py times."""
+    print("full-size case", name, "window", window, "dense", dense, flush=True)
     w0 = wl.named(name)
     tokens = _sample_tokens(w0.total_tokens, n_tokens)
     blocks = _sample_blocks(w0, n_blocks, extra_blocks)
@@ -128,10 +129,10 @@ def _run_case(name, n_tokens=256, n_blocks=8, extra_blocks=(), window=0, closed_
         w.idx = wl.window_block_indices(w.seqlens, w.hkv, window, w.block)
         w.topk = w.idx.shape[2]
     T, g = w.total_tokens, w.g
-    c = Case(w, window=window)
+    c = Case(w, window=window, dense=dense)
     o, lse = c.forward()
     dq, dk, dv = c.backward(o, lse)
-    print("  gpu done", flush=True)
+    print("  gpu done; dense share of the pairs:", round(float(c.attn.dense_entries().mean()), 3), flush=True)
     if extra_blocks:                                         # these lists must really be split over work units
         cnt, _, _, _, _, _ = c.attn.index_arrays()
         for (j, s, x) in extra_blocks:
@@ -201,6 +202,16 @@ def test_ultra_long_256k_tokens_64_heads():
     _run_case("grid_g8_b64_n256_h64", n_tokens=64, n_blocks=4)
 
 
+def test_headline_with_the_gather_route_only():
+    """The routing the library does not pick at the headline shape (shape.dense = -1), forward rows only."""
+    _run_case("headline", n_blocks=1, closed_forms=False, dense=False)
+
+
+def test_varlen_g1_with_the_dense_route_forced():
+    """g = 1 runs the gather route by default; the dense route at that shape (shape.dense = 1)."""
+    _run_case("varlen_g1", n_blocks=1, closed_forms=False, dense=True)
+
+
 def test_headline_gated_entry_points():
     """nsa_sel_fwd_gated / nsa_sel_bwd_gated at the headline shape: O_out, dQ, dgate on sampled rows, dK/dV on sampled
     blocks (the oracle's gated backward is its backward on gate * dO_out)."""
@@ -212,7 +223,7 @@ def test_headline_gated_entry_points():
     oracle = OracleRun(name, tokens, blocks, gated=True)
     w = wl.realise(wl.named(name))
     T = w.total_tokens
-    c = Case(w)
+    c = Case(w, dense=None)
     gate = wl.draw_gates(w.seed, T, w.hq)
     acc_bits = wl.draw_other_branches(w.seed, T, w.hq)
     gate_d, acc_d = torch.from_numpy(gate).cuda(), dev_bf16(acc_bits)
