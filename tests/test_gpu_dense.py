@@ -113,8 +113,9 @@ def test_dense_route_with_capped_workspace_is_bit_identical():
     c = Case(w, bwd=False)
     o, lse = c.forward()
     c.attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal,
-                              block=w.block, ws_cap_bytes=1, bwd=False)
+                              block=w.block, ws_cap_bytes=1, bwd=False, dense=True)
     o2, lse2 = c.forward()
+    assert c.attn.dense_entries().any()
     assert torch.equal(o, o2) and torch.equal(lse, lse2)
 
 

@@ -35,7 +35,7 @@ def test_capped_workspace_matches_single_pass(name, heads):
     assert fmin < ffull and bmin < bfull
     capped = Case(w)
     capped.attn = nsa.SelAttention(w.total_tokens, w.hq, w.hkv, w.topk, nseq=len(w.seqlens), causal=w.causal,
-                                   block=w.block, ws_cap_bytes=heads * max(fmin, bmin))
+                                   block=w.block, ws_cap_bytes=heads * max(fmin, bmin), dense=True)
     assert capped.attn.fwd_ws.numel() < ffull and capped.attn.bwd_ws.numel() < bfull
     # poison the reused buffers so that a stale read from an earlier pass cannot go unnoticed
     capped.attn.fwd_ws.fill_(0x7F)
