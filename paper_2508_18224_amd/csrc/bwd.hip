@@ -416,6 +416,15 @@ __device__ unsigned long long g_pipe_t[2][8];
 #else
 #define PT_STAMP(k)
 #endif
+// f(integral_constant<int, I>) for I = kBegin .. kEnd - 1, every index a compile-time constant
+template <int kBegin, int kEnd, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (kBegin < kEnd) {
+    f(std::integral_constant<int, kBegin>{});
+    static_for<kBegin + 1, kEnd>(f);
+  }
+}
+
 // What one workgroup of k_bwd_pipe128 works on.
 struct PipeUnit {
   int u, ubase, L, j, e0, pos0, ne, tok0, blen;
@@ -675,80 +684,90 @@ pipe_role(const Problem& P, const PipeUnit& U, unsigned char* smem, const int sw
           const bf16_t* dOs = reinterpret_cast<const bf16_t*>(smem + PipeLds::DO0 + buf * PipeLds::QB);
           const bf16_t* Pt = reinterpret_cast<const bf16_t*>(smem + PipeLds::Pt0 + buf * PipeLds::PB);
           const bf16_t* dSt = reinterpret_cast<const bf16_t*>(smem + PipeLds::DSt0 + buf * PipeLds::PB);
-          const bf16_t* parow = Pt + (32 * sw + col) * kPStride + 8 * qh;
+          // Three products of 16 MFMAs each, in this order:
+          //   ops  0..15  dV_i += P^T dO          (op = 4 qs + cb: rows 16 qs.., channels 32 cb..)
+          //   ops 16..31  dQ^T  = K_i^T dS^T      (op = 16 + 2 sp + rb: keys 16 sp.., rows 32 rb..)
+          //   ops 32..47  dK_i += dS^T Q          (as the first, with Q)
+          // Every op's "lane = column" operand is a pair of transposing LDS reads.  As in the S-waves the issue order
+          // is fixed by hand: the operands run through a ring of kRing registers, op i issues its MFMA and refills its
+          // slot with the operand of op i + kRing, across the product boundaries, so only the first kRing reads of a
+          // tile are waited for at full LDS latency.  The dQ slices are stored between the second and third product.
+          constexpr int kRing = 4;
+          const bf16_t* parow = Pt + (32 * sw + col) * kPStride + 8 * qh;   // rows 32 sw.. of P^T: read by this wave only
           const bf16_t* sarow = dSt + (32 * sw + col) * kPStride + 8 * qh;
-          {  // dV_i += P^T dO for keys 32 sw.., all channels.  Rows 32 sw.. of the P^T tile are read by this wave only.
-            const bf16_t* do_tr = dOs + tr_lane;
+          const bf16_t* do_tr = dOs + tr_lane;
+          const bf16_t* q_tr = Qs + tr_lane;
+          const bf16_t* ds_tr = dSt + tr_lane_p;
+          auto operand = [&](auto opc) __attribute__((always_inline)) {
+            constexpr int op = decltype(opc)::value;
+            const bf16_t* p0;
+            constexpr int step = (op >= 16 && op < 32) ? 4 * kPStride : 4 * kRowStride;
+            if constexpr (op < 16)
+              p0 = do_tr + (16 * (op >> 2) * kRowStride + 32 * (op & 3));
+            else if constexpr (op < 32)
+              p0 = ds_tr + (16 * ((op - 16) >> 1) * kPStride + 32 * (op & 1));
+            else
+              p0 = q_tr + (16 * ((op - 32) >> 2) * kRowStride + 32 * (op & 3));
+            const bf16x4 lo4 = lds_read_tr(p0);
+            const bf16x4 hi4 = lds_read_tr(p0 + step);
+            return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+          };
+          bf16x8 ring[kRing], af[4];  // af: the "lane = row of the result" operand of the first / third product
+          f32x16 dqacc[2];
 #pragma unroll
-            for (int qs = 0; qs < 4; ++qs) {
-              const bf16x8 pa = *reinterpret_cast<const bf16x8*>(parow + 16 * qs);
+          for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-              for (int cb = 0; cb < 4; ++cb) {
-                const bf16x4 d0 = lds_read_tr(do_tr + (16 * qs * kRowStride + 32 * cb));
-                const bf16x4 d1 = lds_read_tr(do_tr + ((16 * qs + 4) * kRowStride + 32 * cb));
-                const bf16x8 dob = __builtin_shufflevector(d0, d1, 0, 1, 2, 3, 4, 5, 6, 7);
-                dvacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, dob, dvacc[cb], 0, 0, 0);
+            for (int v = 0; v < 16; ++v) dqacc[rb][v] = 0.f;
+#pragma unroll
+          for (int qs = 0; qs < 4; ++qs) af[qs] = *reinterpret_cast<const bf16x8*>(parow + 16 * qs);
+          static_for<0, kRing>([&](auto opc) { ring[decltype(opc)::value] = operand(opc); });
+          __builtin_amdgcn_sched_barrier(0);
+          static_for<0, 48>([&](auto opc) __attribute__((always_inline)) {
+            constexpr int op = decltype(opc)::value;
+            if constexpr (op < 16)
+              dvacc[op & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[op >> 2], ring[op % kRing], dvacc[op & 3], 0, 0, 0);
+            else if constexpr (op < 32)
+              dqacc[op & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[(op - 16) >> 1], ring[op % kRing],
+                                                                      dqacc[op & 1], 0, 0, 0);
+            else
+              dkacc[op & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[(op - 32) >> 2], ring[op % kRing],
+                                                                      dkacc[op & 3], 0, 0, 0);
+            if constexpr (op + kRing < 48) ring[op % kRing] = operand(std::integral_constant<int, op + kRing>{});
+            if constexpr (op >= 24 && op < 28)  // the first product is done with af: refill it for the third
+              af[op - 24] = *reinterpret_cast<const bf16x8*>(sarow + 16 * (op - 24));
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (op == 31) {
+              // this wave's 64-byte slice of the tile's dQ rows: accumulator layout (lane = row) -> rows 32 sw.. of
+              // the P^T tile, which this wave has finished reading and the S-waves rewrite only after the next
+              // barrier -> 16-byte row pieces
+              bf16_t* stg = reinterpret_cast<bf16_t*>(smem + PipeLds::Pt0 + buf * PipeLds::PB) + 32 * sw * kPStride;
+#pragma unroll
+              for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                  uint2 w;
+                  w.x = pack_bf16x2(dqacc[rb][4 * a + 0], dqacc[rb][4 * a + 1]);
+                  w.y = pack_bf16x2(dqacc[rb][4 * a + 2], dqacc[rb][4 * a + 3]);
+                  *reinterpret_cast<uint2*>(&stg[(32 * rb + col) * kDqPitch + 8 * a + 4 * qh]) = w;
+                }
+              wave_sync_bwd();
+              const int tile0 = row_first + (it - 1) * kTile;
+              const size_t prow0 = (size_t)(U.e0 - U.pos0) * P.g + (size_t)tile0;
+              int ln = lane;
+              asm volatile("" : "+v"(ln));  // keeps the row addresses from being precomputed and held (register budget)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const int row = 16 * i + (ln >> 2), piece = (ln & 3) * 8;
+                if (tile0 + row < rows_end) {
+                  const uint2 lo2 = *reinterpret_cast<const uint2*>(&stg[row * kDqPitch + piece]);
+                  const uint2 hi2 = *reinterpret_cast<const uint2*>(&stg[row * kDqPitch + piece + 4]);
+                  store_streaming(dqpart + (prow0 + row) * kD + 32 * sw + piece,
+                                  make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
+                }
               }
+              __builtin_amdgcn_sched_barrier(0);
             }
-          }
-          {  // dQ^T[channels 32 sw.., rows 32 rb..] = K_i^T dS^T over the 128 keys, stored at once: the stores overlap
-             // the last product
-            f32x16 dqacc[2];
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) dqacc[rb][v] = 0.f;
-            const bf16_t* ds_tr = dSt + tr_lane_p;
-#pragma unroll
-            for (int sp = 0; sp < 8; ++sp)
-#pragma unroll
-              for (int rb = 0; rb < 2; ++rb) {
-                const bf16x4 b0 = lds_read_tr(ds_tr + (16 * sp * kPStride + 32 * rb));
-                const bf16x4 b1 = lds_read_tr(ds_tr + ((16 * sp + 4) * kPStride + 32 * rb));
-                const bf16x8 dsb = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
-                dqacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sp], dsb, dqacc[rb], 0, 0, 0);
-              }
-            // this wave's 64-byte slice of the tile's dQ rows: accumulator layout (lane = row) -> rows 32 sw.. of the
-            // P^T tile, which this wave has finished reading and the S-waves rewrite only after the next barrier ->
-            // 16-byte row pieces
-            bf16_t* stg = reinterpret_cast<bf16_t*>(smem + PipeLds::Pt0 + buf * PipeLds::PB) + 32 * sw * kPStride;
-            wave_sync_bwd();  // the dV product's reads of these rows are complete
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-              for (int a = 0; a < 4; ++a) {
-                uint2 w;
-                w.x = pack_bf16x2(dqacc[rb][4 * a + 0], dqacc[rb][4 * a + 1]);
-                w.y = pack_bf16x2(dqacc[rb][4 * a + 2], dqacc[rb][4 * a + 3]);
-                *reinterpret_cast<uint2*>(&stg[(32 * rb + col) * kDqPitch + 8 * a + 4 * qh]) = w;
-              }
-            wave_sync_bwd();
-            const int tile0 = row_first + (it - 1) * kTile;
-            const size_t prow0 = (size_t)(U.e0 - U.pos0) * P.g + (size_t)tile0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const int row = 16 * i + (lane >> 2), piece = (lane & 3) * 8;
-              if (tile0 + row < rows_end) {
-                const uint2 lo2 = *reinterpret_cast<const uint2*>(&stg[row * kDqPitch + piece]);
-                const uint2 hi2 = *reinterpret_cast<const uint2*>(&stg[row * kDqPitch + piece + 4]);
-                store_streaming(dqpart + (prow0 + row) * kD + 32 * sw + piece, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
-              }
-            }
-          }
-          {  // dK_i += dS^T Q for keys 32 sw.., all channels
-            const bf16_t* q_tr = Qs + tr_lane;
-#pragma unroll
-            for (int qs = 0; qs < 4; ++qs) {
-              const bf16x8 sa = *reinterpret_cast<const bf16x8*>(sarow + 16 * qs);
-#pragma unroll
-              for (int cb = 0; cb < 4; ++cb) {
-                const bf16x4 q0 = lds_read_tr(q_tr + (16 * qs * kRowStride + 32 * cb));
-                const bf16x4 q1 = lds_read_tr(q_tr + ((16 * qs + 4) * kRowStride + 32 * cb));
-                const bf16x8 qb = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
-                dkacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, qb, dkacc[cb], 0, 0, 0);
-              }
-            }
-          }
+          });
         }
         PT_STAMP(1)
         __syncthreads();  // every wave is done with the tiles of `it - 1`
