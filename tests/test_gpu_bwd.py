@@ -37,6 +37,21 @@ def test_backward_long_list_splits_over_units_and_is_reproducible():
     assert torch.equal(dk, dk2) and torch.equal(dv, dv2) and torch.equal(dq, dq2)
 
 
+@pytest.mark.parametrize("seqlens,hq,hkv,topk", [
+    ([2500], 3, 1, 3),            # g = 3: a sink list of 2500 entries = one full unit (two 1024-entry segments) + a second unit
+    ([1300, 77, 129], 8, 1, 2),   # g = 8: 10400 rows in the sink list's unit, ragged last blocks, a 1-block sequence
+    ([640], 5, 5, 8),             # g = 1, more picks than blocks: short lists, tiles with a single row
+])
+def test_backward_128_key_blocks_long_lists(seqlens, hq, hkv, topk):
+    """(B_K, T) = (128, .): lists longer than the token ids one workgroup keeps resident, an odd and an even number of
+    64-row tiles per segment, group sizes that do not divide the tile, and ragged last blocks."""
+    print("case b128 long lists", seqlens, hq, hkv, topk, flush=True)
+    w = wl.realise(wl.Workload("b128long", seqlens, hq=hq, hkv=hkv, topk=topk, sink=True, block=128, seed=77 + hq))
+    c, (o, lse), (dq, dk, dv) = _run(w)
+    dq2, dk2, dv2 = c.backward(o, lse)
+    assert torch.equal(dk, dk2) and torch.equal(dv, dv2) and torch.equal(dq, dq2)
+
+
 def test_backward_adversarial_rows_and_scale():
     print("case adversarial", flush=True)
     w = wl.realise(wl.Workload("adv", [900, 300], hq=6, hkv=2, topk=10, seed=21))
