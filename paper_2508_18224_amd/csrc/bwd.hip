@@ -85,8 +85,8 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
 // With B_K = 64 (NKB = 2) a workgroup is four wavefronts (256 registers each) and half of a CU's LDS, so TWO
 // workgroups share a CU and run out of phase: one's barriers, gather waits, unit prologue and LDS-bound phases are
 // covered by the other's MFMA work (with one eight-wave workgroup per CU all waves sat in the same phase, and LDS,
-// MFMA and VALU time simply added up).  With B_K = 128 (NKB = 4) the fp32 dK/dV accumulators of the block need eight
-// waves' registers and there is one workgroup per CU.
+// MFMA and VALU time simply added up).  The kernel is written for any NKB, but only NKB = 2 is built: with B_K = 128 the
+// fp32 dK/dV accumulators leave room for one workgroup per CU only, and k_bwd_pipe128 below serves that case.
 // Per tile, wave w takes three roles in turn:
 //   rows/keys   (rb = w / NKB, kb = w % NKB): S^T, dP^T, P, dS for rows 32 rb.. and keys 32 kb..; K_i fragments from
 //               LDS, V_i fragments of the wave's 32 keys held in registers for the whole unit (only this role uses V_i)
@@ -109,7 +109,7 @@ struct BwdLds {
   static constexpr int Pt = DO + kTile * kRowStride * 2;
   static constexpr int DSt = Pt + kKeys * kPStride * 2;
   static constexpr int Ent = DSt + kKeys * kPStride * 2;
-  static constexpr int Bytes = Ent + kEntSeg * 4;  // 80896 (NKB = 2), 118784 (NKB = 4)
+  static constexpr int Bytes = Ent + kEntSeg * 4;  // 80896 (NKB = 2)
 };
 static_assert(2 * BwdLds<2>::Bytes <= 160 * 1024, "two workgroups of the 64-key backward must fit one CU's LDS");
 
