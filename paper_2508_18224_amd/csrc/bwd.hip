@@ -923,7 +923,9 @@ k_bwd_dkv_reduce(Problem P, const int32_t* __restrict__ nu_scan, const int32_t* 
 }
 
 #ifdef NSA_PIPE_TIMING
-extern "C" int nsa_dev_read_timers(unsigned long long* out, int reset) {
+// Measuring build only: copies the 2 x 8 counters (role x {phase 0..3 clocks, waves counted, unused}) to the host `out`
+// (synchronous, on the current device) and, with `reset`, zeroes them.  Returns 0, or -1 if a HIP call failed.
+extern "C" int nsa_sel_pipe_timing_read(unsigned long long* out, int reset) {
   if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_pipe_t), sizeof(unsigned long long) * 16) != hipSuccess) return -1;
   if (reset) {
     unsigned long long z[16] = {};
