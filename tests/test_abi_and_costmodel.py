@@ -23,6 +23,17 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
+def test_measuring_build_exports_the_same_boundary_plus_its_reader():
+    """libnsa_sel_timing.so (cycle stamps in the pipelined backward, see pipe_timing.py) is the same library otherwise."""
+    import ctypes
+    from paper_2508_18224_amd.build import LIB_TIMING
+    nsa, _ = _lib()
+    assert os.path.exists(LIB_TIMING), "python -m paper_2508_18224_amd.build builds it"
+    T = ctypes.CDLL(LIB_TIMING)
+    for name in nsa.SYMBOLS + ["nsa_sel_pipe_timing_read"]:
+        assert hasattr(T, name), name
+
+
 def test_shape_validation_happens_on_the_host():
     nsa, L = _lib()
     ok = nsa.Shape(4096, 1, 8, 2, 128, 64, 16, 1, 0.0, 0)
