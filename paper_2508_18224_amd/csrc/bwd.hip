@@ -109,7 +109,8 @@ struct BwdLds {
   static constexpr int Pt = DO + kTile * kRowStride * 2;
   static constexpr int DSt = Pt + kKeys * kPStride * 2;
   static constexpr int Ent = DSt + kKeys * kPStride * 2;
-  static constexpr int Bytes = Ent + kEntSeg * 4;  // 80896 (NKB = 2)
+  static constexpr int Rec = Ent + kEntSeg * 4;    // per row of the tile: LSE (log2 domain), delta * scale, visible keys
+  static constexpr int Bytes = Rec + 3 * kTile * 4;  // 81664 (NKB = 2)
 };
 static_assert(2 * BwdLds<2>::Bytes <= 160 * 1024, "two workgroups of the 64-key backward must fit one CU's LDS");
 
@@ -237,10 +238,17 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
       int lim = P.causal ? min(blen, t - tok0 + 1) : blen;  // keys [0, lim) of the block are visible to this row
       if (!valid) lim = 0;
       // kWin: the kernel variant for a sliding window, whose rows also hide the keys before lo
-      const int lo = kWin ? t - P.window + 1 - tok0 : 0;
-      __syncthreads();  // Q / dO tile staged by all waves
+      const int lo = kWin ? min(max(t - P.window + 1 - tok0, 0), kKeys) : 0;
+      if (kb == 0 && qh == 0) {  // this row's record, for the lanes of the rows/keys role (which hold keys, not rows)
+        float* rec = reinterpret_cast<float*>(smem + Lds::Rec) + 32 * rb + col;
+        rec[0] = lse2;
+        rec[kTile] = dl * P.scale;
+        reinterpret_cast<uint32_t*>(rec)[2 * kTile] = (uint32_t)(lo | (max(lim - lo, 0) << 16));  // keys [lo, lo + span)
+      }
+      __syncthreads();  // Q / dO tile and the row records staged by all waves
 
-      {  // role rows/keys
+      {  // role rows/keys: S = Q K_i^T, dP = dO V_i^T for rows 32 rb.. x keys 32 kb..: lane = key, register v = row
+         // 8 (v >> 2) + 4 qh + (v & 3), so four consecutive rows of P^T / dS^T leave each lane as one 8-byte LDS store
         f32x16 sacc, dpacc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -255,19 +263,31 @@ k_bwd_tiled(Problem P, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ 
           const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
           const bf16x8 dof = *reinterpret_cast<const bf16x8*>(drow + 16 * s);
           const bf16x8 kfa = *reinterpret_cast<const bf16x8*>(krow + 16 * s);
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa, qf, sacc, 0, 0, 0);
-          dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], dof, dpacc, 0, 0, 0);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kfa, sacc, 0, 0, 0);
+          dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dof, vf[s], dpacc, 0, 0, 0);
         }
-        bf16_t* pdst = Pt + 32 * rb + col;
-        bf16_t* sdst = dSt + 32 * rb + col;
-        const float dls = dl * P.scale;
+        const float* rec = reinterpret_cast<const float*>(smem + Lds::Rec);
+        const int key = 32 * kb + col;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = 32 * kb + 8 * (v >> 2) + 4 * qh + (v & 3);
-          const float p = (key < lim && (!kWin || key >= lo)) ? __builtin_amdgcn_exp2f(fmaf(sacc[v], c2, -lse2)) : 0.f;
-          const float ds = p * fmaf(dpacc[v], P.scale, -dls);  // P (dP - delta) scale
-          pdst[key * kPStride] = (bf16_t)p;
-          sdst[key * kPStride] = (bf16_t)ds;
+        for (int a = 0; a < 4; ++a) {
+          const int r4 = 32 * rb + 8 * a + 4 * qh;
+          const f32x4 lse4 = *reinterpret_cast<const f32x4*>(rec + r4);
+          const f32x4 dls4 = *reinterpret_cast<const f32x4*>(rec + kTile + r4);
+          const u32x4 vis4 = *reinterpret_cast<const u32x4*>(rec + 2 * kTile + r4);
+          float p[4], ds[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const bool seen = (uint32_t)key - (vis4[c] & 0xffffu) < (vis4[c] >> 16);
+            p[c] = seen ? __builtin_amdgcn_exp2f(fmaf(sacc[4 * a + c], c2, -lse4[c])) : 0.f;
+            ds[c] = p[c] * fmaf(dpacc[4 * a + c], P.scale, -dls4[c]);  // P (dP - delta) scale
+          }
+          uint2 pw, sw2;
+          pw.x = pack_bf16x2(p[0], p[1]);
+          pw.y = pack_bf16x2(p[2], p[3]);
+          sw2.x = pack_bf16x2(ds[0], ds[1]);
+          sw2.y = pack_bf16x2(ds[2], ds[3]);
+          *reinterpret_cast<uint2*>(&Pt[key * kPStride + r4]) = pw;
+          *reinterpret_cast<uint2*>(&dSt[key * kPStride + r4]) = sw2;
         }
       }
       __syncthreads();  // P^T, dS^T complete
