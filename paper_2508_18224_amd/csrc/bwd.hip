@@ -8,7 +8,7 @@
 //   k_bwd_tiled<NKB>  the main kernel for B_K = 64 (NKB = B_K / 32 = 2).  One work unit = (kv head j, KV block i, up to
 //                     P.unit list entries): four wavefronts and half of a CU's LDS, so two workgroups share a CU and
 //                     cover each other's barriers and waits.  The waves share tiles of 64 gathered rows and take three
-//                     roles per tile (see the comment above the kernel): S^T = K_i Q^T, dP^T = V_i dO^T,
+//                     roles per tile (see the comment above the kernel): S = Q K_i^T, dP = dO V_i^T,
 //                     P = exp(S - LSE), dS = P (dP - delta) scale; then dV_i += P^T dO and dK_i += dS^T Q
 //                     (accumulators in registers for the whole unit) and dQ^T = K_i^T dS^T.  Operands are row-major
 //                     tiles in LDS; "lane = column" operands are LDS transpose reads.  Partial dQ rows go to the
@@ -88,8 +88,11 @@ k_bwd_delta(int64_t rows, const bf16_t* __restrict__ O, const bf16_t* __restrict
 // MFMA and VALU time simply added up).  The kernel is written for any NKB, but only NKB = 2 is built: with B_K = 128 the
 // fp32 dK/dV accumulators leave room for one workgroup per CU only, and k_bwd_pipe128 below serves that case.
 // Per tile, wave w takes three roles in turn:
-//   rows/keys   (rb = w / NKB, kb = w % NKB): S^T, dP^T, P, dS for rows 32 rb.. and keys 32 kb..; K_i fragments from
-//               LDS, V_i fragments of the wave's 32 keys held in registers for the whole unit (only this role uses V_i)
+//   rows/keys   (rb = w / NKB, kb = w % NKB): S = Q K_i^T, dP = dO V_i^T, P, dS for rows 32 rb.. and keys 32 kb..; K_i
+//               fragments from LDS, V_i fragments of the wave's 32 keys held in registers for the whole unit (only this
+//               role uses V_i).  The products are taken with lane = key, so that a lane holds four consecutive rows of
+//               P^T / dS^T per register quad (one 8-byte LDS store); the rows' statistics come from a record per row
+//               that the staging waves leave in LDS
 //   keys/chans  (kb2 = w / 2, hf = w % 2): dV_i, dK_i accumulators for keys 32 kb2.. and channels 64 hf.. (two
 //               32-channel blocks share every P^T / dS^T operand read)
 //   rows/chans  (rb = w / NKB, part = w % NKB): dQ^T for rows 32 rb.. and the 128 / NKB channels of `part`; the same
